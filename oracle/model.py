@@ -1,0 +1,144 @@
+"""The encoder and the three task heads, written out with the fp64 oracle operators.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).
+
+What is computed follows the paper's Sec. "Example implementation": a DINOv2-style
+ViT/14 encoder configured to output its final features plus three evenly spaced
+intermediate layers, read by a DPT-style depth head, a linear segmentation head and
+a detection head.  The paper prints no formulas, so every step is the standard
+definition of the named layer; choices the paper leaves open are stated where made.
+
+`spec` is any object with the attributes of `vpe_inputs.ModelSpec`; `w` is a dict of
+arrays named as in `vpe_inputs.backbone_layout` / `head_layout`.
+"""
+from __future__ import annotations
+
+from typing import Dict, List
+
+import numpy as np
+
+from . import ops
+
+MLP_SWIGLU = 1
+
+
+def tokens_from_image(spec, w, img) -> np.ndarray:
+    """x0 [N][D]: CLS + pos[0]; registers (no positional term); patch p + pos[1+p].
+
+    Patch embedding is the 14x14 stride-14 convolution; the positional table has
+    1+P rows (generated at the grid size, never interpolated); register tokens sit
+    between CLS and the patches and receive no positional embedding.
+    """
+    D, R = spec.dim, spec.registers
+    t = ops.patch_embed(img, w["patch_w"], w["patch_b"], 14)
+    pos = np.asarray(w["pos"], dtype=np.float64)
+    x = np.empty((spec.tokens, D))
+    x[0] = np.asarray(w["cls"], dtype=np.float64) + pos[0]
+    if R:
+        x[1:1 + R] = np.asarray(w["reg"], dtype=np.float64)
+    x[1 + R:] = t + pos[1:]
+    return x
+
+
+def block(spec, w, l: int, x: np.ndarray) -> np.ndarray:
+    """One pre-LN transformer block with LayerScale on both residual branches."""
+    p = f"blk{l}."
+    u = ops.layernorm(x, w[p + "ln1_g"], w[p + "ln1_b"], spec.ln_eps)
+    qkv = ops.linear(u, w[p + "qkv_w"], w[p + "qkv_b"])
+    a = ops.attention(qkv, spec.heads, spec.head_dim)
+    x = ops.scale_residual(x, ops.linear(a, w[p + "proj_w"], w[p + "proj_b"]), w[p + "ls1"])
+    u = ops.layernorm(x, w[p + "ln2_g"], w[p + "ln2_b"], spec.ln_eps)
+    hdn = ops.linear(u, w[p + "fc1_w"], w[p + "fc1_b"])
+    hdn = ops.swiglu(hdn) if spec.mlp_kind == MLP_SWIGLU else ops.gelu(hdn)
+    x = ops.scale_residual(x, ops.linear(hdn, w[p + "fc2_w"], w[p + "fc2_b"]), w[p + "ls2"])
+    return x
+
+
+def encode_image(spec, w, img, return_blocks: bool = False):
+    """Encoder forward for one image [3][H][W].
+
+    Returns the four feature maps F_0..F_3, each [N][D]: the shared final LayerNorm
+    applied to the residual stream after the blocks listed in spec.taps (1-based);
+    F_3 (after the last block) is "the final tokens".  With return_blocks also returns
+    the raw residual stream after every block (x0 first).
+    """
+    x = tokens_from_image(spec, w, img)
+    feats: List[np.ndarray] = []
+    stream = [x.copy()]
+    for l in range(spec.depth):
+        x = block(spec, w, l, x)
+        if return_blocks:
+            stream.append(x.copy())
+        if (l + 1) in spec.taps:
+            feats.append(ops.layernorm(x, w["norm_g"], w["norm_b"], spec.ln_eps))
+    assert len(feats) == 4 and spec.taps[3] == spec.depth
+    return (feats, stream) if return_blocks else feats
+
+
+def encode(spec, w, images) -> List[np.ndarray]:
+    """Batched encoder: images [B][3][H][W] -> four arrays [B][N][D]."""
+    per = [encode_image(spec, w, im) for im in images]
+    return [np.stack([per[b][k] for b in range(len(per))]) for k in range(4)]
+
+
+def _grid(spec, feat) -> np.ndarray:
+    """Patch rows of one feature map [N][D] as a channels-first grid [D][gh][gw]."""
+    g = np.asarray(feat, dtype=np.float64)[1 + spec.registers:]
+    return np.ascontiguousarray(g.reshape(spec.gh, spec.gw, spec.dim).transpose(2, 0, 1))
+
+
+def _decide(z: np.ndarray, decide_dtype) -> np.ndarray:
+    """Channel argmax taken in the precision the GPU path decides in (ties -> lowest)."""
+    return ops.argmax_channels(np.asarray(z, dtype=decide_dtype).astype(np.float64))
+
+
+def seg_head(spec, hw, feats, decide_dtype=np.float32) -> Dict[str, np.ndarray]:
+    """Linear segmentation head on one image's features.
+
+    z = 1x1 conv D->C on the final patch tokens; Z = bilinear(z -> HxW); class = argmax_c Z.
+    Returns logits [C][gh][gw] and classmap [H][W].
+    """
+    z = ops.conv1x1(_grid(spec, feats[3]), hw["seg_w"], hw["seg_b"])
+    Z = ops.bilinear(z, spec.img_h, spec.img_w)
+    return {"logits": z, "classmap": _decide(Z, decide_dtype)}
+
+
+def det_head(spec, hw, feats, decide_dtype=np.float32) -> Dict[str, np.ndarray]:
+    """Dense detection head: two parallel 3x3 conv towers (D -> Ch, ReLU) on the final
+    patch grid; class tower -> 1x1 to the class logits, box tower -> 1x1 to 4 offsets.
+    Raw outputs (no sigmoid, decoding or NMS).  Returns logits [K][gh][gw], box [4][gh][gw],
+    classmap [gh][gw]."""
+    g = _grid(spec, feats[3])
+    tc = ops.conv3x3(g, hw["cls_tower_w"], hw["cls_tower_b"], relu=True)
+    tb = ops.conv3x3(g, hw["box_tower_w"], hw["box_tower_b"], relu=True)
+    logits = ops.conv1x1(tc, hw["cls_w"], hw["cls_b"])
+    box = ops.conv1x1(tb, hw["box_w"], hw["box_b"])
+    return {"logits": logits, "box": box, "classmap": _decide(logits, decide_dtype)}
+
+
+def depth_head(spec, hw, feats, return_stages: bool = False) -> Dict[str, np.ndarray]:
+    """DPT-lite depth head.  Taps deep -> shallow: t_0 = F_3, t_1 = F_2, t_2 = F_1, t_3 = F_0.
+
+    p_s = 1x1 conv D->Ch of t_s on the patch grid; u_s = bilinear(p_s -> 2^s gh x 2^s gw);
+    z_s = u_s + y_{s-1} (y_{-1} = 0); y_s = bilinear x2 of ReLU(conv3x3(z_s) + b_s).
+    d = 1x1 conv Ch->1 of y_3 (at 16 gh x 16 gw); depth = ReLU(bilinear(d -> H x W)).
+    """
+    gh, gw = spec.gh, spec.gw
+    y = None
+    stages = []
+    for s in range(4):
+        p = ops.conv1x1(_grid(spec, feats[3 - s]), hw[f"proj{s}_w"], hw[f"proj{s}_b"])
+        hs, ws = gh << s, gw << s
+        u = p if s == 0 else ops.bilinear(p, hs, ws)
+        z = u if y is None else u + y
+        r = ops.conv3x3(z, hw[f"fuse{s}_w"], hw[f"fuse{s}_b"], relu=True)
+        y = ops.bilinear(r, 2 * hs, 2 * ws)
+        if return_stages:
+            stages.append({"p": p, "z": z, "r": r})
+    d = ops.conv1x1(y, hw["out_w"], hw["out_b"])
+    depth = np.maximum(ops.bilinear(d, spec.img_h, spec.img_w), 0.0)[0]
+    out = {"depth": depth}
+    if return_stages:
+        out["stages"] = stages
+        out["d16"] = d
+    return out

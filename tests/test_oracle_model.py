@@ -1,0 +1,291 @@
+"""Pins for the oracle's model composition (encoder + heads): hand-expanded scalar loops on a
+tiny ViT, an independent second writing with library layers (torch CPU fp64), and the
+invariants the definitions imply."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import vpe_inputs as vi
+from oracle import model, ops
+
+T64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64))
+
+
+def relerr(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    assert a.shape == b.shape, (a.shape, b.shape)
+    return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300))
+
+
+def boost(w, factor=8.0):
+    """Scale the random weights up so every branch contributes visibly (std 0.02 makes
+    residual branches tiny, which would hide a dropped term)."""
+    out = {}
+    for k, v in w.items():
+        leaf = k.split(".")[-1]
+        if leaf in ("ls1", "ls2"):
+            out[k] = np.linspace(0.3, 0.9, v.size).astype(np.float64).reshape(v.shape)
+        elif leaf.endswith("_g"):
+            out[k] = 1.0 + (v.astype(np.float64) - 1.0) * factor
+        else:
+            out[k] = v.astype(np.float64) * factor
+    return out
+
+
+# ------------------------------------------------------------------ hand-expanded tiny ViT
+def _hand_block_forward(spec, w, img):
+    """Scalar loops only: one block of a 1-head ViT plus the final LayerNorm."""
+    D, N, gw = spec.dim, spec.tokens, spec.gw
+    x = [[0.0] * D for _ in range(N)]
+    for d in range(D):
+        x[0][d] = w["cls"][d] + w["pos"][0][d]
+    for p in range(spec.patches):
+        i, j = divmod(p, gw)
+        for d in range(D):
+            acc = w["patch_b"][d]
+            for c in range(3):
+                for u in range(14):
+                    for v in range(14):
+                        acc += w["patch_w"][d][c][u][v] * img[c][14 * i + u][14 * j + v]
+            x[1 + p][d] = acc + w["pos"][1 + p][d]
+
+    def ln(rows, g, b):
+        out = []
+        for r in rows:
+            mu = sum(r) / D
+            var = sum((e - mu) ** 2 for e in r) / D
+            out.append([g[d] * (r[d] - mu) / math.sqrt(var + spec.ln_eps) + b[d] for d in range(D)])
+        return out
+
+    def lin(rows, W, b, n_out):
+        return [[b[n] + sum(r[k] * W[k][n] for k in range(len(r))) for n in range(n_out)] for r in rows]
+
+    u = ln(x, w["blk0.ln1_g"], w["blk0.ln1_b"])
+    qkv = lin(u, w["blk0.qkv_w"], w["blk0.qkv_b"], 3 * D)
+    att = []
+    for i in range(N):
+        s = [sum(qkv[i][e] * qkv[j][D + e] for e in range(D)) / math.sqrt(D) for j in range(N)]
+        m = max(s)
+        e_ = [math.exp(v - m) for v in s]
+        z = sum(e_)
+        att.append([sum(e_[j] / z * qkv[j][2 * D + e] for j in range(N)) for e in range(D)])
+    o = lin(att, w["blk0.proj_w"], w["blk0.proj_b"], D)
+    x = [[x[t][d] + w["blk0.ls1"][d] * o[t][d] for d in range(D)] for t in range(N)]
+    u = ln(x, w["blk0.ln2_g"], w["blk0.ln2_b"])
+    h = lin(u, w["blk0.fc1_w"], w["blk0.fc1_b"], spec.mlp_hidden)
+    h = [[0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in r] for r in h]
+    m_ = lin(h, w["blk0.fc2_w"], w["blk0.fc2_b"], D)
+    x = [[x[t][d] + w["blk0.ls2"][d] * m_[t][d] for d in range(D)] for t in range(N)]
+    return np.array(x), np.array(ln(x, w["norm_g"], w["norm_b"]))
+
+
+def test_tiny_vit_block_equals_hand_expanded_loops():
+    spec = vi.ModelSpec("hand", dim=8, depth=1, heads=1, mlp_hidden=12, img_h=14, img_w=56, dtype="f32",
+                        taps=(1, 1, 1, 1), head_dim=8)
+    w = boost(vi.make_backbone_weights(spec, 5))
+    img = vi.make_image(14, 56, 6).astype(np.float64)
+    x_hand, f_hand = _hand_block_forward(spec, {k: v.tolist() for k, v in w.items()}, img.tolist())
+    x = model.block(spec, w, 0, model.tokens_from_image(spec, w, img))
+    assert relerr(x, x_hand) < 1e-13
+    assert relerr(ops.layernorm(x, w["norm_g"], w["norm_b"], spec.ln_eps), f_hand) < 1e-13
+
+
+# ------------------------------------------------------------------ second writing with library layers
+def _torch_encoder(spec, w, img):
+    D, R, nh, dh = spec.dim, spec.registers, spec.heads, spec.head_dim
+    t = F.conv2d(T64(img)[None], T64(w["patch_w"]), T64(w["patch_b"]), stride=14)[0]     # [D][gh][gw]
+    t = t.flatten(1).T + T64(w["pos"])[1:]
+    x = torch.cat([(T64(w["cls"]) + T64(w["pos"])[0])[None], T64(w["reg"]).reshape(R, D), t], 0)
+    feats = []
+    for l in range(spec.depth):
+        p = f"blk{l}."
+        u = F.layer_norm(x, (D,), T64(w[p + "ln1_g"]), T64(w[p + "ln1_b"]), spec.ln_eps)
+        qkv = u @ T64(w[p + "qkv_w"]) + T64(w[p + "qkv_b"])
+        q, k, v = (qkv[:, i * D:(i + 1) * D].reshape(-1, nh, dh).transpose(0, 1) for i in range(3))
+        a = F.scaled_dot_product_attention(q, k, v).transpose(0, 1).reshape(-1, D)
+        x = x + T64(w[p + "ls1"]) * (a @ T64(w[p + "proj_w"]) + T64(w[p + "proj_b"]))
+        u = F.layer_norm(x, (D,), T64(w[p + "ln2_g"]), T64(w[p + "ln2_b"]), spec.ln_eps)
+        h = u @ T64(w[p + "fc1_w"]) + T64(w[p + "fc1_b"])
+        if spec.mlp_kind == vi.MLP_SWIGLU:
+            h = F.silu(h[:, :spec.mlp_hidden]) * h[:, spec.mlp_hidden:]
+        else:
+            h = F.gelu(h)
+        x = x + T64(w[p + "ls2"]) * (h @ T64(w[p + "fc2_w"]) + T64(w[p + "fc2_b"]))
+        if l + 1 in spec.taps:
+            feats.append(F.layer_norm(x, (D,), T64(w["norm_g"]), T64(w["norm_b"]), spec.ln_eps))
+    return feats
+
+
+def _torch_grid(spec, f):
+    return f[1 + spec.registers:].reshape(spec.gh, spec.gw, spec.dim).permute(2, 0, 1)[None]
+
+
+def _torch_heads(spec, hs, hd, hp, feats):
+    g = _torch_grid(spec, feats[3])
+    seg = F.conv2d(g, T64(hs["seg_w"])[:, :, None, None], T64(hs["seg_b"]))
+    segmap = F.interpolate(seg, size=(spec.img_h, spec.img_w), mode="bilinear", align_corners=False)[0].argmax(0)
+    tc = F.relu(F.conv2d(g, T64(hd["cls_tower_w"]), T64(hd["cls_tower_b"]), padding=1))
+    tb = F.relu(F.conv2d(g, T64(hd["box_tower_w"]), T64(hd["box_tower_b"]), padding=1))
+    logits = F.conv2d(tc, T64(hd["cls_w"])[:, :, None, None], T64(hd["cls_b"]))[0]
+    box = F.conv2d(tb, T64(hd["box_w"])[:, :, None, None], T64(hd["box_b"]))[0]
+    y = None
+    for s in range(4):
+        p = F.conv2d(_torch_grid(spec, feats[3 - s]), T64(hp[f"proj{s}_w"])[:, :, None, None], T64(hp[f"proj{s}_b"]))
+        if s:
+            p = F.interpolate(p, scale_factor=2 ** s, mode="bilinear", align_corners=False)
+        z = p if y is None else p + y
+        r = F.relu(F.conv2d(z, T64(hp[f"fuse{s}_w"]), T64(hp[f"fuse{s}_b"]), padding=1))
+        y = F.interpolate(r, scale_factor=2, mode="bilinear", align_corners=False)
+    d = F.conv2d(y, T64(hp["out_w"])[:, :, None, None], T64(hp["out_b"]))
+    depth = F.relu(F.interpolate(d, size=(spec.img_h, spec.img_w), mode="bilinear", align_corners=False))[0, 0]
+    return seg[0], segmap, logits, box, depth
+
+
+@pytest.mark.parametrize("mlp_kind,registers", [(vi.MLP_GELU, 0), (vi.MLP_SWIGLU, 2)])
+def test_encoder_and_heads_equal_library_composition(mlp_kind, registers):
+    spec = vi.ModelSpec("second", dim=64, depth=4, heads=2, mlp_hidden=96, mlp_kind=mlp_kind, registers=registers,
+                        img_h=28, img_w=42, dtype="f32", taps=(1, 2, 3, 4), head_ch=16, seg_classes=5,
+                        det_classes=7, head_dim=32)
+    w = boost(vi.make_backbone_weights(spec, 11))
+    hs, hd, hp = (boost(vi.make_head_weights(spec, k, 11)) for k in (vi.HEAD_SEG, vi.HEAD_DET, vi.HEAD_DEPTH))
+    img = vi.make_image(28, 42, 12)
+    feats = model.encode_image(spec, w, img)
+    tfeats = _torch_encoder(spec, w, img)
+    for a, b in zip(feats, tfeats):
+        assert relerr(a, b.numpy()) < 1e-12
+    seg = model.seg_head(spec, hs, feats, decide_dtype=np.float64)
+    det = model.det_head(spec, hd, feats, decide_dtype=np.float64)
+    dep = model.depth_head(spec, hp, feats)
+    tseg, tsegmap, tlog, tbox, tdepth = _torch_heads(spec, hs, hd, hp, tfeats)
+    assert relerr(seg["logits"], tseg.numpy()) < 1e-12
+    assert np.mean(seg["classmap"] == tsegmap.numpy()) == 1.0
+    assert relerr(det["logits"], tlog.numpy()) < 1e-12
+    assert relerr(det["box"], tbox.numpy()) < 1e-12
+    assert np.array_equal(det["classmap"], tlog.argmax(0).numpy())
+    assert relerr(dep["depth"], tdepth.numpy()) < 1e-12
+    assert dep["depth"].min() >= 0.0 and dep["depth"].max() > 0.0
+
+
+# ------------------------------------------------------------------ invariants
+def _spec(**kw):
+    base = dict(dim=32, depth=4, heads=2, mlp_hidden=48, img_h=28, img_w=42, dtype="f32", taps=(1, 2, 3, 4),
+                head_ch=8, seg_classes=4, det_classes=5, head_dim=16)
+    base.update(kw)
+    return vi.ModelSpec("inv", **base)
+
+
+def test_zero_layerscale_makes_blocks_the_identity():
+    spec = _spec()
+    w = boost(vi.make_backbone_weights(spec, 3))
+    for l in range(spec.depth):
+        w[f"blk{l}.ls1"][:] = 0.0
+        w[f"blk{l}.ls2"][:] = 0.0
+    img = vi.make_image(28, 42, 4)
+    feats, stream = model.encode_image(spec, w, img, return_blocks=True)
+    for x in stream[1:]:
+        assert relerr(x, stream[0]) == 0.0
+    assert relerr(feats[0], feats[3]) == 0.0
+
+
+def test_taps_are_final_norm_of_the_stream_after_the_listed_blocks():
+    spec = _spec(depth=6, taps=(1, 3, 4, 6))
+    w = boost(vi.make_backbone_weights(spec, 8))
+    feats, stream = model.encode_image(spec, w, vi.make_image(28, 42, 9), return_blocks=True)
+    for f, l in zip(feats, spec.taps):
+        ref = F.layer_norm(T64(stream[l]), (spec.dim,), T64(w["norm_g"]), T64(w["norm_b"]), spec.ln_eps).numpy()
+        assert relerr(f, ref) < 1e-13
+
+
+def test_patch_permutation_equivariance_without_positional_embedding():
+    spec = _spec(registers=1)
+    w = boost(vi.make_backbone_weights(spec, 21))
+    w["pos"][:] = 0.0
+    img = vi.make_image(28, 42, 22).astype(np.float64)
+    # swap patch (0,0) with patch (1,2) in the image
+    img2 = img.copy()
+    img2[:, 0:14, 0:14], img2[:, 14:28, 28:42] = img[:, 14:28, 28:42], img[:, 0:14, 0:14]
+    f1 = model.encode_image(spec, w, img)[3]
+    f2 = model.encode_image(spec, w, img2)[3]
+    perm = np.arange(spec.tokens)
+    a, b = 1 + 1 + 0, 1 + 1 + (1 * 3 + 2)
+    perm[a], perm[b] = b, a
+    assert relerr(f2, f1[perm]) < 1e-12
+    assert relerr(f2, f1) > 1e-3          # and the swap really changed something
+
+
+def test_identical_patches_and_no_positional_embedding_give_identical_patch_outputs():
+    spec = _spec()
+    w = boost(vi.make_backbone_weights(spec, 31))
+    w["pos"][:] = 0.0
+    tile = vi.make_image(14, 14, 32).astype(np.float64)
+    img = np.tile(tile, (1, 2, 3))
+    f = model.encode_image(spec, w, img)[3]
+    assert relerr(f[2:], np.repeat(f[1:2], spec.patches - 1, 0)) < 1e-12
+
+
+def test_batch_elements_are_independent():
+    spec = _spec(batch=3)
+    w = vi.make_backbone_weights(spec, 41)
+    imgs = vi.make_batch(spec, 42)
+    feats = model.encode(spec, w, imgs)
+    single = model.encode_image(spec, w, imgs[1])
+    for k in range(4):
+        assert feats[k].shape == (3, spec.tokens, spec.dim)
+        assert relerr(feats[k][1], single[k]) == 0.0
+
+
+def test_one_channel_projection_commutes_with_bilinear_resize():
+    rng = np.random.default_rng(5)
+    r = rng.normal(size=(16, 6, 9))
+    wv, b = rng.normal(size=(1, 16)), rng.normal(size=1)
+    a = ops.conv1x1(ops.bilinear(r, 12, 18), wv, b)
+    c = ops.bilinear(ops.conv1x1(r, wv, b), 12, 18)
+    assert relerr(a, c) < 1e-12
+
+
+def test_depth_head_stage_structure():
+    spec = _spec()
+    w = boost(vi.make_backbone_weights(spec, 51))
+    hp = boost(vi.make_head_weights(spec, vi.HEAD_DEPTH, 51))
+    feats = model.encode_image(spec, w, vi.make_image(28, 42, 52))
+    out = model.depth_head(spec, hp, feats, return_stages=True)
+    for s, st in enumerate(out["stages"]):
+        assert st["p"].shape == (spec.head_ch, spec.gh, spec.gw)
+        assert st["z"].shape == (spec.head_ch, spec.gh << s, spec.gw << s)
+        assert st["r"].min() >= 0.0
+    assert out["d16"].shape == (1, 16 * spec.gh, 16 * spec.gw)
+    assert out["depth"].shape == (spec.img_h, spec.img_w) and out["depth"].min() >= 0.0
+    # stage 0 reads the deepest tap: changing the shallowest tap must leave its p untouched
+    feats2 = [f.copy() for f in feats]
+    feats2[0] += 1.0
+    out2 = model.depth_head(spec, hp, feats2, return_stages=True)
+    assert relerr(out2["stages"][0]["p"], out["stages"][0]["p"]) == 0.0
+    assert relerr(out2["stages"][3]["p"], out["stages"][3]["p"]) > 1e-3
+
+
+def test_heads_ignore_cls_and_register_rows():
+    spec = _spec(registers=2)
+    w = boost(vi.make_backbone_weights(spec, 61))
+    hs = boost(vi.make_head_weights(spec, vi.HEAD_SEG, 61))
+    hd = boost(vi.make_head_weights(spec, vi.HEAD_DET, 61))
+    feats = model.encode_image(spec, w, vi.make_image(28, 42, 62))
+    feats2 = [f.copy() for f in feats]
+    for f in feats2:
+        f[:3] += 5.0
+    assert relerr(model.seg_head(spec, hs, feats2)["logits"], model.seg_head(spec, hs, feats)["logits"]) == 0.0
+    assert relerr(model.det_head(spec, hd, feats2)["box"], model.det_head(spec, hd, feats)["box"]) == 0.0
+
+
+def test_fp32_rounding_of_inputs_bounds_oracle_sensitivity():
+    # the same model evaluated from fp32-rounded intermediates of the stream start stays within 1e-5:
+    # shows the 1e-4 fp32 gate is not consumed by conditioning of the problem itself
+    spec = _spec()
+    w = vi.make_backbone_weights(spec, 71)
+    img = vi.make_image(28, 42, 72)
+    f = model.encode_image(spec, w, img)[3]
+    img_pert = img.astype(np.float64) * (1.0 + 6e-8)
+    f2 = model.encode_image(spec, w, img_pert)[3]
+    assert relerr(f2, f) < 1e-5
