@@ -1,0 +1,170 @@
+/*
+ * vpe.h -- C ABI of the MI355X-native Visual Perception Engine hot path.
+ *
+ * The paper's engine (Sec. "System architecture") is a foundation module that runs a
+ * vision backbone continuously and writes its features into a "middle buffer", plus any
+ * number of head modules that read those features by reference, each at its own
+ * adjustable rate, with all buffers preallocated at start-up.  This library is that
+ * data path on one AMD MI355X (gfx950) in one process: the encoder writes each frame's
+ * features ONCE into a slot of a preallocated device ring; heads read the slot IN PLACE
+ * (no copies) on their own HIP streams; ordering is by HIP events.
+ *
+ * Every compute step behind these calls is a hand-written HIP kernel.  The library never
+ * touches host copies of activations and never allocates device memory after vpe_create.
+ *
+ * Conventions
+ *   - return value: 0 = VPE_OK, 1 = VPE_SKIPPED (head not due on that frame; not an
+ *     error), negative = error (see vpe_status).  vpe_last_error() gives a message.
+ *   - "device" pointers are HIP device addresses on the current device; "host" pointers
+ *     are ordinary process memory.
+ *   - streams are hipStream_t passed as void*; NULL selects the engine's own stream for
+ *     that call (one encoder stream, one stream per head, all at default priority).
+ *   - vpe_encode and vpe_run_head only enqueue work; vpe_sync blocks until it is done.
+ *   - an engine may be driven from one host thread at a time.
+ */
+#ifndef VPE_H
+#define VPE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vpe_engine vpe_engine;                 /* opaque, owned by the library */
+
+/* Feature handle returned by vpe_encode: which ring slot holds the frame, and the frame's
+ * index (0 for the first vpe_encode of the engine, then 1, 2, ...).  A plain value. */
+typedef struct { int32_t slot; int32_t reserved; int64_t frame; } vpe_feat;
+
+typedef enum { VPE_OK = 0, VPE_SKIPPED = 1, VPE_EINVAL = -1, VPE_ENOMEM = -2, VPE_ESTALE = -3,
+               VPE_EHIP = -4 } vpe_status;
+typedef enum { VPE_F32 = 0, VPE_BF16 = 1 } vpe_dtype;
+typedef enum { VPE_MLP_GELU = 0, VPE_MLP_SWIGLU = 1 } vpe_mlp;
+typedef enum { VPE_HEAD_SEG = 0, VPE_HEAD_DEPTH = 1, VPE_HEAD_DET = 2 } vpe_head_kind;
+
+enum {
+    VPE_FLAG_GRAPHS = 1,     /* replay the encoder and the heads as captured HIP graphs */
+    VPE_FLAG_HOST_ONLY = 2   /* no device at all: calls do the scheduling bookkeeping only (slot ring, rates,
+                                staleness, counters); for exercising the host logic on a machine without a GPU */
+};
+
+/*
+ * Backbone: a DINOv2-style ViT with 14x14 patches (paper, Sec. "Example implementation":
+ * the encoder outputs its final features and three evenly spaced intermediate layers).
+ *   tokens per image N = 1 + registers + (img_h/14)*(img_w/14): CLS, registers, patches.
+ *   taps[k] (1-based, strictly increasing, taps[3] == depth): after block taps[k] the shared
+ *   final LayerNorm of the residual stream is written to feature map k of the slot.
+ *   dtype: VPE_F32 = fp32 storage and fp32 MFMA arithmetic; VPE_BF16 = bf16 operands with
+ *   fp32 accumulation, fp32 residual stream and LayerNorm statistics.
+ *   weights: HOST pointer to fp32 values in this order (linear weights [in][out]):
+ *     patch_w [dim][3][14][14], patch_b [dim], cls [dim], reg [registers][dim],
+ *     pos [1 + patches][dim]  (row 0 is added to CLS, row 1+p to patch p; registers get none),
+ *     then per block: ln1_g, ln1_b [dim], qkv_w [dim][3 dim], qkv_b [3 dim]
+ *       (columns: queries of all heads, keys, values; head i owns 64 i .. 64 i + 63 of each),
+ *       proj_w [dim][dim], proj_b [dim], ls1 [dim], ln2_g, ln2_b [dim],
+ *       fc1_w [dim][F], fc1_b [F]  (F = mlp_hidden for GELU; 2 mlp_hidden for SwiGLU: gate half, then linear half),
+ *       fc2_w [mlp_hidden][dim], fc2_b [dim], ls2 [dim];
+ *     then norm_g, norm_b [dim].
+ *   The blob is read during vpe_create only; the caller keeps ownership and may free it after.
+ */
+typedef struct {
+    int32_t dim;          /* = heads * 64 */
+    int32_t depth;
+    int32_t heads;
+    int32_t mlp_hidden;
+    int32_t mlp_kind;     /* vpe_mlp */
+    int32_t registers;
+    int32_t img_h, img_w; /* multiples of 14 */
+    int32_t batch;
+    int32_t dtype;        /* vpe_dtype */
+    int32_t taps[4];
+    int32_t ring_slots;   /* >= 1; 2 or more lets encode(f+1) overlap heads(f) */
+    int32_t flags;        /* VPE_FLAG_* */
+    float   ln_eps;
+    int32_t reserved;
+    const void* weights;  /* host, fp32 */
+    uint64_t weights_bytes;
+} vpe_backbone_cfg;
+
+/*
+ * Heads (paper, Sec. "Head Module" and "Example implementation"), all reading patch rows of
+ * the slot's feature maps as an [img_h/14][img_w/14][dim] channels-last grid:
+ *   VPE_HEAD_SEG   linear segmentation: 1x1 conv dim->classes on the final map; bilinear x14
+ *                  (half-pixel centres) to img_h x img_w; per-pixel argmax (ties -> lowest).
+ *                  weights: seg_w [classes][dim], seg_b [classes].
+ *                  outputs: 0 = logits fp32 [B][gh][gw][classes]; 1 = class map u8 [B][img_h][img_w].
+ *   VPE_HEAD_DET   dense detection: two parallel 3x3 conv towers dim->channels (+ReLU) on the
+ *                  final map, then 1x1 to `classes` logits (class tower) and 4 box offsets (box tower).
+ *                  weights: cls_tower_w [ch][dim][3][3], cls_tower_b [ch], box_tower_w, box_tower_b (same
+ *                  shapes), cls_w [classes][ch], cls_b, box_w [4][ch], box_b.
+ *                  outputs: 0 = fp32 [B][gh][gw][classes + 4] (logits then box); 1 = class map u8 [B][gh][gw].
+ *   VPE_HEAD_DEPTH DPT-lite: stage s = 0..3 takes feature map 3 - s: 1x1 conv dim->ch, bilinear to
+ *                  2^s x the patch grid, add the previous stage's output, 3x3 conv ch->ch + ReLU, bilinear x2;
+ *                  then 1x1 conv ch->1, bilinear to img_h x img_w, ReLU.
+ *                  weights: proj{0..3}_w [ch][dim], proj{s}_b [ch] (pairs, s ascending), then
+ *                  fuse{0..3}_w [ch][ch][3][3], fuse{s}_b [ch] (pairs), out_w [1][ch], out_b [1].
+ *                  outputs: 0 = depth fp32 [B][img_h][img_w].
+ *   every_n >= 1: the head runs on frame f iff f % every_n == 0 (paper, Sec. "Dynamic Frequency Control").
+ */
+typedef struct {
+    int32_t kind;         /* vpe_head_kind */
+    int32_t classes;      /* seg: C; det: number of object classes; depth: ignored */
+    int32_t channels;     /* det / depth hidden width (multiple of 64); seg: ignored */
+    int32_t every_n;
+    const void* weights;  /* host, fp32 */
+    uint64_t weights_bytes;
+} vpe_head_cfg;
+
+/* Device bytes the engine needs for weights, scratch, the feature ring and head outputs.
+ * Returns 0 and sets *bytes, or VPE_EINVAL. */
+int vpe_workspace_bytes(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_heads, uint64_t* bytes);
+
+/* Build an engine.  workspace: DEVICE memory of at least vpe_workspace_bytes, 256-byte aligned,
+ * owned by the caller and kept alive until vpe_destroy (lets the caller's allocator own all
+ * device memory); NULL makes the library allocate it once with hipMalloc.  Uploads and re-lays
+ * the weights, zeroes padding, creates streams and events.  After this returns the engine
+ * never allocates device memory (paper, Sec. "Memory Management": preallocate at start-up). */
+int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_heads,
+               void* workspace, uint64_t workspace_bytes, vpe_engine** out);
+
+/* Encode one batch: images = DEVICE fp32 [batch][3][img_h][img_w], already normalised; it must
+ * stay valid until the enqueued work has run.  Picks ring slot frame % ring_slots, waits (on
+ * the GPU) for heads still reading that slot, runs the encoder, and returns the handle. */
+int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out);
+
+/* Run head `head` on a frame's features.  Returns VPE_SKIPPED when fh.frame % every_n != 0,
+ * VPE_ESTALE when the slot has been reused by a later frame. */
+int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream);
+
+/* Change a head's rate; takes effect from the next vpe_run_head.  every_n_frames < 1 -> VPE_EINVAL. */
+int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames);
+
+/* Borrowed DEVICE pointer to feature map `tap` (0..3, 3 = final tokens) of a frame:
+ * [batch][N][dim] in the engine's dtype.  Valid until the slot is reused. */
+int vpe_feat_view(vpe_engine* e, vpe_feat fh, int tap, const void** dev_ptr, int64_t shape[3]);
+
+/* Borrowed DEVICE pointer to output `which` of a head (see vpe_head_cfg); shape is padded
+ * with 1s to four entries.  Contents are those of the head's most recent run. */
+int vpe_head_output(vpe_engine* e, int head, int which, const void** dev_ptr, int64_t shape[4]);
+
+/* Block until everything enqueued through this engine has finished. */
+int vpe_sync(vpe_engine* e);
+
+/* Counters: frames encoded, and per head (up to n entries) how often it ran / was skipped. */
+int vpe_stats(vpe_engine* e, int64_t* frames, int64_t* head_runs, int64_t* head_skips, int n);
+
+/* Timing aid for benchmarks: enqueue `reps` repetitions of one internal kernel family on the
+ * encoder stream with HIP events around them and return the mean milliseconds per launch.
+ * which: 0 = the fused-QKV GEMM of block 0 on the current activations, 1 = the attention
+ * kernel of block 0, 2 = LayerNorm, 3 = the depth head's largest 3x3 convolution (needs a depth head).
+ * Also reports the algorithmic flops and bytes of one launch. */
+int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes);
+
+const char* vpe_last_error(vpe_engine* e);            /* engine may be NULL: last create error */
+void vpe_destroy(vpe_engine* e);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VPE_H */

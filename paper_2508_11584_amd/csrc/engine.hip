@@ -1,0 +1,771 @@
+// The engine behind the C ABI of vpe.h: device memory plan, weight upload and re-layout,
+// the encoder and head launch sequences, and the frame scheduler (feature-slot ring guarded
+// by HIP events, per-head streams and rate dividers, optional HIP-graph replay).
+//
+// Mapping to the paper (Sec. "System architecture"): vpe_encode is the foundation module,
+// the slot ring is its "middle buffer" (a circular GPU buffer that is overwritten oldest
+// first), vpe_run_head is a head module reading that buffer by reference, and every_n is the
+// per-head frequency control.  The paper's one-process-per-module + MPS design is replaced by
+// one process with one HIP stream per module.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "vpe.h"
+
+using namespace vpe;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+constexpr int KPATCH = 588;      // 3 * 14 * 14
+constexpr int KPATCH_PAD = 640;  // next multiple of the k-tile
+constexpr int NPAD = 128;        // weight rows are padded to the widest GEMM tile
+
+struct Bump {
+    char* base = nullptr;  // null: only count
+    uint64_t off = 0;
+    void* take(uint64_t bytes) {
+        off = (uint64_t)rup((int64_t)off, 256);
+        void* p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+struct BlockW {
+    float *ln1_g, *ln1_b, *qkv_b, *proj_b, *ls1, *ln2_g, *ln2_b, *fc1_b, *fc2_b, *ls2;
+    void *qkv_w, *proj_w, *fc1_w, *fc2_w;
+};
+
+struct Head {
+    int kind = 0, classes = 0, ch = 0, every_n = 1;
+    // weights
+    void* w0 = nullptr;            // seg: [C][D]; det: towers [2ch][9D]; depth: unused
+    float* b0 = nullptr;
+    void* w1 = nullptr;            // det: block-diagonal [classes + 4][2 ch]
+    float* b1 = nullptr;
+    void* proj_w[4] = {};          // depth
+    float* proj_b[4] = {};
+    void* fuse_w[4] = {};
+    float* fuse_b[4] = {};
+    float* out_w = nullptr;
+    float out_b = 0.0f;
+    // activations / outputs
+    float* logits = nullptr;       // seg [B P][C]; det [B P][classes + 4]
+    uint8_t* classmap = nullptr;
+    void* tower = nullptr;         // det [B P][2 ch]
+    void* p[4] = {};               // depth [B P][ch]
+    void *z = nullptr, *r = nullptr;
+    float *d8 = nullptr, *depth = nullptr;
+    // scheduling
+    hipStream_t stream = nullptr;
+    hipEvent_t last_done = nullptr;   // completion of the most recent run (any slot)
+    bool ran = false;
+    int64_t runs = 0, skips = 0;
+    std::vector<hipGraphExec_t> graphs;   // per slot
+};
+
+}  // namespace
+
+struct vpe_engine {
+    vpe_backbone_cfg cfg{};
+    bool bf = true, host_only = false, graphs = false, owns_ws = false;
+    int D = 0, L = 0, nh = 0, Mh = 0, F = 0, R = 0, B = 0, H = 0, W = 0, gh = 0, gw = 0, P = 0, N = 0, T = 0;
+    int npad = 0, esz = 2, S = 1;
+    char* ws = nullptr;
+    uint64_t ws_bytes = 0;
+    // backbone weights
+    void* patch_w = nullptr;
+    float *patch_b = nullptr, *special = nullptr, *pos = nullptr, *norm_g = nullptr, *norm_b = nullptr;
+    std::vector<BlockW> blk;
+    // encoder scratch
+    void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
+    float* x = nullptr;
+    // ring
+    std::vector<void*> feat;             // [S][4]
+    std::vector<int64_t> slot_frame;     // frame held by each slot, -1 = none
+    std::vector<hipEvent_t> ready;       // [S]
+    std::vector<hipEvent_t> done;        // [S][n_heads]
+    std::vector<char> done_set;          // [S][n_heads]
+    std::vector<hipGraphExec_t> enc_graphs;   // [S]
+    int last_enc_slot = -1;
+    std::vector<Head> heads;
+    hipStream_t enc_stream = nullptr, cap_stream = nullptr;
+    int64_t frames = 0;
+    std::string err;
+
+    int fail(int code, const std::string& m) { err = m; return code; }
+};
+
+namespace {
+
+#define HIPCHK(e, call)                                                                      \
+    do {                                                                                     \
+        hipError_t err__ = (call);                                                           \
+        if (err__ != hipSuccess)                                                             \
+            return (e)->fail(VPE_EHIP, std::string(#call) + ": " + hipGetErrorString(err__)); \
+    } while (0)
+
+int64_t backbone_floats(const vpe_backbone_cfg& c) {
+    const int64_t D = c.dim, P = (int64_t)(c.img_h / 14) * (c.img_w / 14);
+    const int64_t F = (int64_t)c.mlp_hidden * (c.mlp_kind == VPE_MLP_SWIGLU ? 2 : 1);
+    int64_t n = D * KPATCH + D + D + (int64_t)c.registers * D + (1 + P) * D;
+    n += c.depth * (2 * D + D * 3 * D + 3 * D + D * D + D + D + 2 * D + D * F + F + c.mlp_hidden * D + D + D);
+    return n + 2 * D;
+}
+
+int64_t head_floats(const vpe_backbone_cfg& c, const vpe_head_cfg& h) {
+    const int64_t D = c.dim, ch = h.channels;
+    switch (h.kind) {
+        case VPE_HEAD_SEG: return (int64_t)h.classes * D + h.classes;
+        case VPE_HEAD_DET: return 2 * (ch * D * 9 + ch) + (int64_t)h.classes * ch + h.classes + 4 * ch + 4;
+        case VPE_HEAD_DEPTH: return 4 * (ch * D + ch) + 4 * (ch * ch * 9 + ch) + ch + 1;
+    }
+    return -1;
+}
+
+// Returns an empty string when the configuration is acceptable.
+std::string validate(const vpe_backbone_cfg* c, const vpe_head_cfg* heads, int n_heads) {
+    char buf[256];
+    if (!c) return "backbone_cfg is null";
+    if (n_heads < 0 || (n_heads > 0 && !heads)) return "heads is null";
+    if (c->dim <= 0 || c->heads <= 0 || c->dim != c->heads * 64) return "dim must equal heads * 64";
+    if (c->dim > 2048) return "dim above 2048 is not supported";
+    if (c->depth < 1 || c->mlp_hidden < 64 || c->mlp_hidden % 64) return "depth >= 1 and mlp_hidden a multiple of 64 required";
+    if (c->mlp_kind != VPE_MLP_GELU && c->mlp_kind != VPE_MLP_SWIGLU) return "unknown mlp_kind";
+    if (c->dtype != VPE_F32 && c->dtype != VPE_BF16) return "unknown dtype";
+    if (c->registers < 0 || c->registers > 64) return "registers out of range";
+    if (c->batch < 1) return "batch must be >= 1";
+    if (c->img_h < 14 || c->img_w < 14 || c->img_h % 14 || c->img_w % 14) return "img_h and img_w must be positive multiples of 14";
+    if (c->ring_slots < 1 || c->ring_slots > 64) return "ring_slots must be in 1..64";
+    if (!(c->ln_eps > 0.0f)) return "ln_eps must be positive";
+    for (int k = 0; k < 4; ++k) {
+        if (c->taps[k] < 1 || c->taps[k] > c->depth) return "taps must lie in 1..depth";
+        if (k && c->taps[k] <= c->taps[k - 1]) return "taps must be strictly increasing";
+    }
+    if (c->taps[3] != c->depth) return "taps[3] must equal depth";
+    if (!c->weights) return "backbone weights pointer is null";
+    if ((int64_t)c->weights_bytes != 4 * backbone_floats(*c)) {
+        snprintf(buf, sizeof buf, "backbone weights_bytes is %llu, expected %lld", (unsigned long long)c->weights_bytes,
+                 (long long)(4 * backbone_floats(*c)));
+        return buf;
+    }
+    for (int i = 0; i < n_heads; ++i) {
+        const vpe_head_cfg& h = heads[i];
+        if (h.kind != VPE_HEAD_SEG && h.kind != VPE_HEAD_DEPTH && h.kind != VPE_HEAD_DET) return "unknown head kind";
+        if (h.every_n < 1) return "every_n must be >= 1";
+        if (h.kind != VPE_HEAD_DEPTH && (h.classes < 1 || h.classes > 256)) return "classes must be in 1..256";
+        if (h.kind != VPE_HEAD_SEG && (h.channels < 64 || h.channels % 64 || h.channels > 1024))
+            return "channels must be a multiple of 64 in 64..1024";
+        if (!h.weights) return "head weights pointer is null";
+        if ((int64_t)h.weights_bytes != 4 * head_floats(*c, h)) {
+            snprintf(buf, sizeof buf, "head %d weights_bytes is %llu, expected %lld", i,
+                     (unsigned long long)h.weights_bytes, (long long)(4 * head_floats(*c, h)));
+            return buf;
+        }
+    }
+    return "";
+}
+
+void derive(vpe_engine& e, const vpe_backbone_cfg& c, const vpe_head_cfg* heads, int n_heads) {
+    e.cfg = c;
+    e.cfg.weights = nullptr;
+    e.bf = c.dtype == VPE_BF16;
+    e.esz = e.bf ? 2 : 4;
+    e.host_only = false;
+    e.graphs = (c.flags & VPE_FLAG_GRAPHS) != 0;
+    e.D = c.dim; e.L = c.depth; e.nh = c.heads; e.Mh = c.mlp_hidden;
+    e.F = c.mlp_hidden * (c.mlp_kind == VPE_MLP_SWIGLU ? 2 : 1);
+    e.R = c.registers; e.B = c.batch; e.H = c.img_h; e.W = c.img_w;
+    e.gh = c.img_h / 14; e.gw = c.img_w / 14; e.P = e.gh * e.gw;
+    e.N = 1 + e.R + e.P; e.T = e.B * e.N;
+    e.npad = (int)rup(e.N, 64);
+    e.S = c.ring_slots;
+    e.heads.assign(n_heads, Head());
+    for (int i = 0; i < n_heads; ++i) {
+        e.heads[i].kind = heads[i].kind;
+        e.heads[i].classes = heads[i].classes;
+        e.heads[i].ch = heads[i].channels;
+        e.heads[i].every_n = heads[i].every_n;
+    }
+}
+
+// Hands out every device region; with b.base == nullptr it only measures.
+void layout(vpe_engine& e, Bump& b) {
+    const uint64_t esz = e.esz;
+    const uint64_t D = e.D, T = e.T, P = e.P, B = e.B;
+    auto wrows = [&](int n) { return (uint64_t)rup(n, NPAD); };
+    auto f32 = [&](uint64_t n) { return (float*)b.take(4 * n); };
+    e.patch_w = b.take(wrows(e.D) * KPATCH_PAD * esz);
+    e.patch_b = f32(D);
+    e.special = f32((1 + e.R) * D);
+    e.pos = f32(P * D);
+    e.blk.resize(e.L);
+    for (auto& w : e.blk) {
+        w.ln1_g = f32(D); w.ln1_b = f32(D);
+        w.qkv_w = b.take(wrows(3 * e.D) * D * esz); w.qkv_b = f32(3 * D);
+        w.proj_w = b.take(wrows(e.D) * D * esz); w.proj_b = f32(D);
+        w.ls1 = f32(D);
+        w.ln2_g = f32(D); w.ln2_b = f32(D);
+        w.fc1_w = b.take(wrows(e.F) * D * esz); w.fc1_b = f32(e.F);
+        w.fc2_w = b.take(wrows(e.D) * e.Mh * esz); w.fc2_b = f32(D);
+        w.ls2 = f32(D);
+    }
+    e.norm_g = f32(D); e.norm_b = f32(D);
+    e.apatch = b.take(B * P * KPATCH_PAD * esz);
+    e.x = f32(T * D);
+    e.u = b.take(T * D * esz);
+    e.qk = b.take(T * 2 * D * esz);
+    e.vt = b.take(B * D * e.npad * esz);
+    e.att = b.take(T * D * esz);
+    e.hid = b.take(T * e.Mh * esz);
+    e.feat.resize((size_t)e.S * 4);
+    for (auto& f : e.feat) f = b.take(T * D * esz);
+    for (auto& h : e.heads) {
+        const uint64_t ch = h.ch, BP = B * P;
+        if (h.kind == VPE_HEAD_SEG) {
+            h.w0 = b.take(wrows(h.classes) * D * esz); h.b0 = f32(h.classes);
+            h.logits = f32(BP * h.classes);
+            h.classmap = (uint8_t*)b.take(B * e.H * e.W);
+        } else if (h.kind == VPE_HEAD_DET) {
+            h.w0 = b.take(wrows(2 * h.ch) * 9 * D * esz); h.b0 = f32(2 * ch);
+            h.w1 = b.take(wrows(h.classes + 4) * 2 * ch * esz); h.b1 = f32(h.classes + 4);
+            h.tower = b.take(BP * 2 * ch * esz);
+            h.logits = f32(BP * (h.classes + 4));
+            h.classmap = (uint8_t*)b.take(BP);
+        } else {
+            for (int s = 0; s < 4; ++s) { h.proj_w[s] = b.take(wrows(h.ch) * D * esz); h.proj_b[s] = f32(ch); }
+            for (int s = 0; s < 4; ++s) { h.fuse_w[s] = b.take(wrows(h.ch) * 9 * ch * esz); h.fuse_b[s] = f32(ch); }
+            h.out_w = f32(ch);
+            for (int s = 0; s < 4; ++s) h.p[s] = b.take(BP * ch * esz);
+            h.z = b.take(BP * 64 * ch * esz);
+            h.r = b.take(BP * 64 * ch * esz);
+            h.d8 = f32(BP * 64);
+            h.depth = f32(B * e.H * e.W);
+        }
+    }
+}
+
+// Walks a host fp32 blob in its documented order and places each tensor on the device.
+struct Uploader {
+    vpe_engine* e;
+    const float* host;
+    int64_t n, pos = 0;
+    float* staging;
+    const float* take(int64_t k) { const float* p = host + pos; pos += k; return p; }
+    int f32(float* dst, int64_t k) {
+        HIPCHK(e, hipMemcpy(dst, take(k), 4 * k, hipMemcpyHostToDevice));
+        return 0;
+    }
+    // tensor of `count` floats -> dst rows/cols via relayout_kernel (see rowops.h)
+    int relayout(int64_t count, void* dst, int n_rows, int n_cols, int64_t rs, int64_t cs, int mode, int cin,
+                 int swiglu_half, int64_t dst_ld, int row_off, int col_off) {
+        HIPCHK(e, hipMemcpy(staging, take(count), 4 * count, hipMemcpyHostToDevice));
+        HIPCHK(e, launch_relayout(e->bf, staging, dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld,
+                                  row_off, col_off, nullptr));
+        HIPCHK(e, hipStreamSynchronize(nullptr));
+        return 0;
+    }
+    // y = x W + b weights stored [in][out]  ->  [out][in]
+    int linear(void* dst, int in, int out, int swiglu_half = 0) {
+        return relayout((int64_t)in * out, dst, out, in, 1, out, 0, 0, swiglu_half, in, 0, 0);
+    }
+};
+
+#define TRY(x) do { int rc__ = (x); if (rc__) return rc__; } while (0)
+
+int upload_backbone(vpe_engine& e, const float* blob, float* staging) {
+    Uploader up{&e, blob, backbone_floats(e.cfg), 0, staging};
+    const int D = e.D;
+    // patch kernel [D][588] -> [D][640] (zero padded columns)
+    TRY(up.relayout((int64_t)D * KPATCH, e.patch_w, D, KPATCH, KPATCH, 1, 0, 0, 0, KPATCH_PAD, 0, 0));
+    TRY(up.f32(e.patch_b, D));
+    // special rows: CLS + pos[0], then the registers; remaining pos rows belong to the patches
+    const float* cls = up.take(D);
+    const float* reg = up.take((int64_t)e.R * D);
+    const float* pos = up.take((int64_t)(1 + e.P) * D);
+    std::vector<float> sp((size_t)(1 + e.R) * D);
+    for (int d = 0; d < D; ++d) sp[d] = cls[d] + pos[d];
+    if (e.R) memcpy(sp.data() + D, reg, sizeof(float) * (size_t)e.R * D);
+    HIPCHK(&e, hipMemcpy(e.special, sp.data(), sp.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(&e, hipMemcpy(e.pos, pos + D, (size_t)e.P * D * 4, hipMemcpyHostToDevice));
+    const bool sw = e.cfg.mlp_kind == VPE_MLP_SWIGLU;
+    for (auto& w : e.blk) {
+        TRY(up.f32(w.ln1_g, D)); TRY(up.f32(w.ln1_b, D));
+        TRY(up.linear(w.qkv_w, D, 3 * D)); TRY(up.f32(w.qkv_b, 3 * D));
+        TRY(up.linear(w.proj_w, D, D)); TRY(up.f32(w.proj_b, D));
+        TRY(up.f32(w.ls1, D));
+        TRY(up.f32(w.ln2_g, D)); TRY(up.f32(w.ln2_b, D));
+        TRY(up.linear(w.fc1_w, D, e.F, sw ? e.Mh : 0));
+        if (sw) {   // bias follows the same physical column order as the re-laid weight
+            const float* b = up.take(e.F);
+            std::vector<float> pb(e.F);
+            for (int n = 0; n < e.F; ++n) {
+                const int grp = n >> 6, j = n & 63;
+                pb[n] = b[j < 32 ? 32 * grp + j : e.Mh + 32 * grp + j - 32];
+            }
+            HIPCHK(&e, hipMemcpy(w.fc1_b, pb.data(), 4 * (size_t)e.F, hipMemcpyHostToDevice));
+        } else {
+            TRY(up.f32(w.fc1_b, e.F));
+        }
+        TRY(up.linear(w.fc2_w, e.Mh, D)); TRY(up.f32(w.fc2_b, D));
+        TRY(up.f32(w.ls2, D));
+    }
+    TRY(up.f32(e.norm_g, D)); TRY(up.f32(e.norm_b, D));
+    return up.pos == up.n ? 0 : e.fail(VPE_EINVAL, "backbone blob size mismatch");
+}
+
+int upload_head(vpe_engine& e, Head& h, const float* blob, int64_t n, float* staging) {
+    Uploader up{&e, blob, n, 0, staging};
+    const int D = e.D, ch = h.ch;
+    if (h.kind == VPE_HEAD_SEG) {
+        TRY(up.relayout((int64_t)h.classes * D, h.w0, h.classes, D, D, 1, 0, 0, 0, D, 0, 0));
+        TRY(up.f32(h.b0, h.classes));
+    } else if (h.kind == VPE_HEAD_DET) {
+        // both towers as one [2 ch][9 D] implicit-GEMM weight (class tower first)
+        TRY(up.relayout((int64_t)ch * D * 9, h.w0, ch, 9 * D, 0, 0, 1, D, 0, 9 * D, 0, 0));
+        TRY(up.f32(h.b0, ch));
+        TRY(up.relayout((int64_t)ch * D * 9, h.w0, ch, 9 * D, 0, 0, 1, D, 0, 9 * D, ch, 0));
+        TRY(up.f32(h.b0 + ch, ch));
+        // block-diagonal 1x1: class logits read tower columns [0, ch), box offsets [ch, 2 ch)
+        TRY(up.relayout((int64_t)h.classes * ch, h.w1, h.classes, ch, ch, 1, 0, 0, 0, 2 * ch, 0, 0));
+        TRY(up.f32(h.b1, h.classes));
+        TRY(up.relayout((int64_t)4 * ch, h.w1, 4, ch, ch, 1, 0, 0, 0, 2 * ch, h.classes, ch));
+        TRY(up.f32(h.b1 + h.classes, 4));
+    } else {
+        for (int s = 0; s < 4; ++s) {
+            TRY(up.relayout((int64_t)ch * D, h.proj_w[s], ch, D, D, 1, 0, 0, 0, D, 0, 0));
+            TRY(up.f32(h.proj_b[s], ch));
+        }
+        for (int s = 0; s < 4; ++s) {
+            TRY(up.relayout((int64_t)ch * ch * 9, h.fuse_w[s], ch, 9 * ch, 0, 0, 1, ch, 0, 9 * ch, 0, 0));
+            TRY(up.f32(h.fuse_b[s], ch));
+        }
+        TRY(up.f32(h.out_w, ch));
+        h.out_b = *up.take(1);
+    }
+    return up.pos == up.n ? 0 : e.fail(VPE_EINVAL, "head blob size mismatch");
+}
+
+GemmArgs plain_gemm(const void* A, int64_t lda, const void* W, const float* bias, int M, int N, int K) {
+    GemmArgs a{};
+    a.A = A; a.lda = lda; a.W = W; a.bias = bias; a.M = M; a.N = N; a.K = K;
+    a.a_rpi = M > 0 ? M : 1; a.a_istride = 0; a.a_off = 0;
+    a.o_rpi = M > 0 ? M : 1; a.o_istride = 0; a.o_off = 0;
+    a.epi = EPI_STORE; a.act = ACT_NONE; a.out_f32 = 0;
+    return a;
+}
+
+// ------------------------------------------------------------------ launch sequences
+int enqueue_encoder_body(vpe_engine& e, int slot, hipStream_t s) {
+    const int D = e.D, T = e.T, dt = e.bf;
+    {   // patch embedding: [B P][640] x [D][640]^T + bias + pos -> residual stream rows of the patches
+        GemmArgs a = plain_gemm(e.apatch, KPATCH_PAD, e.patch_w, e.patch_b, e.B * e.P, D, KPATCH_PAD);
+        a.epi = EPI_PATCH; a.out = e.x; a.ldo = D; a.pos = e.pos;
+        a.o_rpi = e.P; a.o_istride = e.N; a.o_off = 1 + e.R;
+        HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+    }
+    int tap = 0;
+    for (int l = 0; l < e.L; ++l) {
+        const BlockW& w = e.blk[l];
+        HIPCHK(&e, launch_layernorm(dt, e.x, T, D, w.ln1_g, w.ln1_b, e.cfg.ln_eps, e.u, s));
+        {
+            GemmArgs a = plain_gemm(e.u, D, w.qkv_w, w.qkv_b, T, 3 * D, D);
+            a.epi = EPI_QKV; a.out = e.qk; a.ldo = 2 * D; a.out2 = e.vt; a.ntok = e.N; a.npad = e.npad; a.dim = D;
+            HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        }
+        {
+            AttnArgs a{e.qk, e.vt, e.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f};
+            HIPCHK(&e, launch_attention(dt, a, s));
+        }
+        {
+            GemmArgs a = plain_gemm(e.att, D, w.proj_w, w.proj_b, T, D, D);
+            a.epi = EPI_RESID; a.out = e.x; a.ldo = D; a.gamma = w.ls1;
+            HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        }
+        HIPCHK(&e, launch_layernorm(dt, e.x, T, D, w.ln2_g, w.ln2_b, e.cfg.ln_eps, e.u, s));
+        {
+            GemmArgs a = plain_gemm(e.u, D, w.fc1_w, w.fc1_b, T, e.F, D);
+            a.out = e.hid; a.ldo = e.Mh;
+            if (e.cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
+            else a.act = ACT_GELU;
+            HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        }
+        {
+            GemmArgs a = plain_gemm(e.hid, e.Mh, w.fc2_w, w.fc2_b, T, D, e.Mh);
+            a.epi = EPI_RESID; a.out = e.x; a.ldo = D; a.gamma = w.ls2;
+            HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        }
+        if (tap < 4 && l + 1 == e.cfg.taps[tap]) {
+            HIPCHK(&e, launch_layernorm(dt, e.x, T, D, e.norm_g, e.norm_b, e.cfg.ln_eps, e.feat[slot * 4 + tap], s));
+            ++tap;
+        }
+    }
+    return 0;
+}
+
+// 1x1 convolution on the patch rows of a feature map: skips CLS / register rows via the row map
+GemmArgs tokens_gemm(vpe_engine& e, const void* feat, const void* W, const float* bias, int N) {
+    GemmArgs a = plain_gemm(feat, e.D, W, bias, e.B * e.P, N, e.D);
+    a.a_rpi = e.P; a.a_istride = e.N; a.a_off = 1 + e.R;
+    return a;
+}
+
+GemmArgs conv3_gemm(const void* in, int C, int B, int h, int w, int istride, int off, const void* W,
+                    const float* bias, int N) {
+    GemmArgs a = plain_gemm(in, C, W, bias, B * h * w, N, 9 * C);
+    a.a_istride = istride; a.a_off = off; a.cH = h; a.cW = w; a.cC = C;
+    a.act = ACT_RELU;
+    return a;
+}
+
+int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
+    const int dt = e.bf, BP = e.B * e.P;
+    void* const* f = &e.feat[slot * 4];
+    if (h.kind == VPE_HEAD_SEG) {
+        GemmArgs a = tokens_gemm(e, f[3], h.w0, h.b0, h.classes);
+        a.out = h.logits; a.ldo = h.classes; a.out_f32 = 1;
+        HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        HIPCHK(&e, launch_seg_upsample_argmax(h.logits, e.B, e.gh, e.gw, h.classes, e.H, e.W, h.classmap, s));
+    } else if (h.kind == VPE_HEAD_DET) {
+        GemmArgs a = conv3_gemm(f[3], e.D, e.B, e.gh, e.gw, e.N, 1 + e.R, h.w0, h.b0, 2 * h.ch);
+        a.out = h.tower; a.ldo = 2 * h.ch;
+        HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
+        GemmArgs o = plain_gemm(h.tower, 2 * h.ch, h.w1, h.b1, BP, h.classes + 4, 2 * h.ch);
+        o.out = h.logits; o.ldo = h.classes + 4; o.out_f32 = 1;
+        HIPCHK(&e, launch_gemm(dt, o, A_PLAIN, s));
+        HIPCHK(&e, launch_argmax_rows(h.logits, BP, h.classes, h.classes + 4, h.classmap, s));
+    } else {
+        for (int st = 0; st < 4; ++st) {
+            GemmArgs a = tokens_gemm(e, f[3 - st], h.proj_w[st], h.proj_b[st], h.ch);
+            a.out = h.p[st]; a.ldo = h.ch;
+            HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        }
+        for (int st = 0; st < 4; ++st) {
+            const int hs = e.gh << st, wsz = e.gw << st;
+            const void* in = h.p[0];
+            if (st) {
+                HIPCHK(&e, launch_fuse_upsample(dt, h.p[st], e.gh, e.gw, h.r, e.B, hs, wsz, h.ch, h.z, s));
+                in = h.z;
+            }
+            GemmArgs a = conv3_gemm(in, h.ch, e.B, hs, wsz, hs * wsz, 0, h.fuse_w[st], h.fuse_b[st], h.ch);
+            a.out = h.r; a.ldo = h.ch;
+            HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
+        }
+        HIPCHK(&e, launch_rowdot(dt, h.r, (int64_t)BP * 64, h.ch, h.out_w, h.out_b, h.d8, s));
+        HIPCHK(&e, launch_depth_output(h.d8, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
+    }
+    return 0;
+}
+
+// Capture `body` on the engine's capture stream into an executable graph.
+template <typename Fn>
+int capture(vpe_engine& e, hipGraphExec_t* out, Fn body) {
+    HIPCHK(&e, hipStreamBeginCapture(e.cap_stream, hipStreamCaptureModeRelaxed));
+    const int rc = body(e.cap_stream);
+    hipGraph_t g = nullptr;
+    const hipError_t ec = hipStreamEndCapture(e.cap_stream, &g);
+    if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+    HIPCHK(&e, ec);
+    const hipError_t ei = hipGraphInstantiate(out, g, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(g);
+    HIPCHK(&e, ei);
+    return 0;
+}
+
+void destroy_engine(vpe_engine* e) {
+    if (!e) return;
+    if (!e->host_only) {
+        (void)hipDeviceSynchronize();
+        for (auto g : e->enc_graphs) if (g) (void)hipGraphExecDestroy(g);
+        for (auto& h : e->heads) {
+            for (auto g : h.graphs) if (g) (void)hipGraphExecDestroy(g);
+            if (h.stream) (void)hipStreamDestroy(h.stream);
+        }
+        for (auto ev : e->ready) if (ev) (void)hipEventDestroy(ev);
+        for (auto ev : e->done) if (ev) (void)hipEventDestroy(ev);
+        if (e->enc_stream) (void)hipStreamDestroy(e->enc_stream);
+        if (e->cap_stream) (void)hipStreamDestroy(e->cap_stream);
+        if (e->owns_ws && e->ws) (void)hipFree(e->ws);
+    }
+    delete e;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" {
+
+int vpe_workspace_bytes(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_heads, uint64_t* bytes) {
+    const std::string v = validate(cfg, heads, n_heads);
+    if (!v.empty() || !bytes) { g_create_error = v.empty() ? "bytes is null" : v; return VPE_EINVAL; }
+    vpe_engine e;
+    derive(e, *cfg, heads, n_heads);
+    Bump b;
+    layout(e, b);
+    *bytes = (uint64_t)rup((int64_t)b.off, 256);
+    return VPE_OK;
+}
+
+int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_heads, void* workspace,
+               uint64_t workspace_bytes, vpe_engine** out) {
+    if (out) *out = nullptr;
+    const std::string v = validate(cfg, heads, n_heads);
+    if (!v.empty() || !out) { g_create_error = v.empty() ? "out is null" : v; return VPE_EINVAL; }
+    vpe_engine* e = new vpe_engine();
+    derive(*e, *cfg, heads, n_heads);
+    e->host_only = (cfg->flags & 2) != 0;
+    Bump measure;
+    layout(*e, measure);
+    const uint64_t need = (uint64_t)rup((int64_t)measure.off, 256);
+    auto bail = [&](int code) { g_create_error = e->err; destroy_engine(e); return code; };
+    const int nh = (int)e->heads.size();
+    e->slot_frame.assign(e->S, -1);
+    e->done_set.assign((size_t)e->S * std::max(nh, 1), 0);
+    if (e->host_only) { *out = e; return VPE_OK; }
+
+    if (workspace) {
+        if (workspace_bytes < need || ((uintptr_t)workspace & 255)) {
+            e->fail(VPE_EINVAL, "workspace too small or not 256-byte aligned");
+            return bail(VPE_EINVAL);
+        }
+        e->ws = (char*)workspace;
+    } else {
+        if (hipMalloc((void**)&e->ws, need) != hipSuccess) {
+            e->fail(VPE_ENOMEM, "hipMalloc of the engine workspace failed (is a HIP device present?)");
+            return bail(VPE_ENOMEM);
+        }
+        e->owns_ws = true;
+    }
+    e->ws_bytes = need;
+    auto hip = [&](hipError_t rc, const char* what) {
+        if (rc == hipSuccess) return 0;
+        e->fail(VPE_EHIP, std::string(what) + ": " + hipGetErrorString(rc));
+        return 1;
+    };
+    if (hip(hipMemset(e->ws, 0, need), "hipMemset")) return bail(VPE_EHIP);
+    Bump real;
+    real.base = e->ws;
+    layout(*e, real);
+
+    // staging for one tensor at a time (freed before returning)
+    int64_t big = (int64_t)e->D * std::max({3 * e->D, e->F, e->Mh, KPATCH});
+    for (auto& h : e->heads) big = std::max<int64_t>(big, (int64_t)h.ch * 9 * std::max(e->D, h.ch));
+    for (auto& h : e->heads) big = std::max<int64_t>(big, (int64_t)h.classes * e->D);
+    float* staging = nullptr;
+    if (hip(hipMalloc((void**)&staging, 4 * big), "hipMalloc(staging)")) return bail(VPE_ENOMEM);
+    int rc = upload_backbone(*e, (const float*)cfg->weights, staging);
+    for (int i = 0; i < nh && !rc; ++i)
+        rc = upload_head(*e, e->heads[i], (const float*)heads[i].weights, head_floats(*cfg, heads[i]), staging);
+    (void)hipFree(staging);
+    if (rc) return bail(rc);
+
+    if (hip(hipStreamCreateWithFlags(&e->enc_stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+    if (hip(hipStreamCreateWithFlags(&e->cap_stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+    e->ready.assign(e->S, nullptr);
+    e->done.assign((size_t)e->S * std::max(nh, 1), nullptr);
+    for (auto& ev : e->ready)
+        if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
+    for (auto& ev : e->done)
+        if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
+    e->enc_graphs.assign(e->S, nullptr);
+    for (auto& h : e->heads) {
+        if (hip(hipStreamCreateWithFlags(&h.stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+        h.graphs.assign(e->S, nullptr);
+    }
+    if (hip(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(VPE_EHIP);
+    *out = e;
+    return VPE_OK;
+}
+
+int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out) {
+    if (!e) return VPE_EINVAL;
+    if (!out) return e->fail(VPE_EINVAL, "out is null");
+    if (!images && !e->host_only) return e->fail(VPE_EINVAL, "images is null");
+    const int64_t frame = e->frames;
+    const int slot = (int)(frame % e->S);
+    const int nh = (int)e->heads.size();
+    if (!e->host_only) {
+        hipStream_t s = stream ? (hipStream_t)stream : e->enc_stream;
+        // the slot's previous frame may still be read by heads: wait for them on the GPU
+        for (int h = 0; h < nh; ++h)
+            if (e->done_set[(size_t)slot * nh + h]) HIPCHK(e, hipStreamWaitEvent(s, e->done[(size_t)slot * nh + h], 0));
+        // the encoder's scratch is single-instance: order after the previous encode
+        if (e->last_enc_slot >= 0) HIPCHK(e, hipStreamWaitEvent(s, e->ready[e->last_enc_slot], 0));
+        HIPCHK(e, launch_im2col(e->bf, images, e->B, e->H, e->W, KPATCH_PAD, e->apatch, e->special, 1 + e->R,
+                                e->N, e->D, e->x, s));
+        if (e->graphs) {
+            if (!e->enc_graphs[slot])
+                TRY(capture(*e, &e->enc_graphs[slot], [&](hipStream_t cs) { return enqueue_encoder_body(*e, slot, cs); }));
+            HIPCHK(e, hipGraphLaunch(e->enc_graphs[slot], s));
+        } else {
+            TRY(enqueue_encoder_body(*e, slot, s));
+        }
+        HIPCHK(e, hipEventRecord(e->ready[slot], s));
+    }
+    for (int h = 0; h < nh; ++h) e->done_set[(size_t)slot * nh + h] = 0;
+    e->last_enc_slot = slot;
+    e->slot_frame[slot] = frame;
+    e->frames = frame + 1;
+    out->slot = slot;
+    out->reserved = 0;
+    out->frame = frame;
+    return VPE_OK;
+}
+
+int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    if (fh.slot < 0 || fh.slot >= e->S || fh.frame < 0 || fh.frame >= e->frames || fh.frame % e->S != fh.slot)
+        return e->fail(VPE_EINVAL, "feature handle was not produced by this engine");
+    Head& h = e->heads[head];
+    if (fh.frame % h.every_n != 0) { ++h.skips; return VPE_SKIPPED; }
+    if (e->slot_frame[fh.slot] != fh.frame) return e->fail(VPE_ESTALE, "slot has been reused by a later frame");
+    const int nh = (int)e->heads.size();
+    if (!e->host_only) {
+        hipStream_t s = stream ? (hipStream_t)stream : h.stream;
+        HIPCHK(e, hipStreamWaitEvent(s, e->ready[fh.slot], 0));
+        // the head's scratch and outputs are single-instance: order after its previous run
+        if (h.ran) HIPCHK(e, hipStreamWaitEvent(s, h.last_done, 0));
+        if (e->graphs) {
+            if (!h.graphs[fh.slot])
+                TRY(capture(*e, &h.graphs[fh.slot], [&](hipStream_t cs) { return enqueue_head_body(*e, h, fh.slot, cs); }));
+            HIPCHK(e, hipGraphLaunch(h.graphs[fh.slot], s));
+        } else {
+            TRY(enqueue_head_body(*e, h, fh.slot, s));
+        }
+        hipEvent_t ev = e->done[(size_t)fh.slot * nh + head];
+        HIPCHK(e, hipEventRecord(ev, s));
+        h.last_done = ev;
+    }
+    e->done_set[(size_t)fh.slot * nh + head] = 1;
+    h.ran = true;
+    ++h.runs;
+    return VPE_OK;
+}
+
+int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    if (every_n_frames < 1) return e->fail(VPE_EINVAL, "every_n_frames must be >= 1");
+    e->heads[head].every_n = every_n_frames;
+    return VPE_OK;
+}
+
+int vpe_feat_view(vpe_engine* e, vpe_feat fh, int tap, const void** dev_ptr, int64_t shape[3]) {
+    if (!e) return VPE_EINVAL;
+    if (tap < 0 || tap > 3 || !dev_ptr || !shape) return e->fail(VPE_EINVAL, "bad tap or null output");
+    if (fh.slot < 0 || fh.slot >= e->S || fh.frame < 0 || fh.frame >= e->frames || fh.frame % e->S != fh.slot)
+        return e->fail(VPE_EINVAL, "feature handle was not produced by this engine");
+    if (e->slot_frame[fh.slot] != fh.frame) return e->fail(VPE_ESTALE, "slot has been reused by a later frame");
+    *dev_ptr = e->host_only ? nullptr : e->feat[(size_t)fh.slot * 4 + tap];
+    shape[0] = e->B; shape[1] = e->N; shape[2] = e->D;
+    return VPE_OK;
+}
+
+int vpe_head_output(vpe_engine* e, int head, int which, const void** dev_ptr, int64_t shape[4]) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size() || !dev_ptr || !shape) return e->fail(VPE_EINVAL, "unknown head or null output");
+    const Head& h = e->heads[head];
+    shape[0] = e->B; shape[1] = shape[2] = shape[3] = 1;
+    if (h.kind == VPE_HEAD_SEG && which == 0) { *dev_ptr = h.logits; shape[1] = e->gh; shape[2] = e->gw; shape[3] = h.classes; }
+    else if (h.kind == VPE_HEAD_SEG && which == 1) { *dev_ptr = h.classmap; shape[1] = e->H; shape[2] = e->W; }
+    else if (h.kind == VPE_HEAD_DET && which == 0) { *dev_ptr = h.logits; shape[1] = e->gh; shape[2] = e->gw; shape[3] = h.classes + 4; }
+    else if (h.kind == VPE_HEAD_DET && which == 1) { *dev_ptr = h.classmap; shape[1] = e->gh; shape[2] = e->gw; }
+    else if (h.kind == VPE_HEAD_DEPTH && which == 0) { *dev_ptr = h.depth; shape[1] = e->H; shape[2] = e->W; }
+    else return e->fail(VPE_EINVAL, "this head has no such output");
+    return VPE_OK;
+}
+
+int vpe_sync(vpe_engine* e) {
+    if (!e) return VPE_EINVAL;
+    if (e->host_only) return VPE_OK;
+    HIPCHK(e, hipDeviceSynchronize());
+    return VPE_OK;
+}
+
+int vpe_stats(vpe_engine* e, int64_t* frames, int64_t* head_runs, int64_t* head_skips, int n) {
+    if (!e) return VPE_EINVAL;
+    if (frames) *frames = e->frames;
+    for (int i = 0; i < n && i < (int)e->heads.size(); ++i) {
+        if (head_runs) head_runs[i] = e->heads[i].runs;
+        if (head_skips) head_skips[i] = e->heads[i].skips;
+    }
+    return VPE_OK;
+}
+
+int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes) {
+    if (!e) return VPE_EINVAL;
+    if (e->host_only || reps < 1 || !ms_per_launch) return e->fail(VPE_EINVAL, "bad arguments");
+    hipStream_t s = e->enc_stream;
+    hipEvent_t t0, t1;
+    HIPCHK(e, hipEventCreate(&t0));
+    HIPCHK(e, hipEventCreate(&t1));
+    const int D = e->D, T = e->T, dt = e->bf;
+    double fl = 0.0, by = 0.0;
+    int launches = reps, rc = 0;
+    Head* dh = nullptr;
+    for (auto& h : e->heads) if (h.kind == VPE_HEAD_DEPTH) dh = &h;
+    auto body = [&](bool timed) -> int {
+        if (timed) HIPCHK(e, hipEventRecord(t0, s));
+        for (int i = 0; i < (timed ? reps : 1); ++i) {
+            if (which == 0) {
+                GemmArgs a = plain_gemm(e->u, D, e->blk[0].qkv_w, e->blk[0].qkv_b, T, 3 * D, D);
+                a.epi = EPI_QKV; a.out = e->qk; a.ldo = 2 * D; a.out2 = e->vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
+                HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
+            } else if (which == 1) {
+                AttnArgs a{e->qk, e->vt, e->att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f};
+                HIPCHK(e, launch_attention(dt, a, s));
+            } else if (which == 2) {
+                HIPCHK(e, launch_layernorm(dt, e->x, T, D, e->blk[0].ln1_g, e->blk[0].ln1_b, e->cfg.ln_eps, e->u, s));
+            } else {
+                // the three large 3x3 convolutions of the depth head (stages 1..3), same shapes and
+                // buffers as in a head run; timing does not depend on the values in z
+                for (int st = 1; st < 4; ++st) {
+                    const int hs = e->gh << st, wsz = e->gw << st;
+                    GemmArgs a = conv3_gemm(dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[st], dh->fuse_b[st], dh->ch);
+                    a.out = dh->r; a.ldo = dh->ch;
+                    HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
+                }
+            }
+        }
+        if (timed) HIPCHK(e, hipEventRecord(t1, s));
+        return 0;
+    };
+    if (which < 0 || which > 3 || (which == 3 && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
+    if (!rc) rc = body(false);   // warm-up launch
+    if (!rc) rc = body(true);
+    if (!rc && hipEventSynchronize(t1) != hipSuccess) rc = e->fail(VPE_EHIP, "hipEventSynchronize failed");
+    float ms = 0.0f;
+    if (!rc && hipEventElapsedTime(&ms, t0, t1) != hipSuccess) rc = e->fail(VPE_EHIP, "hipEventElapsedTime failed");
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (rc) return rc;
+    const double esz = e->esz;
+    if (which == 0) { fl = 2.0 * T * D * 3.0 * D; by = esz * ((double)T * D + 3.0 * D * D + 3.0 * T * D); }
+    else if (which == 1) { fl = 4.0 * e->B * (double)e->N * e->N * D; by = esz * 4.0 * T * D; }
+    else if (which == 2) { fl = 8.0 * T * D; by = (4.0 + esz) * T * D; }
+    else {
+        launches = 3 * reps;
+        const double ch = dh->ch, pix = (double)e->B * e->P * (4 + 16 + 64) / 3.0;   // mean over the three launches
+        fl = 2.0 * 9.0 * ch * ch * pix;
+        by = esz * (2.0 * pix * ch + 9.0 * ch * ch);
+    }
+    *ms_per_launch = ms / launches;
+    if (flops) *flops = fl;
+    if (bytes) *bytes = by;
+    return VPE_OK;
+}
+
+const char* vpe_last_error(vpe_engine* e) { return e ? e->err.c_str() : g_create_error.c_str(); }
+
+void vpe_destroy(vpe_engine* e) { destroy_engine(e); }
+
+}  // extern "C"

@@ -1,0 +1,31 @@
+// Host-callable launchers of the gfx950 kernels, one translation unit per kernel family so
+// the heavy MFMA templates compile in parallel.  dtype: 0 = fp32, 1 = bf16 (vpe_dtype).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attention.h"
+#include "gemm.h"
+
+namespace vpe {
+
+hipError_t launch_gemm(int dtype, const GemmArgs& a, int amode, hipStream_t s);
+hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s);
+
+hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const float* g, const float* b,
+                            float eps, void* y, hipStream_t s);
+hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
+                         const float* special, int nspecial, int ntok, int D, float* x, hipStream_t s);
+hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, int n_cols, int64_t rs,
+                           int64_t cs, int mode, int cin, int swiglu_half, int64_t dst_ld, int row_off,
+                           int col_off, hipStream_t s);
+hipError_t launch_rowdot(int dtype, const void* in, int64_t rows, int C, const float* w, float bias,
+                         float* out, hipStream_t s);
+hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint8_t* out, hipStream_t s);
+hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const void* r, int B, int Hs, int Ws,
+                                int C, void* z, hipStream_t s);
+hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw, int C, int H, int W,
+                                      uint8_t* cls, hipStream_t s);
+hipError_t launch_depth_output(const float* d, int B, int h8, int w8, int H, int W, float* depth, hipStream_t s);
+
+}  // namespace vpe

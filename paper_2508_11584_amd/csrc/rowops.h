@@ -1,0 +1,153 @@
+// Bandwidth-bound row kernels: LayerNorm, patch gathering (im2col), weight re-layout at
+// engine creation, per-pixel dot products and channel argmax.  All are coalesced along the
+// contiguous (channel) axis; one wavefront owns one row.
+#pragma once
+#include "common.h"
+
+namespace vpe {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// LayerNorm over the last axis of the fp32 residual stream: y = g (x - mean) / sqrt(var + eps) + b
+// with the biased variance; statistics in fp32 (mean first, then centred second moment, both
+// from registers).  One wave per row, 4 rows per workgroup.  D multiple of 64, D <= 64 * 32.
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, int rows, int D,
+                                                        const float* __restrict__ gam,
+                                                        const float* __restrict__ bet, float eps,
+                                                        T* __restrict__ y) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    constexpr int MAXV = 16;                     // float2 per lane -> D <= 2048
+    const int nv = D >> 7;                       // full float2 passes (128 elements each)
+    const bool tail = (D & 64) != 0;             // one extra pass of single floats
+    const float* xr = x + (int64_t)row * D;
+    f32x2 v[MAXV];
+    float t = 0.0f, sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i)
+        if (i < nv) {
+            v[i] = *reinterpret_cast<const f32x2*>(xr + i * 128 + 2 * lane);
+            sum += v[i][0] + v[i][1];
+        }
+    if (tail) { t = xr[nv * 128 + lane]; sum += t; }
+    const float mean = wave_sum(sum) / D;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i)
+        if (i < nv) {
+            const float a = v[i][0] - mean, b = v[i][1] - mean;
+            sq += a * a + b * b;
+        }
+    if (tail) sq += (t - mean) * (t - mean);
+    const float rstd = 1.0f / sqrtf(wave_sum(sq) / D + eps);
+    T* yr = y + (int64_t)row * D;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i)
+        if (i < nv) {
+            const int c = i * 128 + 2 * lane;
+            const f32x2 gg = *reinterpret_cast<const f32x2*>(gam + c);
+            const f32x2 bb = *reinterpret_cast<const f32x2*>(bet + c);
+            yr[c] = from_f32<T>(gg[0] * (v[i][0] - mean) * rstd + bb[0]);
+            yr[c + 1] = from_f32<T>(gg[1] * (v[i][1] - mean) * rstd + bb[1]);
+        }
+    if (tail) {
+        const int c = nv * 128 + lane;
+        yr[c] = from_f32<T>(gam[c] * (t - mean) * rstd + bet[c]);
+    }
+}
+
+// Patch gathering for the 14x14 stride-14 embedding: row (b, p) of `cols` receives the 588
+// pixels of patch p in (channel, row, column) order, zero-padded to kpad columns.  The same
+// launch also fills the non-patch rows of the residual stream (CLS + pos[0], then registers)
+// from the `special` table [1 + R][D].  blocks [0, B*P) gather; the rest write special rows.
+template <typename T>
+__global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ img, int B, int H, int W,
+                                                     int kpad, T* __restrict__ cols,
+                                                     const float* __restrict__ special, int nspecial,
+                                                     int ntok, int D, float* __restrict__ x) {
+    const int gw = W / 14, P = (H / 14) * gw;
+    int blk = blockIdx.x;
+    if (blk < B * P) {
+        const int b = blk / P, p = blk % P, pi = p / gw, pj = p % gw;
+        const float* src = img + (int64_t)b * 3 * H * W;
+        for (int k = threadIdx.x; k < kpad; k += 256) {
+            float v = 0.0f;
+            if (k < 588) {
+                const int c = k / 196, u = (k % 196) / 14, w = k % 14;
+                v = src[((int64_t)c * H + pi * 14 + u) * W + pj * 14 + w];
+            }
+            cols[(int64_t)blk * kpad + k] = from_f32<T>(v);
+        }
+    } else {
+        blk -= B * P;
+        const int b = blk / nspecial, r = blk % nspecial;
+        for (int d = threadIdx.x; d < D; d += 256) x[((int64_t)b * ntok + r) * D + d] = special[(int64_t)r * D + d];
+    }
+}
+
+// Weight re-layout at engine creation: dst[(row_off + n)][col_off + k] = src element (n, k).
+//   mode 0: src index = n * rs + k * cs                       (any strided 2-D view)
+//   mode 1: src is a conv kernel [n][cin][3][3]; k = tap * cin + ci -> src[(n * cin + ci) * 9 + tap]
+//   swiglu != 0: physical row n reads logical row  32 (n / 64) + n % 64          if n % 64 < 32
+//                                                  half + 32 (n / 64) + n % 64 - 32   otherwise
+template <typename T>
+__global__ __launch_bounds__(256) void relayout_kernel(const float* __restrict__ src, T* __restrict__ dst,
+                                                       int n_rows, int n_cols, int64_t rs, int64_t cs,
+                                                       int mode, int cin, int swiglu_half, int64_t dst_ld,
+                                                       int row_off, int col_off) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)n_rows * n_cols) return;
+    const int n = (int)(idx / n_cols), k = (int)(idx % n_cols);
+    int nl = n;
+    if (swiglu_half) {
+        const int grp = n >> 6, j = n & 63;
+        nl = j < 32 ? 32 * grp + j : swiglu_half + 32 * grp + j - 32;
+    }
+    int64_t si;
+    if (mode == 0) si = nl * rs + k * cs;
+    else {
+        const int tap = k / cin, ci = k % cin;
+        si = ((int64_t)nl * cin + ci) * 9 + tap;
+    }
+    dst[(int64_t)(row_off + n) * dst_ld + col_off + k] = from_f32<T>(src[si]);
+}
+
+// out[r] = bias + sum_c in[r][c] * w[c]: the depth head's 1-channel projection, one wave per pixel.
+template <typename T>
+__global__ __launch_bounds__(256) void rowdot_kernel(const T* __restrict__ in, int64_t rows, int C,
+                                                     const float* __restrict__ w, float bias,
+                                                     float* __restrict__ out) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    const T* r = in + row * C;
+    float acc = 0.0f;
+    for (int c = lane * 4; c < C; c += 256) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc += to_f32(r[c + i]) * w[c + i];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) out[row] = acc + bias;
+}
+
+// Per-row argmax over the first C of `ld` fp32 values (ties -> lowest index); one thread per row.
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ in, int64_t rows, int C,
+                                                          int ld, uint8_t* __restrict__ out) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    const float* p = in + r * ld;
+    int best = 0;
+    float bv = p[0];
+    for (int c = 1; c < C; ++c) {
+        const float v = p[c];
+        if (v > bv) { bv = v; best = c; }
+    }
+    out[r] = (uint8_t)best;
+}
+
+}  // namespace vpe

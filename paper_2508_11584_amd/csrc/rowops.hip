@@ -1,0 +1,72 @@
+// Launchers of the bandwidth-bound kernels (LayerNorm, im2col, re-layout, resampling, argmax).
+#include "kernels.h"
+#include "resize.h"
+#include "rowops.h"
+
+namespace vpe {
+
+static inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const float* g, const float* b,
+                            float eps, void* y, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    if (dtype) hipLaunchKernelGGL(layernorm_kernel<bf16>, dim3(blocks_for(rows, 4)), dim3(256), 0, s, x, rows, D, g, b, eps, (bf16*)y);
+    else hipLaunchKernelGGL(layernorm_kernel<float>, dim3(blocks_for(rows, 4)), dim3(256), 0, s, x, rows, D, g, b, eps, (float*)y);
+    return hipGetLastError();
+}
+
+hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
+                         const float* special, int nspecial, int ntok, int D, float* x, hipStream_t s) {
+    const int P = (H / 14) * (W / 14);
+    const unsigned nb = (unsigned)(B * P + B * nspecial);
+    if (dtype) hipLaunchKernelGGL(im2col_kernel<bf16>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (bf16*)cols, special, nspecial, ntok, D, x);
+    else hipLaunchKernelGGL(im2col_kernel<float>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (float*)cols, special, nspecial, ntok, D, x);
+    return hipGetLastError();
+}
+
+hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, int n_cols, int64_t rs,
+                           int64_t cs, int mode, int cin, int swiglu_half, int64_t dst_ld, int row_off,
+                           int col_off, hipStream_t s) {
+    const int64_t n = (int64_t)n_rows * n_cols;
+    if (n <= 0) return hipSuccess;
+    if (dtype) hipLaunchKernelGGL(relayout_kernel<bf16>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, (bf16*)dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off, col_off);
+    else hipLaunchKernelGGL(relayout_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, (float*)dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off, col_off);
+    return hipGetLastError();
+}
+
+hipError_t launch_rowdot(int dtype, const void* in, int64_t rows, int C, const float* w, float bias,
+                         float* out, hipStream_t s) {
+    if (dtype) hipLaunchKernelGGL(rowdot_kernel<bf16>, dim3(blocks_for(rows, 4)), dim3(256), 0, s, (const bf16*)in, rows, C, w, bias, out);
+    else hipLaunchKernelGGL(rowdot_kernel<float>, dim3(blocks_for(rows, 4)), dim3(256), 0, s, (const float*)in, rows, C, w, bias, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint8_t* out, hipStream_t s) {
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(blocks_for(rows, 256)), dim3(256), 0, s, in, rows, C, ld, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const void* r, int B, int Hs, int Ws,
+                                int C, void* z, hipStream_t s) {
+    if (dtype) {
+        const int64_t n = (int64_t)B * Hs * Ws * (C / 8);
+        hipLaunchKernelGGL(fuse_upsample_kernel<bf16>, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const bf16*)p, gh, gw, (const bf16*)r, B, Hs, Ws, C, (bf16*)z);
+    } else {
+        const int64_t n = (int64_t)B * Hs * Ws * (C / 4);
+        hipLaunchKernelGGL(fuse_upsample_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const float*)p, gh, gw, (const float*)r, B, Hs, Ws, C, (float*)z);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw, int C, int H, int W,
+                                      uint8_t* cls, hipStream_t s) {
+    hipLaunchKernelGGL(seg_upsample_argmax_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, logits, B, gh, gw, C, H, W, cls);
+    return hipGetLastError();
+}
+
+hipError_t launch_depth_output(const float* d, int B, int h8, int w8, int H, int W, float* depth, hipStream_t s) {
+    hipLaunchKernelGGL(depth_output_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, d, B, h8, w8, H, W, depth);
+    return hipGetLastError();
+}
+
+}  // namespace vpe

@@ -1,0 +1,167 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, validates
+configurations, and its host-side scheduling logic (slot ring, rates, staleness, counters)
+behaves as the header says.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2508_11584_amd as vpe
+import vpe_inputs as vi
+from helpers import make_engine
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "vpe.h")).read()
+    names = set(re.findall(r"\b(vpe_[a-z_]+)\s*\(", hdr))
+    assert {"vpe_create", "vpe_encode", "vpe_run_head", "vpe_set_head_rate"} <= names
+    L = vpe.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+def test_product_does_not_import_the_oracle():
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2508_11584_amd")):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in txt, os.path.join(dirpath, f)
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            assert "paper_2508_11584_amd" not in open(os.path.join(ROOT, "oracle", f)).read()
+
+
+def _cfg(spec, blob, **over):
+    c = vpe.binding.vpe_backbone_cfg()
+    c.dim, c.depth, c.heads, c.mlp_hidden, c.mlp_kind = spec.dim, spec.depth, spec.heads, spec.mlp_hidden, spec.mlp_kind
+    c.registers, c.img_h, c.img_w, c.batch, c.dtype = spec.registers, spec.img_h, spec.img_w, spec.batch, 1
+    c.taps = (C.c_int32 * 4)(*spec.taps)
+    c.ring_slots, c.flags, c.ln_eps = 2, vpe.VPE_FLAG_HOST_ONLY, 1e-6
+    c.weights, c.weights_bytes = blob.ctypes.data, blob.nbytes
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+@pytest.mark.parametrize("over,needle", [
+    (dict(dim=100), "heads * 64"), (dict(img_h=57), "multiples of 14"), (dict(ring_slots=0), "ring_slots"),
+    (dict(batch=0), "batch"), (dict(depth=0), "depth"), (dict(mlp_kind=7), "mlp_kind"), (dict(dtype=3), "dtype"),
+    (dict(weights_bytes=16), "weights_bytes"), (dict(ln_eps=0.0), "ln_eps"),
+    (dict(taps=(C.c_int32 * 4)(1, 2, 2, 4)), "increasing"), (dict(depth=5), "taps[3]"),
+])
+def test_invalid_configurations_are_rejected_before_touching_the_device(over, needle):
+    spec = vi.small_spec()
+    blob = vi.pack_backbone(spec, vi.make_backbone_weights(spec, 1))
+    c = _cfg(spec, blob, **over)
+    with pytest.raises(vpe.VpeError) as ei:
+        vpe.vpe_create(c, None, 0, None, 0)
+    assert ei.value.code == vpe.VPE_EINVAL and needle in str(ei.value)
+    with pytest.raises(vpe.VpeError):
+        vpe.vpe_workspace_bytes(c, None, 0)
+
+
+def test_invalid_heads_are_rejected():
+    spec = vi.small_spec()
+    blob = vi.pack_backbone(spec, vi.make_backbone_weights(spec, 1))
+    c = _cfg(spec, blob)
+    h = (vpe.binding.vpe_head_cfg * 1)()
+    hb = vi.pack_head(spec, vi.HEAD_SEG, vi.make_head_weights(spec, vi.HEAD_SEG, 1))
+    h[0].kind, h[0].classes, h[0].every_n, h[0].weights, h[0].weights_bytes = 0, spec.seg_classes, 0, hb.ctypes.data, hb.nbytes
+    with pytest.raises(vpe.VpeError, match="every_n"):
+        vpe.vpe_create(c, h, 1, None, 0)
+    h[0].every_n, h[0].classes = 1, 300
+    with pytest.raises(vpe.VpeError, match="classes"):
+        vpe.vpe_create(c, h, 1, None, 0)
+    h[0].classes, h[0].weights_bytes = spec.seg_classes, hb.nbytes - 4
+    with pytest.raises(vpe.VpeError, match="weights_bytes"):
+        vpe.vpe_create(c, h, 1, None, 0)
+
+
+def test_workspace_bytes_accounts_for_ring_and_grows_with_slots():
+    spec = vi.small_spec()
+    blob = vi.pack_backbone(spec, vi.make_backbone_weights(spec, 1))
+    a = vpe.vpe_workspace_bytes(_cfg(spec, blob, ring_slots=1), None, 0)
+    b = vpe.vpe_workspace_bytes(_cfg(spec, blob, ring_slots=3), None, 0)
+    slot = 4 * spec.batch * spec.tokens * spec.dim * 2
+    assert b - a >= 2 * slot and b - a < 2 * slot + 8 * 256 * 2
+    assert a > blob.nbytes // 2      # bf16 weights alone
+
+
+def test_rate_divider_counts_are_exact_over_300_frames():
+    # the paper's rate-limiting experiment (300 frames, several rates) made deterministic:
+    # every_n = 1, 2, 3 must give exactly 300 / 150 / 100 executions
+    eng, _, _ = make_engine(vi.small_spec(), 1, every_n=(1, 2, 3), flags=vpe.VPE_FLAG_HOST_ONLY)
+    for f in range(300):
+        fh = eng.encode(None)
+        assert fh.frame == f and fh.slot == f % 2
+        rcs = [eng.run_head(h, fh) for h in range(3)]
+        assert rcs == [0, 0 if f % 2 == 0 else 1, 0 if f % 3 == 0 else 1]
+    frames, runs, skips = eng.stats()
+    assert frames == 300 and runs == [300, 150, 100] and skips == [0, 150, 200]
+
+
+def test_rate_can_change_at_run_time():
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg",), flags=vpe.VPE_FLAG_HOST_ONLY)
+    ran = []
+    for f in range(60):
+        if f == 20:
+            eng.set_head_rate(0, 5)
+        if f == 40:
+            eng.set_head_rate(0, 2)
+        ran.append(eng.run_head(0, eng.encode(None)) == 0)
+    expect = [True] * 20 + [f % 5 == 0 for f in range(20, 40)] + [f % 2 == 0 for f in range(40, 60)]
+    assert ran == expect
+    with pytest.raises(vpe.VpeError, match="every_n"):
+        eng.set_head_rate(0, 0)
+    with pytest.raises(vpe.VpeError, match="unknown head"):
+        eng.set_head_rate(3, 1)
+
+
+def test_ring_overwrites_oldest_and_stale_handles_are_refused():
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg",), ring_slots=2, flags=vpe.VPE_FLAG_HOST_ONLY)
+    f0, f1 = eng.encode(None), eng.encode(None)
+    assert (f0.slot, f1.slot) == (0, 1)
+    assert eng.run_head(0, f0) == 0 and eng.run_head(0, f1) == 0      # both still resident
+    f2 = eng.encode(None)                                            # reuses slot 0: frame 0 is gone
+    assert f2.slot == 0
+    with pytest.raises(vpe.VpeError) as ei:
+        eng.run_head(0, f0)
+    assert ei.value.code == vpe.VPE_ESTALE
+    with pytest.raises(vpe.VpeError) as ei:
+        vpe.vpe_feat_view(eng.handle, f0, 3)
+    assert ei.value.code == vpe.VPE_ESTALE
+    assert eng.run_head(0, f1) == 0 and eng.run_head(0, f2) == 0
+    bogus = vpe.binding.vpe_feat(slot=1, reserved=0, frame=2)         # frame 2 lives in slot 0
+    with pytest.raises(vpe.VpeError, match="not produced"):
+        eng.run_head(0, bogus)
+    future = vpe.binding.vpe_feat(slot=1, reserved=0, frame=7)
+    with pytest.raises(vpe.VpeError, match="not produced"):
+        eng.run_head(0, future)
+
+
+def test_feature_and_output_shapes():
+    spec = vi.small_spec(registers=2, batch=2)
+    eng, _, _ = make_engine(spec, 1, flags=vpe.VPE_FLAG_HOST_ONLY)
+    fh = eng.encode(None)
+    _, shape = vpe.vpe_feat_view(eng.handle, fh, 0)
+    assert shape == (2, spec.tokens, spec.dim)
+    assert vpe.vpe_head_output(eng.handle, 0, 0)[1] == (2, spec.gh, spec.gw, spec.seg_classes)
+    assert vpe.vpe_head_output(eng.handle, 0, 1)[1] == (2, spec.img_h, spec.img_w, 1)
+    assert vpe.vpe_head_output(eng.handle, 1, 0)[1] == (2, spec.img_h, spec.img_w, 1)
+    assert vpe.vpe_head_output(eng.handle, 2, 0)[1] == (2, spec.gh, spec.gw, spec.det_classes + 4)
+    assert vpe.vpe_head_output(eng.handle, 2, 1)[1] == (2, spec.gh, spec.gw, 1)
+    with pytest.raises(vpe.VpeError):
+        vpe.vpe_head_output(eng.handle, 1, 1)
+
+
+def test_create_without_a_device_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(vpe.VpeError) as ei:
+        make_engine(vi.small_spec(), 1, kinds=("seg",), torch_workspace=False)
+    assert ei.value.code in (vpe.VPE_ENOMEM, vpe.VPE_EHIP)
