@@ -1,0 +1,139 @@
+"""Benchmark of the hot path on one MI355X: ViT-S/14 bf16 at 476x630 with three heads.
+
+One step = one frame through the whole path: vpe_encode (backbone, written once into the
+shared feature slot) + the seg, depth and det heads reading that slot in place on their own
+streams.  Inputs are synthetic and already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def backbone_flops(spec) -> float:
+    """Algorithmic FLOP of one encoder pass: patch embedding + per block QKV, attention (4 N^2 D,
+    no causal discount), out-projection and MLP.  LayerNorm / activation work is not counted."""
+    B, P, N, D, T = spec.batch, spec.patches, spec.tokens, spec.dim, spec.batch * spec.tokens
+    per_block = 2.0 * T * D * 3 * D + 4.0 * B * N * N * D + 2.0 * T * D * D + 2.0 * T * D * spec.fc1_out \
+        + 2.0 * T * spec.mlp_hidden * D
+    return 2.0 * B * P * 588 * D + spec.depth * per_block
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload)")
+    ap.add_argument("--no-graphs", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-reps", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2508_11584_amd as vpe
+    import vpe_inputs as vi
+    from helpers import make_engine
+
+    spec = vi.CONFIGS[args.config]
+    wseed, iseed = vi.SEEDS[args.config]
+    kinds = ("seg",) if args.config == "cfg1" else ("seg", "depth", "det")
+    flags = 0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS
+    eng, w, hw = make_engine(spec, wseed, kinds=kinds, ring_slots=2, flags=flags)
+    images_np = vi.make_batch(spec, iseed)
+    # two distinct resident frames, alternated, so no step can reuse the previous step's result
+    frames = [torch.from_numpy(images_np).cuda(), torch.from_numpy(np.ascontiguousarray(images_np[..., ::-1])).cuda()]
+    nh = len(kinds)
+
+    def shared_step(i):
+        fh = eng.encode(frames[i & 1])
+        for h in range(nh):
+            eng.run_head(h, fh)
+
+    one = torch.cuda.Stream()
+
+    def sequential_step(i):
+        # baseline: every head recomputes its own backbone pass, all on one stream
+        for h in range(nh):
+            fh = eng.encode(frames[i & 1], stream=one)
+            eng.run_head(h, fh, stream=one)
+
+    def encode_step(i):
+        eng.encode(frames[i & 1])
+
+    def timed(fn, steps, warmup):
+        for i in range(warmup):
+            fn(i)
+        eng.sync()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        eng.sync()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    t_shared = timed(shared_step, args.steps, args.warmup)
+    t_seq = timed(sequential_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
+    t_enc = timed(encode_step, args.steps, args.warmup)
+    fps = spec.batch / t_shared
+    bb_tflops = backbone_flops(spec) / t_enc / 1e12
+
+    # roofline of the dominant kernel: the depth head's 3x3 convolutions (implicit GEMM on MFMA),
+    # timed with HIP events on the stream they are launched on
+    roofline = None
+    kern = {}
+    shared_step(0)
+    eng.sync()
+    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm")) + (((3, "depth_conv3x3"),) if "depth" in kinds else ()):
+        ms, fl, by = eng.time_kernel(which, args.kernel_reps)
+        kern[name] = {"us": round(ms * 1e3, 2), "tflops": round(fl / ms / 1e9, 2), "gbps": round(by / ms / 1e6, 1)}
+        if name == "depth_conv3x3" or (name == "qkv_gemm" and "depth" not in kinds):
+            peak = MFMA_PEAK_TFLOPS[spec.dtype]
+            ach = fl / (ms * 1e-3) / 1e12
+            roofline = {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
+                        "frac": round(ach / peak, 4), "traffic": None, "us_per_launch": round(ms * 1e3, 2)}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on this machine's host cores: one frame (batch element 0) of the same workload
+        from oracle import model, ops
+        t0 = time.perf_counter()
+        feats = model.encode_image(spec, w, images_np[0])
+        for k, hwd in zip(kinds, hw):
+            {"seg": model.seg_head, "depth": model.depth_head, "det": model.det_head}[k](spec, hwd, feats)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": round(1.0 / dt, 5), "unit": "frames/s", "cores": ops.num_threads(), "kind": "oracle",
+                        "sample": f"1 frame (batch element 0) of {spec.name}, encoder + {nh} head(s), {dt:.1f} s"}
+
+    out = {
+        "metric": "end-to-end frames/sec (backbone+3 heads), ViT-S/14 476x630; backbone TFLOP/s",
+        "value": round(fps, 2), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t_shared * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": spec.name, "batch": spec.batch, "img": [spec.img_h, spec.img_w], "tokens": spec.tokens,
+                   "heads": list(kinds), "ring_slots": 2, "hip_graphs": not args.no_graphs},
+        "backbone_tflops": round(bb_tflops, 2), "backbone_ms": round(t_enc * 1e3, 4),
+        "backbone_mfma_frac": round(bb_tflops / MFMA_PEAK_TFLOPS[spec.dtype], 4),
+        "sequential_baseline_fps": round(spec.batch / t_seq, 2), "shared_vs_sequential": round(t_seq / t_shared, 3),
+        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+    eng.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -79,6 +79,81 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb) {
     return xcd * base + (xcd < rem ? xcd : rem) + idx;
 }
 
+// 8 consecutive values of T (16 bytes of bf16, 32 bytes of fp32) to global memory.
+__device__ __forceinline__ void store8(bf16* dst, const float* v) {
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (bf16)v[i];
+    *reinterpret_cast<bf16x8*>(dst) = o;
+}
+__device__ __forceinline__ void store8(float* dst, const float* v) {
+    *reinterpret_cast<f32x4*>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{v[4], v[5], v[6], v[7]};
+}
+
+// Epilogue of one row chunk: columns c .. c + 7 of logical row r (r < M, c < N, c % 8 == 0), the raw
+// accumulators in v.  Full, aligned chunks go out as 16-byte stores; ragged ones element by element.
+template <typename T>
+__device__ __forceinline__ void epilogue_chunk(const GemmArgs& p, int r, int c, float* v) {
+    const int nv = p.N - c < 8 ? p.N - c : 8;
+    if (p.bias) {
+        if (nv == 8) {
+            const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + c), b1 = *reinterpret_cast<const f32x4*>(p.bias + c + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[i] += b0[i]; v[4 + i] += b1[i]; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) if (i < nv) v[i] += p.bias[c + i];
+        }
+    }
+    if (p.epi == EPI_STORE) {
+        if (p.act == ACT_RELU) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = fmaxf(v[i], 0.0f);
+        } else if (p.act == ACT_GELU) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = gelu_erf(v[i]);
+        }
+        const int64_t orow = (int64_t)(r / p.o_rpi) * p.o_istride + p.o_off + r % p.o_rpi;
+        if (p.out_f32) {
+            float* dst = reinterpret_cast<float*>(p.out) + orow * p.ldo + c;
+            if (nv == 8 && (p.ldo & 3) == 0) store8(dst, v);
+            else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) if (i < nv) dst[i] = v[i];
+            }
+        } else {
+            T* dst = reinterpret_cast<T*>(p.out) + orow * p.ldo + c;
+            if (nv == 8 && (p.ldo & 7) == 0) store8(dst, v);
+            else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) if (i < nv) dst[i] = from_f32<T>(v[i]);
+            }
+        }
+    } else if (p.epi == EPI_RESID || p.epi == EPI_PATCH) {
+        // fp32 residual stream, N = ldo = model width (multiple of 64): always full aligned chunks
+        int64_t orow = r;
+        if (p.epi == EPI_PATCH) {
+            const int b = r / p.o_rpi, pp = r % p.o_rpi;
+            orow = (int64_t)b * p.o_istride + p.o_off + pp;
+            const float* ps = p.pos + (int64_t)pp * p.N + c;
+            const f32x4 p0 = *reinterpret_cast<const f32x4*>(ps), p1 = *reinterpret_cast<const f32x4*>(ps + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[i] += p0[i]; v[4 + i] += p1[i]; }
+        }
+        float* x = reinterpret_cast<float*>(p.out) + orow * p.ldo + c;
+        if (p.epi == EPI_RESID) {
+            const f32x4 g0 = *reinterpret_cast<const f32x4*>(p.gamma + c), g1 = *reinterpret_cast<const f32x4*>(p.gamma + c + 4);
+            const f32x4 x0 = *reinterpret_cast<const f32x4*>(x), x1 = *reinterpret_cast<const f32x4*>(x + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[i] = x0[i] + g0[i] * v[i]; v[4 + i] = x1[i] + g1[i] * v[4 + i]; }
+        }
+        store8(x, v);
+    } else {   // EPI_QKV, query / key columns
+        store8(reinterpret_cast<T*>(p.out) + (int64_t)r * p.ldo + c, v);
+    }
+}
+
 template <typename T, int BM, int BN, int WGM, int WGN, int AMODE>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs p) {
     constexpr int NT = 64 * WGM * WGN;
@@ -195,69 +270,83 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs p) 
     }
 
     // ---------------------------------------------------------------- epilogue
-    // accumulator element v of lane (g, li) in block (i, j):
-    //   row = 32 i + 8 (v / 4) + 4 g + v % 4,  col = 32 j + li
-    const int rbase = m0 + wm * WM + 4 * g;
-    const int cbase = n0 + wn * WN + li;
+    // The accumulators go through LDS (free after the k loop) as a row-major fp32 tile, so that
+    // each thread then owns 8 consecutive columns of a row: one row-index computation and
+    // 16-byte coalesced global accesses per chunk instead of 64 scattered 2-byte stores per lane.
+    // accumulator element v of lane (g, li) in block (i, j): row = 32 i + 8 (v / 4) + 4 g + v % 4, col = 32 j + li
+    static_assert(BM * BN * 4 <= 2 * STAGE, "accumulator tile must fit the stage buffers");
+    float* sC = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                sC[(wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * BN + wn * WN + j * 32 + li] = acc[i][j][v];
+    __syncthreads();
+
     if (p.epi == EPI_SWIGLU) {
-        // physical columns come in groups of 64: 32 gate columns then their 32 linear partners
-        if constexpr (NI % 2 == 0) {
+        // physical columns come in groups of 64: 32 gate columns, then their 32 linear partners;
+        // a thread takes 8 gate columns and their partners and writes 8 hidden units
+        constexpr int CG = BN / 16, RPASS = NT / CG;
+        const int cg = tid % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
+        const int ca = n0 + grp * 64 + j0;            // physical gate column
+        if (ca + 40 <= p.N) {
+            const int oc = (ca >> 6) * 32 + j0;       // hidden unit index
             T* out = reinterpret_cast<T*>(p.out);
+            for (int rr = tid / CG; rr < BM; rr += RPASS) {
+                const int r = m0 + rr;
+                if (r >= p.M) break;
+                const float* src = sC + rr * BN + grp * 64 + j0;
+                float h[8];
 #pragma unroll
-            for (int j = 0; j < NI; j += 2) {
-                const int ca = cbase + j * 32, cb = ca + 32;
-                if (cb >= p.N) continue;
-                const float ba = p.bias[ca], bb = p.bias[cb];
-                const int oc = (ca >> 6) * 32 + li;
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int r = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
-                        if (r >= p.M) continue;
-                        const float a = acc[i][j][v] + ba, b = acc[i][j + 1][v] + bb;
-                        out[(int64_t)r * p.ldo + oc] = from_f32<T>(a / (1.0f + __expf(-a)) * b);
-                    }
+                for (int i = 0; i < 8; ++i) {
+                    const float a = src[i] + p.bias[ca + i], b = src[32 + i] + p.bias[ca + 32 + i];
+                    h[i] = a / (1.0f + __expf(-a)) * b;
+                }
+                store8(out + (int64_t)r * p.ldo + oc, h);
             }
         }
         return;
     }
+    if (p.epi == EPI_QKV && n0 >= 2 * p.dim) {
+        // value columns: written transposed, vt[(b dim + c)][token]; a thread takes one column and 8 tokens
+        constexpr int RG = NT / BN;
+        const int cc = tid % BN, c2 = n0 + cc - 2 * p.dim;
+        T* vt = reinterpret_cast<T*>(p.out2);
+        const float bias = p.bias[n0 + cc];
+        for (int rr = (tid / BN) * 8; rr < BM; rr += RG * 8) {
+            const int r = m0 + rr;
+            if (r >= p.M) break;
+            float v[8];
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int c = cbase + j * 32;
-        if (c >= p.N) continue;
-        const float bias = p.bias ? p.bias[c] : 0.0f;
-        const float gam = p.epi == EPI_RESID ? p.gamma[c] : 0.0f;
+            for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * BN + cc] + bias;
+            const int b = r / p.ntok, n = r % p.ntok;
+            if (n + 8 <= p.ntok && (n & 7) == 0) {
+                store8(vt + ((int64_t)b * p.dim + c2) * p.npad + n, v);
+            } else {
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
-                if (r >= p.M) continue;
-                float val = acc[i][j][v] + bias;
-                if (p.epi == EPI_STORE) {
-                    if (p.act == ACT_RELU) val = fmaxf(val, 0.0f);
-                    else if (p.act == ACT_GELU) val = gelu_erf(val);
-                    const int64_t orow = (int64_t)(r / p.o_rpi) * p.o_istride + p.o_off + r % p.o_rpi;
-                    if (p.out_f32) reinterpret_cast<float*>(p.out)[orow * p.ldo + c] = val;
-                    else reinterpret_cast<T*>(p.out)[orow * p.ldo + c] = from_f32<T>(val);
-                } else if (p.epi == EPI_RESID) {
-                    float* x = reinterpret_cast<float*>(p.out) + (int64_t)r * p.ldo + c;
-                    *x = *x + gam * val;
-                } else if (p.epi == EPI_PATCH) {
-                    const int b = r / p.o_rpi, pp = r % p.o_rpi;
-                    const int64_t orow = (int64_t)b * p.o_istride + p.o_off + pp;
-                    reinterpret_cast<float*>(p.out)[orow * p.ldo + c] = val + p.pos[(int64_t)pp * p.N + c];
-                } else {   // EPI_QKV
-                    if (c < 2 * p.dim) {
-                        reinterpret_cast<T*>(p.out)[(int64_t)r * p.ldo + c] = from_f32<T>(val);
-                    } else {
-                        const int b = r / p.ntok, n = r % p.ntok;
-                        reinterpret_cast<T*>(p.out2)[((int64_t)b * p.dim + (c - 2 * p.dim)) * p.npad + n] =
-                            from_f32<T>(val);
-                    }
+                for (int k = 0; k < 8; ++k) {
+                    const int rk = r + k;
+                    if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
                 }
             }
+        }
+        return;
+    }
+    {
+        constexpr int CG = BN / 8, RPASS = NT / CG;
+        const int cg = tid % CG, c = n0 + cg * 8;
+        if (c < p.N) {
+            for (int rr = tid / CG; rr < BM; rr += RPASS) {
+                const int r = m0 + rr;
+                if (r >= p.M) break;
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8 + 4);
+                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                epilogue_chunk<T>(p, r, c, v);
+            }
+        }
     }
 }
 
