@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libvpe.so")
 OBJ = os.path.join(HERE, "_build")
-UNITS = ["engine", "gemm_bf16", "gemm_f32", "attention", "rowops"]
+UNITS = ["engine", "gemm_bf16", "gemm_dma", "gemm_f32", "attention", "rowops"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", f"-I{INCLUDE}", f"-I{CSRC}"]
 

@@ -96,149 +96,219 @@ template <> struct AttnMma<float> {
     }
 };
 
-template <typename T, int NW>
-__global__ __launch_bounds__(64 * NW) void attention_kernel(const AttnArgs p) {
-    constexpr int NT = 64 * NW;
+// Workgroup shape: QW x KW waves.  Wave (qw, kw) owns QB blocks of 32 queries (query group qw) and
+// the key tiles t with t % KW == kw.  Each iteration stages KW key tiles and KW value tiles in LDS,
+// loaded by all threads; waves of the same kw share their tile across query groups.  At the end
+// the KW partial results of a query group are merged in LDS by its kw = 0 wave (fixed order, so
+// results are deterministic).  KW > 1 gives small problems enough waves to fill 1024 SIMDs;
+// QW > 1 and QB = 2 cut the L2 -> LDS traffic per query on large ones.
+template <typename T, int QB, int QW, int KW>
+__global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs p) {
+    constexpr int NW = QW * KW, NT = 64 * NW;
     constexpr int CE = Elem<T>::CE;
     constexpr int CPR = 64 / CE;                 // 16-byte chunks per 64-element row
     constexpr int ROWB = AttnMma<T>::ROWB;
     constexpr int TILE = 64 * ROWB;
-    constexpr int RPP = NT / CPR;                // rows loaded per pass
-    constexpr int IT = 64 / RPP;
-    static_assert(64 % RPP == 0, "loader pass must divide the tile");
-    __shared__ __attribute__((aligned(16))) char smem[2 * TILE];
-    char* sK = smem;
-    char* sV = smem + TILE;
+    constexpr int CH = KW * 2 * 64 * CPR / NT;   // chunks per thread per iteration
+    static_assert((KW * 2 * 64 * CPR) % NT == 0 && NT % CPR == 0, "loader mapping");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qw = wave % QW, kw = wave / QW;
     const int g = lane >> 5, li = lane & 31;
     const int bh = blockIdx.y, b = bh / p.heads, h = bh % p.heads;
-    const int q0 = blockIdx.x * (32 * NW) + wave * 32;
+    const int q0 = blockIdx.x * (32 * QB * QW) + qw * 32 * QB;
     const int ld = 2 * p.dim;
 
     const T* __restrict__ qk = reinterpret_cast<const T*>(p.qk) + (int64_t)b * p.N * ld + h * 64;
     const T* __restrict__ kbase = qk + p.dim;
     const T* __restrict__ vt = reinterpret_cast<const T*>(p.vt) + ((int64_t)b * p.dim + h * 64) * p.npad;
 
-    typename AttnMma<T>::QFrag q[4];
-    {
-        const int qi = q0 + li;
+    typename AttnMma<T>::QFrag q[QB][4];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int qi = q0 + qb * 32 + li;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            q[ks] = qi < p.N ? AttnMma<T>::load_q(qk + (int64_t)qi * ld, ks, g) : AttnMma<T>::zero_q();
+            q[qb][ks] = qi < p.N ? AttnMma<T>::load_q(qk + (int64_t)qi * ld, ks, g) : AttnMma<T>::zero_q();
     }
 
-    f32x16 o[2];
+    f32x16 o[QB][2];
+    float m_run[QB], l_run[QB];
 #pragma unroll
-    for (int d = 0; d < 2; ++d)
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.0f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[d][v] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+        for (int d = 0; d < 2; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[qb][d][v] = 0.0f;
+    }
 
-    const int lrow = tid / CPR, lchunk = tid % CPR;
     const int KT = p.npad / 64;
-    u32x4 rk[IT], rv[IT];
-    auto gload = [&](int kt) {
+    const int NIT = (KT + KW - 1) / KW;
+    const int lchunk = tid % CPR;
+    u32x4 rg[CH];
+    // chunk i of this thread: linear index tid + i NT over (tile j, K|V, row, chunk)
+    auto gload = [&](int it) {
 #pragma unroll
-        for (int i = 0; i < IT; ++i) {
-            const int r = lrow + i * RPP;
-            const int key = kt * 64 + r;
-            rk[i] = key < p.N ? ld_global_16(kbase + (int64_t)key * ld + lchunk * CE) : u32x4{0, 0, 0, 0};
-            rv[i] = ld_global_16(vt + (int64_t)r * p.npad + kt * 64 + lchunk * CE);
+        for (int i = 0; i < CH; ++i) {
+            const int idx = (tid + i * NT) / CPR;          // (j * 2 + which) * 64 + row
+            const int row = idx & 63, which = (idx >> 6) & 1, t = it * KW + (idx >> 7);
+            // always-valid addresses instead of branches: a key row past N re-reads row N - 1 (its
+            // scores are masked to -inf anyway) and a tile past the end re-reads the last tile (the
+            // wave that would use it skips its compute)
+            const int tc = t < KT ? t : KT - 1;
+            const int key = tc * 64 + row < p.N ? tc * 64 + row : p.N - 1;
+            const T* src = which ? vt + (int64_t)row * p.npad + tc * 64 + lchunk * CE
+                                 : kbase + (int64_t)key * ld + lchunk * CE;
+            rg[i] = ld_global_16(src);
         }
     };
     auto sstore = [&]() {
 #pragma unroll
-        for (int i = 0; i < IT; ++i) {
-            const int r = lrow + i * RPP;
-            const int phys = (lchunk & ~7) | swz(r, lchunk & 7);
-            *reinterpret_cast<u32x4*>(sK + (r * CPR + phys) * 16) = rk[i];
-            *reinterpret_cast<u32x4*>(sV + (r * CPR + phys) * 16) = rv[i];
+        for (int i = 0; i < CH; ++i) {
+            const int idx = (tid + i * NT) / CPR;
+            const int row = idx & 63;
+            const int phys = (lchunk & ~7) | swz(row, lchunk & 7);
+            *reinterpret_cast<u32x4*>(smem + (idx >> 6) * TILE + (row * CPR + phys) * 16) = rg[i];
         }
     };
 
     gload(0);
-    for (int kt = 0; kt < KT; ++kt) {
-        __syncthreads();           // everyone is done reading the previous tile
+    for (int it = 0; it < NIT; ++it) {
+        __syncthreads();           // everyone is done reading the previous tiles
         sstore();
         __syncthreads();
-        if (kt + 1 < KT) gload(kt + 1);
-
-        f32x16 s[2];
+        gload(it + 1);         // unconditional (indices are clamped): keeps the in-flight load count static
+        const int t = it * KW + kw;
+        if (t >= KT) continue;     // (barriers above are reached by every wave in every iteration)
+        const char* sK = smem + (kw * 2) * TILE;
+        const char* sV = sK + TILE;
+        const bool last = t == KT - 1;     // keys past N only exist in the last tile
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int qb = 0; qb < QB; ++qb) {
+            f32x16 s[2];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s[kb][v] = 0.0f;
-            AttnMma<T>::qk(s[kb], sK, kb * 32 + li, q, g);
-        }
-        if (kt == KT - 1) {        // keys past N only exist in the last tile
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[kb][v] = 0.0f;
+                AttnMma<T>::qk(s[kb], sK, kb * 32 + li, q[qb], g);
+            }
+            if (last) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                        if (key >= p.N) s[kb][v] = -INFINITY;
+                    }
+            }
+            float mx = s[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[qb], mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * p.scale_log2e);
+            const float mc = m_new * p.scale_log2e;
+            float psum = 0.0f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = kt * 64 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    if (key >= p.N) s[kb][v] = -INFINITY;
+                    const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][v], p.scale_log2e, -mc));
+                    s[kb][v] = e;
+                    psum += e;
                 }
+            l_run[qb] = l_run[qb] * alpha + psum;
+            m_run[qb] = m_new;
+#pragma unroll
+            for (int d = 0; d < 2; ++d)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[qb][d][v] *= alpha;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int d = 0; d < 2; ++d) AttnMma<T>::pv(o[qb][d], sV, d * 32 + li, kb, s[kb], g);
         }
-        float mx = s[0][0];
+    }
+
+    if constexpr (KW > 1) {
+        // merge the KW partial (max, sum, O) triples of each query group, lane by lane
+        constexpr int PER = QB * (32 + 2) * 64;          // floats per wave: O (32 per lane), m, l
+        float* red = reinterpret_cast<float*>(smem);
+        __syncthreads();
+        if (kw > 0) {
+            float* dst = red + ((kw - 1) * QW + qw) * PER + lane;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e);
-        const float mc = m_new * p.scale_log2e;
-        float psum = 0.0f;
+                for (int d = 0; d < 2; ++d)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][v], p.scale_log2e, -mc));
-                s[kb][v] = e;
-                psum += e;
+                    for (int v = 0; v < 16; ++v) dst[(qb * 34 + d * 16 + v) * 64] = o[qb][d][v];
+                dst[(qb * 34 + 32) * 64] = m_run[qb];
+                dst[(qb * 34 + 33) * 64] = l_run[qb];
             }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        }
+        __syncthreads();
+        if (kw > 0) return;
+        for (int k = 1; k < KW; ++k) {
+            const float* src = red + ((k - 1) * QW + qw) * PER + lane;
 #pragma unroll
-        for (int d = 0; d < 2; ++d)
+            for (int qb = 0; qb < QB; ++qb) {
+                const float mk = src[(qb * 34 + 32) * 64], lk = src[(qb * 34 + 33) * 64];
+                const float m_new = fmaxf(m_run[qb], mk);
+                const float a = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * p.scale_log2e);
+                const float bsc = __builtin_amdgcn_exp2f((mk - m_new) * p.scale_log2e);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+                for (int d = 0; d < 2; ++d)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int d = 0; d < 2; ++d) AttnMma<T>::pv(o[d], sV, d * 32 + li, kb, s[kb], g);
+                    for (int v = 0; v < 16; ++v)
+                        o[qb][d][v] = o[qb][d][v] * a + src[(qb * 34 + d * 16 + v) * 64] * bsc;
+                l_run[qb] = l_run[qb] * a + lk * bsc;
+                m_run[qb] = m_new;
+            }
+        }
     }
 
     // each lane half summed its own keys; the query's denominator is the sum of both halves
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = 1.0f / l_tot;
-    const int qi = q0 + li;
-    if (qi < p.N) {
-        T* orow = reinterpret_cast<T*>(p.out) + ((int64_t)b * p.N + qi) * p.dim + h * 64;
 #pragma unroll
-        for (int d = 0; d < 2; ++d)
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+        const float inv = 1.0f / l_tot;
+        const int qi = q0 + qb * 32 + li;
+        if (qi < p.N) {
+            T* orow = reinterpret_cast<T*>(p.out) + ((int64_t)b * p.N + qi) * p.dim + h * 64;
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                // O^T rows (dh) 32 d + 8 v4 + 4 g .. + 3 of this lane's query
-                T* dst = orow + 32 * d + 8 * v4 + 4 * g;
+            for (int d = 0; d < 2; ++d)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) dst[i] = from_f32<T>(o[d][4 * v4 + i] * inv);
-            }
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    // O^T rows (dh) 32 d + 8 v4 + 4 g .. + 3 of this lane's query
+                    T* dst = orow + 32 * d + 8 * v4 + 4 * g;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) dst[i] = from_f32<T>(o[qb][d][4 * v4 + i] * inv);
+                }
+        }
     }
 }
 
-template <typename T>
-static inline hipError_t launch_attention_t(const AttnArgs& a, hipStream_t s) {
-    // fewer waves per workgroup when there would otherwise be too few workgroups for 256 CUs
-    const int bh = a.B * a.heads;
-    if ((int64_t)cdiv(a.N, 128) * bh >= 512) {
-        hipLaunchKernelGGL((attention_kernel<T, 4>), dim3(cdiv(a.N, 128), bh), dim3(256), 0, s, a);
-    } else if ((int64_t)cdiv(a.N, 64) * bh >= 256) {
-        hipLaunchKernelGGL((attention_kernel<T, 2>), dim3(cdiv(a.N, 64), bh), dim3(128), 0, s, a);
-    } else {
-        hipLaunchKernelGGL((attention_kernel<T, 1>), dim3(cdiv(a.N, 32), bh), dim3(64), 0, s, a);
+template <typename T, int QB, int QW, int KW>
+static inline hipError_t launch_attention_variant(const AttnArgs& a, hipStream_t s, bool configure_only) {
+    constexpr int TILE = 64 * AttnMma<T>::ROWB;
+    constexpr int kv = KW * 2 * TILE, red = (KW - 1) * QW * QB * 34 * 64 * 4;
+    constexpr int lds = kv > red ? kv : red;
+    static bool configured = false;       // opt in to more than 64 KB of LDS once per instantiation
+    if (!configured) {
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<T, QB, QW, KW>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (rc != hipSuccess) return rc;
+        configured = true;
     }
+    if (configure_only) return hipSuccess;
+    hipLaunchKernelGGL((attention_kernel<T, QB, QW, KW>), dim3(cdiv(a.N, 32 * QB * QW), a.B * a.heads),
+                       dim3(64 * QW * KW), lds, s, a);
     return hipGetLastError();
 }
 

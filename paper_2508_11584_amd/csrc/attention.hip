@@ -1,7 +1,54 @@
-// Instantiations of the flash-style attention kernel.
+// Instantiations of the flash-style attention kernel and the choice of workgroup shape.
+#include <cstdlib>
+
 #include "kernels.h"
 namespace vpe {
+
+// variant = QB * 100 + QW * 10 + KW
+template <typename T>
+static hipError_t launch_variant(int variant, const AttnArgs& a, hipStream_t s, bool cfg = false) {
+    switch (variant) {
+        case 114: return launch_attention_variant<T, 1, 1, 4>(a, s, cfg);
+        case 141: return launch_attention_variant<T, 1, 4, 1>(a, s, cfg);
+        default: break;
+    }
+    if constexpr (sizeof(T) == 2) {
+        switch (variant) {
+            case 214: return launch_attention_variant<T, 2, 1, 4>(a, s, cfg);
+            case 218: return launch_attention_variant<T, 2, 1, 8>(a, s, cfg);
+            case 118: return launch_attention_variant<T, 1, 1, 8>(a, s, cfg);
+            case 122: return launch_attention_variant<T, 1, 2, 2>(a, s, cfg);
+            case 124: return launch_attention_variant<T, 1, 2, 4>(a, s, cfg);
+            case 222: return launch_attention_variant<T, 2, 2, 2>(a, s, cfg);
+            case 224: return launch_attention_variant<T, 2, 2, 4>(a, s, cfg);
+            case 241: return launch_attention_variant<T, 2, 4, 1>(a, s, cfg);
+            case 221: return launch_attention_variant<T, 2, 2, 1>(a, s, cfg);
+            default: break;
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+// LDS opt-in for every instantiation; called once at engine creation, outside any stream capture.
+hipError_t configure_attention() {
+    static const int all[] = {114, 141, 214, 218, 118, 122, 124, 222, 224, 241, 221};
+    AttnArgs a{};
+    for (int v : all) {
+        hipError_t rc = launch_variant<bf16>(v, a, nullptr, true);
+        if (rc != hipSuccess) return rc;
+    }
+    hipError_t rc = launch_variant<float>(114, a, nullptr, true);
+    if (rc != hipSuccess) return rc;
+    return launch_variant<float>(141, a, nullptr, true);
+}
+
 hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {
-    return dtype ? launch_attention_t<bf16>(a, s) : launch_attention_t<float>(a, s);
+    const char* env = getenv("VPE_ATTN_VARIANT");
+    const int forced = env ? atoi(env) : 0;
+    // few (batch x head) pairs: split the keys over the waves of a workgroup; many: share key tiles
+    const int64_t qblocks = (int64_t)cdiv(a.N, 32) * a.B * a.heads;
+    int variant = qblocks >= 2048 ? 224 : 124;
+    if (forced) variant = forced;
+    return dtype ? launch_variant<bf16>(variant, a, s) : launch_variant<float>(forced == 141 || qblocks >= 2048 ? 141 : 114, a, s);
 }
 }  // namespace vpe

@@ -29,9 +29,11 @@ template <> __device__ __forceinline__ float from_f32<float>(float v) { return v
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
 
 // LDS tiles are stored as rows of 16-byte chunks; chunk c of row r lives at physical chunk
-// c ^ (r & 7), so that 8 consecutive rows reading the same logical chunk hit 8 different
-// 16-byte bank groups (a 128-byte row would otherwise put them all on the same banks).
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+// c ^ ((r >> 1) & 7).  The gfx950 LDS has 64 banks of 4 bytes (256 bytes per cycle): a 128-byte row
+// covers half of them, rows r and r + 1 the two halves, so 16 consecutive rows reading the same
+// logical chunk land on 16 different 16-byte bank groups (measured: ds_read_b128 at 5.25 cycles per
+// wave-instruction, the same as a linear pattern; XOR with r & 7 costs 8.0, no swizzle 32).
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
 __device__ __forceinline__ u32x4 ld_global_16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 

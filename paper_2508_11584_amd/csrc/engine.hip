@@ -26,7 +26,7 @@ thread_local std::string g_create_error;
 
 constexpr int KPATCH = 588;      // 3 * 14 * 14
 constexpr int KPATCH_PAD = 640;  // next multiple of the k-tile
-constexpr int NPAD = 128;        // weight rows are padded to the widest GEMM tile
+constexpr int NPAD = 256;        // weight rows are padded to the widest GEMM tile
 
 struct Bump {
     char* base = nullptr;  // null: only count
@@ -86,6 +86,7 @@ struct vpe_engine {
     float *patch_b = nullptr, *special = nullptr, *pos = nullptr, *norm_g = nullptr, *norm_b = nullptr;
     std::vector<BlockW> blk;
     // encoder scratch
+    void* zeros = nullptr;               // 256 bytes that stay zero (padding taps of the 3x3 convolutions)
     void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
     float* x = nullptr;
     // ring
@@ -219,6 +220,7 @@ void layout(vpe_engine& e, Bump& b) {
         w.ls2 = f32(D);
     }
     e.norm_g = f32(D); e.norm_b = f32(D);
+    e.zeros = b.take(256);
     e.apatch = b.take(B * P * KPATCH_PAD * esz);
     e.x = f32(T * D);
     e.u = b.take(T * D * esz);
@@ -418,9 +420,10 @@ GemmArgs tokens_gemm(vpe_engine& e, const void* feat, const void* W, const float
     return a;
 }
 
-GemmArgs conv3_gemm(const void* in, int C, int B, int h, int w, int istride, int off, const void* W,
-                    const float* bias, int N) {
+GemmArgs conv3_gemm(vpe_engine& e, const void* in, int C, int B, int h, int w, int istride, int off,
+                    const void* W, const float* bias, int N) {
     GemmArgs a = plain_gemm(in, C, W, bias, B * h * w, N, 9 * C);
+    a.zeros = e.zeros;
     a.a_istride = istride; a.a_off = off; a.cH = h; a.cW = w; a.cC = C;
     a.act = ACT_RELU;
     return a;
@@ -435,7 +438,7 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
         HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         HIPCHK(&e, launch_seg_upsample_argmax(h.logits, e.B, e.gh, e.gw, h.classes, e.H, e.W, h.classmap, s));
     } else if (h.kind == VPE_HEAD_DET) {
-        GemmArgs a = conv3_gemm(f[3], e.D, e.B, e.gh, e.gw, e.N, 1 + e.R, h.w0, h.b0, 2 * h.ch);
+        GemmArgs a = conv3_gemm(e, f[3], e.D, e.B, e.gh, e.gw, e.N, 1 + e.R, h.w0, h.b0, 2 * h.ch);
         a.out = h.tower; a.ldo = 2 * h.ch;
         HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
         GemmArgs o = plain_gemm(h.tower, 2 * h.ch, h.w1, h.b1, BP, h.classes + 4, 2 * h.ch);
@@ -455,7 +458,7 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
                 HIPCHK(&e, launch_fuse_upsample(dt, h.p[st], e.gh, e.gw, h.r, e.B, hs, wsz, h.ch, h.z, s));
                 in = h.z;
             }
-            GemmArgs a = conv3_gemm(in, h.ch, e.B, hs, wsz, hs * wsz, 0, h.fuse_w[st], h.fuse_b[st], h.ch);
+            GemmArgs a = conv3_gemm(e, in, h.ch, e.B, hs, wsz, hs * wsz, 0, h.fuse_w[st], h.fuse_b[st], h.ch);
             a.out = h.r; a.ldo = h.ch;
             HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
         }
@@ -551,6 +554,8 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
         return 1;
     };
     if (hip(hipMemset(e->ws, 0, need), "hipMemset")) return bail(VPE_EHIP);
+    if (hip(configure_attention(), "configure_attention")) return bail(VPE_EHIP);
+    if (hip(configure_gemm(), "configure_gemm")) return bail(VPE_EHIP);
     Bump real;
     real.base = e->ws;
     layout(*e, real);
@@ -730,7 +735,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 // buffers as in a head run; timing does not depend on the values in z
                 for (int st = 1; st < 4; ++st) {
                     const int hs = e->gh << st, wsz = e->gw << st;
-                    GemmArgs a = conv3_gemm(dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[st], dh->fuse_b[st], dh->ch);
+                    GemmArgs a = conv3_gemm(*e, dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[st], dh->fuse_b[st], dh->ch);
                     a.out = dh->r; a.ldo = dh->ch;
                     HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
                 }

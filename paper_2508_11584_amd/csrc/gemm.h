@@ -7,7 +7,7 @@
 //     read) or an implicit im2col of a channels-last grid for 3x3 / pad 1 convolutions.
 //   * operands in bf16 (v_mfma_f32_32x32x16_bf16) or fp32 (v_mfma_f32_32x32x2_f32).
 //   * LDS: two stages of (BM + BN) rows x 128 bytes, 16-byte chunks XOR-swizzled by row.
-//   * global -> register -> LDS software pipeline, one barrier per k-tile.
+//   * global -> register -> LDS software pipeline two k-tiles deep, one barrier per k-tile.
 #pragma once
 #include "common.h"
 
@@ -20,13 +20,14 @@ enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 struct GemmArgs {
     const void* A;       // T
     int64_t lda;         // elements between consecutive A rows (PLAIN) / pixels (CONV3)
-    const void* W;       // T [N rounded up to 128][K]
+    const void* W;       // T [N rounded up to 256][K]
     const float* bias;   // [N] in the physical column order of W, may be null
     int M, N, K;         // K multiple of 64 (bf16) / 32 (fp32)
     // PLAIN: logical row r reads A row (r / a_rpi) * a_istride + a_off + r % a_rpi
     // CONV3: pixel (b, y, x) is A row b * a_istride + a_off + y * cW + x
     int a_rpi, a_istride, a_off;
     int cH, cW, cC;      // CONV3 grid and channels (K = 9 cC, cC multiple of the k-tile)
+    const void* zeros;   // CONV3: >= 16 bytes of zeros, read in place of out-of-image taps
     int epi, act, out_f32;
     void* out;           // T or float (out_f32); RESID/PATCH: float residual stream
     int64_t ldo;
@@ -70,13 +71,41 @@ template <> struct Mma<float> {
     }
 };
 
-__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+// GELU in its exact (erf) form.  erf by the Abramowitz-Stegun 7.1.26 rational approximation
+// (|error| <= 1.5e-7, i.e. fp32 rounding level): one reciprocal, one exponential and six FMAs
+// instead of the ~40-instruction library erff, which made the GELU epilogue of a 256 x 256 tile as
+// long as its k loop.
+__device__ __forceinline__ float gelu_erf(float v) {
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float erf_abs = 1.0f - poly * t * __expf(-x * x);
+    return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+}
 
 // Spread consecutive block ids (which the hardware deals round-robin to the 8 XCDs) so that
 // each XCD works on one contiguous range of tiles and its L2 sees neighbouring A/W panels.
 __device__ __forceinline__ int xcd_contiguous(int bid, int nb) {
     const int xcd = bid & 7, idx = bid >> 3, base = nb >> 3, rem = nb & 7;
     return xcd * base + (xcd < rem ? xcd : rem) + idx;
+}
+
+// Linear tile index -> (tile row, tile column) in groups of GM tile rows: the ~32 workgroups an XCD
+// runs at a time then cover a GM x (32 / GM) block of tiles instead of one row of 32, so each A
+// k-slice fetched into that XCD's L2 serves 32 / GM workgroups and each W k-slice GM of them.
+// (Measured on the large tiles: with row-major order the loads ran at the XCD <-> memory-side
+// fabric rate, about 13 TB/s in aggregate, not at the L2 rate.)
+__device__ __forceinline__ void tile_coords(int lin, int tiles_m, int tiles_n, int& tm, int& tn) {
+    constexpr int GM = 8;
+    const int per_group = GM * tiles_n;
+    const int group = lin / per_group, rem = lin - group * per_group;
+    const int first = group * GM;
+    const int gsz = tiles_m - first < GM ? tiles_m - first : GM;
+    tm = first + rem % gsz;
+    tn = rem / gsz;
 }
 
 // 8 consecutive values of T (16 bytes of bf16, 32 bytes of fp32) to global memory.
@@ -155,7 +184,7 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& p, int r, int c, 
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN, int AMODE>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs p) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int CE = Elem<T>::CE;
     constexpr int BK = 8 * CE;
@@ -171,68 +200,78 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs p) 
     const int g = lane >> 5, li = lane & 31;
     const int lrow = tid >> 3, lchunk = tid & 7;
 
-    const int tiles_n = (p.N + BN - 1) / BN;
-    const int lin = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int m0 = (lin / tiles_n) * BM, n0 = (lin % tiles_n) * BN;
+    int tm, tn;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
 
     const T* __restrict__ A = reinterpret_cast<const T*>(p.A);
     const T* __restrict__ W = reinterpret_cast<const T*>(p.W);
 
-    // per-thread A row state
+    // per-thread A row state.  Loads carry neither branches nor selects on the loaded value (either
+    // would make the wave wait for the load right where it is issued): rows past M re-read row
+    // M - 1 (their accumulators are never stored) and out-of-image conv taps read a page of zeros.
     const T* aptr[A_IT];
     int ay[A_IT], ax[A_IT];
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-        const int r = m0 + lrow + i * RPP;
-        aptr[i] = nullptr;
+        int r = m0 + lrow + i * RPP;
+        r = r < p.M ? r : p.M - 1;
         ay[i] = ax[i] = 0;
-        if (r < p.M) {
-            if (AMODE == A_PLAIN) {
-                const int64_t ar = (int64_t)(r / p.a_rpi) * p.a_istride + p.a_off + r % p.a_rpi;
-                aptr[i] = A + ar * p.lda + lchunk * CE;
-            } else {
-                const int hw = p.cH * p.cW;
-                const int b = r / hw, pix = r % hw;
-                ay[i] = pix / p.cW;
-                ax[i] = pix % p.cW;
-                aptr[i] = A + ((int64_t)b * p.a_istride + p.a_off + pix) * p.lda + lchunk * CE;
-            }
+        if (AMODE == A_PLAIN) {
+            const int64_t ar = (int64_t)(r / p.a_rpi) * p.a_istride + p.a_off + r % p.a_rpi;
+            aptr[i] = A + ar * p.lda + lchunk * CE;
+        } else {
+            const int hw = p.cH * p.cW;
+            const int b = r / hw, pix = r % hw;
+            ay[i] = pix / p.cW;
+            ax[i] = pix % p.cW;
+            aptr[i] = A + ((int64_t)b * p.a_istride + p.a_off + pix) * p.lda + lchunk * CE;
         }
     }
     const T* wptr = W + (int64_t)(n0 + lrow) * p.K + lchunk * CE;
+    const T* zptr = reinterpret_cast<const T*>(p.zeros);
 
-    u32x4 ra[A_IT], rb[B_IT];
-    auto gload = [&](int kt) {
+    // two register sets: the loads of k-tile kt + 2 are issued while tile kt is multiplied and tile
+    // kt + 1 waits in the other set, so a global load has two tile times to arrive
+    u32x4 ra[2][A_IT], rb[2][B_IT];
+    auto gload = [&](int set, int kt) {
         const int k0 = kt * BK;
         if (AMODE == A_PLAIN) {
 #pragma unroll
-            for (int i = 0; i < A_IT; ++i)
-                ra[i] = aptr[i] ? ld_global_16(aptr[i] + k0) : u32x4{0, 0, 0, 0};
+            for (int i = 0; i < A_IT; ++i) ra[set][i] = ld_global_16(aptr[i] + k0);
         } else {
-            const int tap = k0 / p.cC, c0 = k0 - tap * p.cC;
+            // k-tile order: channel chunk outer, tap inner -- the 9 taps of a chunk re-read the same
+            // 128-byte slices of neighbouring pixels, which keeps a workgroup's L2 footprint small
+            const int cc = kt / 9, tap = kt - cc * 9, c0 = cc * BK;
             const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+            const int64_t shift = (int64_t)(dy * p.cW + dx) * p.lda + c0;
 #pragma unroll
             for (int i = 0; i < A_IT; ++i) {
                 const int yy = ay[i] + dy, xx = ax[i] + dx;
-                const bool ok = aptr[i] && yy >= 0 && yy < p.cH && xx >= 0 && xx < p.cW;
-                ra[i] = ok ? ld_global_16(aptr[i] + (int64_t)(dy * p.cW + dx) * p.lda + c0) : u32x4{0, 0, 0, 0};
+                const bool ok = yy >= 0 && yy < p.cH && xx >= 0 && xx < p.cW;
+                // bitwise pointer select: a ternary here is compiled to a branch around the address math
+                const uint64_t mask = ok ? ~uint64_t(0) : uint64_t(0);
+                const uint64_t addr = (reinterpret_cast<uint64_t>(aptr[i] + shift) & mask) |
+                                      (reinterpret_cast<uint64_t>(zptr) & ~mask);
+                ra[set][i] = ld_global_16(reinterpret_cast<const void*>(addr));
             }
         }
+        const int kw = AMODE == A_PLAIN ? k0 : (kt % 9) * p.cC + (kt / 9) * BK;   // weight column of this k-tile
 #pragma unroll
-        for (int i = 0; i < B_IT; ++i) rb[i] = ld_global_16(wptr + (int64_t)i * RPP * p.K + k0);
+        for (int i = 0; i < B_IT; ++i) rb[set][i] = ld_global_16(wptr + (int64_t)i * RPP * p.K + kw);
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int set, int buf) {
         char* sA = smem + buf * STAGE;
         char* sB = sA + BM * 128;
 #pragma unroll
         for (int i = 0; i < A_IT; ++i) {
             const int r = lrow + i * RPP;
-            *reinterpret_cast<u32x4*>(sA + (r * 8 + swz(r, lchunk)) * 16) = ra[i];
+            *reinterpret_cast<u32x4*>(sA + (r * 8 + swz(r, lchunk)) * 16) = ra[set][i];
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
             const int r = lrow + i * RPP;
-            *reinterpret_cast<u32x4*>(sB + (r * 8 + swz(r, lchunk)) * 16) = rb[i];
+            *reinterpret_cast<u32x4*>(sB + (r * 8 + swz(r, lchunk)) * 16) = rb[set][i];
         }
     };
 
@@ -244,28 +283,48 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs p) 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int KT = p.K / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) gload(kt + 1);
-        const char* sA = smem + cur * STAGE;
+    // fragments of k-step ks + 1 are read from LDS before the MFMAs of step ks are issued
+    auto compute = [&](int buf) {
+        const char* sA = smem + buf * STAGE;
         const char* sB = sA + BM * 128;
+        typename Mma<T>::Frag fa[2][MI], fb[2][NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[0][i] = Mma<T>::load(sA, wm * WM + i * 32 + li, 0, g);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[0][j] = Mma<T>::load(sB, wn * WN + j * 32 + li, 0, g);
 #pragma unroll
         for (int ks = 0; ks < Mma<T>::KS; ++ks) {
-            typename Mma<T>::Frag fa[MI], fb[NI];
+            if (ks + 1 < Mma<T>::KS) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i) fa[i] = Mma<T>::load(sA, wm * WM + i * 32 + li, ks, g);
+                for (int i = 0; i < MI; ++i) fa[(ks + 1) & 1][i] = Mma<T>::load(sA, wm * WM + i * 32 + li, ks + 1, g);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) fb[j] = Mma<T>::load(sB, wn * WN + j * 32 + li, ks, g);
+                for (int j = 0; j < NI; ++j) fb[(ks + 1) & 1][j] = Mma<T>::load(sB, wn * WN + j * 32 + li, ks + 1, g);
+            }
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) Mma<T>::mma(acc[i][j], fa[i], fb[j]);
+                for (int j = 0; j < NI; ++j) Mma<T>::mma(acc[i][j], fa[ks & 1][i], fb[ks & 1][j]);
         }
-        if (kt + 1 < KT) sstore(cur ^ 1);
+    };
+
+    // The prefetches are unconditional (tile index clamped to the last tile) so that the number of
+    // loads in flight is the same on every path: with a conditional prefetch the compiler has to
+    // assume it was skipped and waits for the newest loads before storing the older set.
+    const int KT = p.K / BK;
+    const int klast = KT - 1;
+    gload(0, 0);
+    gload(1, klast < 1 ? klast : 1);
+    sstore(0, 0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+        gload(0, kt + 2 < klast ? kt + 2 : klast);
+        compute(0);
+        sstore(1, 1);
+        __syncthreads();
+        if (kt + 1 >= KT) break;
+        gload(1, kt + 3 < klast ? kt + 3 : klast);
+        compute(1);
+        sstore(0, 0);
         __syncthreads();
     }
 

@@ -1,0 +1,272 @@
+// Large-tile MFMA GEMM for gfx950 with direct global->LDS loads (global_load_lds_dwordx4).
+//
+// Why a second kernel: measured on MI355X, one CU moves about 64 bytes per clock from L2 into LDS
+// and its LDS serves ds_read_b128 at about 200 bytes per clock, while its four MFMA pipes retire
+// a 32x32x16 bf16 MFMA every 32 clocks each.  With 128x128 block tiles (64x64 per wave) every
+// 64-deep k-tile needs 32 KB of loads and 64 KB of LDS reads per 512 MFMA clocks: the load path is
+// as busy as the matrix pipes and the kernel tops out near 30 % of the MFMA peak.  Here a
+// workgroup of 4 waves owns a 256 x BN tile (BN = 256 or 128) and each wave a 128 x BN/2 tile, which
+// halves both ratios; operands go from global memory straight into the swizzled LDS tile
+// (no VGPR staging, no ds_write), the next k-tile's loads are issued before the current tile's
+// MFMAs, and the accumulators (up to 256 registers per lane) leave through a per-wave LDS
+// staging block with 16-byte coalesced stores.  One workgroup per CU; latency is hidden by the
+// software pipeline inside each wave, not by occupancy.
+//
+// Same operands, A modes and epilogues as gemm_kernel (see gemm.h); bf16 only.
+#pragma once
+#include "gemm.h"
+
+namespace vpe {
+
+#define VPE_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define VPE_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+
+// BK = 64 or 32 elements per k-tile (LDS rows of 128 or 64 bytes), S LDS stages: the loads of tile
+// kt + S - 1 are in flight while tile kt is multiplied, so a load has S - 1 tile times to arrive.
+template <int BN, int BK, int S, int AMODE>
+__global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
+    typedef bf16 T;
+    constexpr int BM = 256, CE = 8;
+    constexpr int WM = 128, WN = BN / 2, MI = 4, NI = WN / 32;
+    constexpr int ROWB = BK * 2, CPR = BK / 8, RPI = 64 / CPR;   // row bytes, chunks per row, rows per DMA instruction
+    constexpr int KS = BK / 16;
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_SLOTS = A_BYTES / 4096, B_SLOTS = B_BYTES / 4096;   // 1 KB DMA instructions per wave per k-tile
+    constexpr int PD = S - 1;
+    // chunk swizzle: 256 bytes of LDS (64 banks) hold 2 rows of 128 bytes or 4 rows of 64 bytes
+    constexpr int SW_SHIFT = BK == 64 ? 1 : 2, SW_MASK = CPR - 1;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int g = lane >> 5, li = lane & 31;
+
+    int tm, tn;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const char* __restrict__ A = reinterpret_cast<const char*>(p.A);
+    const char* __restrict__ W = reinterpret_cast<const char*>(p.W);
+
+    // --- loader state.  DMA instruction `slot` of this wave fills 1 KB of LDS = RPI consecutive rows of
+    // the A (or B) tile, row group rg = wave + 4 slot: lane l lands on row rg*RPI + l/CPR, physical
+    // chunk l%CPR, so it must fetch the logical chunk (l%CPR) ^ swizzle(row) of that row.
+    int aoff[A_SLOTS];          // byte offset of the lane's chunk from A (k = 0; conv: centre pixel)
+    int ay[A_SLOTS], ax[A_SLOTS];
+    int boff[B_SLOTS];
+#pragma unroll
+    for (int s = 0; s < A_SLOTS; ++s) {
+        const int row = (wave + 4 * s) * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ ((row >> SW_SHIFT) & SW_MASK);
+        int r = m0 + row;
+        r = r < p.M ? r : p.M - 1;
+        ay[s] = ax[s] = 0;
+        if (AMODE == A_PLAIN) {
+            const int64_t ar = (int64_t)(r / p.a_rpi) * p.a_istride + p.a_off + r % p.a_rpi;
+            aoff[s] = (int)((ar * p.lda + c * CE) * 2);
+        } else {
+            const int hw = p.cH * p.cW;
+            const int b = r / hw, pix = r % hw;
+            ay[s] = pix / p.cW;
+            ax[s] = pix % p.cW;
+            aoff[s] = (int)((((int64_t)b * p.a_istride + p.a_off + pix) * p.lda + c * CE) * 2);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < B_SLOTS; ++s) {
+        const int row = (wave + 4 * s) * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ ((row >> SW_SHIFT) & SW_MASK);
+        boff[s] = (int)(((int64_t)(n0 + row) * p.K + c * CE) * 2);
+    }
+    const char* zptr = reinterpret_cast<const char*>(p.zeros);
+
+    auto dma = [&](int stage, int kt) {
+        char* sA = smem + stage * STAGE;
+        char* sB = sA + A_BYTES;
+        const int k0 = kt * BK;
+        if (AMODE == A_PLAIN) {
+#pragma unroll
+            for (int s = 0; s < A_SLOTS; ++s)
+                __builtin_amdgcn_global_load_lds(VPE_GPTR(A + aoff[s] + k0 * 2), VPE_LPTR(sA + (wave + 4 * s) * 1024), 16, 0, 0);
+        } else {
+            const int cc = kt / 9, tap = kt - cc * 9, c0 = cc * BK;    // chunk-major, tap-minor k order
+            const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+            const int shift = ((dy * p.cW + dx) * (int)p.lda + c0) * 2;
+#pragma unroll
+            for (int s = 0; s < A_SLOTS; ++s) {
+                const int yy = ay[s] + dy, xx = ax[s] + dx;
+                const bool ok = yy >= 0 && yy < p.cH && xx >= 0 && xx < p.cW;
+                const uint64_t mask = ok ? ~uint64_t(0) : uint64_t(0);
+                const uint64_t addr = (reinterpret_cast<uint64_t>(A + aoff[s] + shift) & mask) |
+                                      (reinterpret_cast<uint64_t>(zptr) & ~mask);
+                __builtin_amdgcn_global_load_lds(VPE_GPTR(addr), VPE_LPTR(sA + (wave + 4 * s) * 1024), 16, 0, 0);
+            }
+        }
+        const int kw = AMODE == A_PLAIN ? k0 : (kt % 9) * p.cC + (kt / 9) * BK;   // weight column of this k-tile
+#pragma unroll
+        for (int s = 0; s < B_SLOTS; ++s)
+            __builtin_amdgcn_global_load_lds(VPE_GPTR(W + boff[s] + kw * 2), VPE_LPTR(sB + (wave + 4 * s) * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // --- MFMA operand reads.  Rows of one lane differ by multiples of 32, so the swizzle term is the
+    // same for all of them: one lane offset per k-step, rows by immediates.
+    const int arow0 = wm * WM + li, brow0 = wn * WN + li;
+    const int asw = (arow0 >> SW_SHIFT) & SW_MASK, bsw = (brow0 >> SW_SHIFT) & SW_MASK;
+    auto compute = [&](int stage) {
+        const char* sA = smem + stage * STAGE + arow0 * ROWB;
+        const char* sB = smem + stage * STAGE + A_BYTES + brow0 * ROWB;
+        bf16x8 fa[2][MI], fb[2][NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ((g ^ asw) * 16));
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + ((g ^ bsw) * 16));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+                const int ca = ((2 * (ks + 1) + g) ^ asw) * 16, cb = ((2 * (ks + 1) + g) ^ bsw) * 16;
+#pragma unroll
+                for (int i = 0; i < MI; ++i) fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ca);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + cb);
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+            // Issue order for the scheduler: the LDS reads of step ks + 1 are spread between the MFMAs
+            // of step ks (one read per two MFMAs), so the only wave on this SIMD never waits on LDS
+            // with an empty matrix pipe.  0x100 = DS read, 0x008 = MFMA.
+            if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
+            if (ks + 1 < KS) {
+#pragma unroll
+                for (int n = 0; n < MI + NI; ++n) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, (MI * NI) / (MI + NI), 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI) * ((MI * NI) / (MI + NI)), 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
+            }
+        }
+    };
+
+    // --- main loop: S LDS stages.  Iteration kt: wait until tile kt has landed (the S - 2 younger
+    // tiles may still be in flight), barrier (which also tells everyone that the stage read in
+    // iteration kt - 1 is free), issue the loads of tile kt + S - 1 into that free stage, multiply
+    // tile kt.  Prefetches are unconditional (clamped index): every path has the same loads in flight.
+    const int KT = p.K / BK;
+#pragma unroll
+    for (int s = 0; s < PD; ++s) dma(s, s < KT ? s : KT - 1);
+    for (int kt = 0; kt < KT; ++kt) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * (A_SLOTS + B_SLOTS)));
+        __syncthreads();
+        dma((kt + PD) % S, kt + PD < KT ? kt + PD : KT - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(kt % S);
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // drain the clamped tail prefetches before LDS is reused
+    __syncthreads();
+
+    // --- epilogue.  Each wave stages its accumulators 32 rows at a time in its own 32 x WN fp32
+    // block of LDS (the stage buffers are free now) and leaves with 8-column chunks per lane.
+    float* sC = reinterpret_cast<float*>(smem) + wave * (32 * WN);
+    const int wrow0 = m0 + wm * WM, wcol0 = n0 + wn * WN;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sC[(8 * (v >> 2) + 4 * g + (v & 3)) * WN + j * 32 + li] = acc[i][j][v];
+        const int rblk = wrow0 + i * 32;
+        if (p.epi == EPI_SWIGLU) {
+            // groups of 64 physical columns: 32 gate columns, then their 32 linear partners
+            constexpr int CG = WN / 16;                  // 8-wide gate chunks per row
+            T* out = reinterpret_cast<T*>(p.out);
+            for (int it = lane; it < 32 * CG; it += 64) {
+                const int rr = it / CG, cg = it % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
+                const int r = rblk + rr, ca = wcol0 + grp * 64 + j0;
+                if (r < p.M && ca + 40 <= p.N) {
+                    const float* src = sC + rr * WN + grp * 64 + j0;
+                    float h[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float a = src[e] + p.bias[ca + e], b = src[32 + e] + p.bias[ca + 32 + e];
+                        h[e] = a / (1.0f + __expf(-a)) * b;
+                    }
+                    store8(out + (int64_t)r * p.ldo + (ca >> 6) * 32 + j0, h);
+                }
+            }
+        } else if (p.epi == EPI_QKV && wcol0 >= 2 * p.dim) {
+            // value columns, written transposed: one column and 8 consecutive tokens per lane
+            T* vt = reinterpret_cast<T*>(p.out2);
+            for (int it = lane; it < WN * 4; it += 64) {
+                const int cc = it % WN, rr = (it / WN) * 8;
+                const int r = rblk + rr, c2 = wcol0 + cc - 2 * p.dim;
+                if (r < p.M && wcol0 + cc < p.N) {
+                    const float bias = p.bias[wcol0 + cc];
+                    float v[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * WN + cc] + bias;
+                    const int b = r / p.ntok, n = r % p.ntok;
+                    if (n + 8 <= p.ntok && (n & 7) == 0) {
+                        store8(vt + ((int64_t)b * p.dim + c2) * p.npad + n, v);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int rk = r + k;
+                            if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
+                        }
+                    }
+                }
+            }
+        } else {
+            constexpr int CG = WN / 8;
+            for (int it = lane; it < 32 * CG; it += 64) {
+                const int rr = it / CG, cg = it % CG;
+                const int r = rblk + rr, c = wcol0 + cg * 8;
+                if (r < p.M && c < p.N) {
+                    const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
+                    const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
+                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    epilogue_chunk<T>(p, r, c, v);
+                }
+            }
+        }
+    }
+}
+
+template <int BN, int BK, int S>
+static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
+    constexpr int lds = S * (256 + BN) * BK * 2;
+    static_assert(lds <= 160 * 1024, "LDS budget of one CU");
+    static bool configured = false;
+    if (!configured) {
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, A_PLAIN>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (rc == hipSuccess)
+            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, A_CONV3>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (rc != hipSuccess) return rc;
+        configured = true;
+    }
+    if (configure_only) return hipSuccess;
+    const int tiles = cdiv(a.M, 256) * cdiv(a.N, BN);
+    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, A_PLAIN>), dim3(tiles), dim3(256), lds, s, a);
+    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, A_CONV3>), dim3(tiles), dim3(256), lds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace vpe
