@@ -15,13 +15,12 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
                                             : (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride;
     const bool fits = a_rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
     const int64_t t256 = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 256), t128 = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 128);
-    // Measured on MI355X (3x3 conv 256->256 on 272x360, and M=10992 N=8192 K=1536): the large tiles reach
-    // 88 % of the MFMA rate with their loads switched off but only 610-700 TFLOP/s with them, against
-    // 750-820 TFLOP/s for the 128 x 128 register-staged kernel at two workgroups per CU -- so they are
-    // not the default; VPE_GEMM_TILE=256 / 128 selects them (used by the tests of their epilogues).
-    (void)t256; (void)t128;
-    int bn = 0;
+    // Problems with enough 256 x 128 tiles to keep two workgroups on every CU busy go to the
+    // direct-to-LDS kernel; everything else stays on the register-staged tiles.
+    (void)t256;
+    int bn = fits && t128 >= 448 ? 128 : 0;
     if (forced == 256 || forced == 128) bn = fits ? forced : 0;
+    if (forced == 1) bn = 0;
     if (bn) return launch_gemm_dma_bf16(bn, a, amode, s);
     return launch_gemm_t<bf16>(a, amode, s);
 }

@@ -1,16 +1,15 @@
 // Large-tile MFMA GEMM for gfx950 with direct global->LDS loads (global_load_lds_dwordx4).
 //
-// Why a second kernel: measured on MI355X, one CU moves about 64 bytes per clock from L2 into LDS
-// and its LDS serves ds_read_b128 at about 200 bytes per clock, while its four MFMA pipes retire
-// a 32x32x16 bf16 MFMA every 32 clocks each.  With 128x128 block tiles (64x64 per wave) every
-// 64-deep k-tile needs 32 KB of loads and 64 KB of LDS reads per 512 MFMA clocks: the load path is
-// as busy as the matrix pipes and the kernel tops out near 30 % of the MFMA peak.  Here a
-// workgroup of 4 waves owns a 256 x BN tile (BN = 256 or 128) and each wave a 128 x BN/2 tile, which
-// halves both ratios; operands go from global memory straight into the swizzled LDS tile
-// (no VGPR staging, no ds_write), the next k-tile's loads are issued before the current tile's
-// MFMAs, and the accumulators (up to 256 registers per lane) leave through a per-wave LDS
-// staging block with 16-byte coalesced stores.  One workgroup per CU; latency is hidden by the
-// software pipeline inside each wave, not by occupancy.
+// Why a second kernel: on MI355X the register-staged 128 x 128 tiles stop at 750-840 TFLOP/s: the
+// LDS write path (ds_write_b128 at ~80 bytes per clock per CU) and the global-load issue rate of
+// 8 waves cannot keep four MFMA pipes fed at 64 FLOP per loaded byte.  Here a workgroup owns a
+// 256 x BN tile (BN = 128 or 256), operands go from global memory straight into the swizzled LDS
+// tile (global_load_lds_dwordx4: no VGPR staging, no ds_write), the next k-tile's loads are issued
+// before the current tile's MFMAs, the LDS reads of k-step s + 1 are interleaved with the MFMAs of
+// step s (sched_group_barrier), and the accumulators leave through a per-wave LDS staging block
+// with 16-byte coalesced stores.  Measured: with the loads switched off the loop runs at 88 % of
+// the MFMA rate; the loads are the limit, and their rate grows with the number of waves issuing
+// them (4 waves: 670, 8 waves: 880, 16 waves per CU: 910-970 TFLOP/s on the 3x3 conv).
 //
 // Same operands, A modes and epilogues as gemm_kernel (see gemm.h); bf16 only.
 #pragma once
@@ -27,22 +26,24 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 // BK = 64 or 32 elements per k-tile (LDS rows of 128 or 64 bytes), S LDS stages: the loads of tile
 // kt + S - 1 are in flight while tile kt is multiplied, so a load has S - 1 tile times to arrive.
-template <int BN, int BK, int S, int AMODE>
-__global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
+// WGM x 2 waves: WGM = 2 gives 128-row wave tiles (256 accumulator registers, one wave per SIMD),
+// WGM = 4 gives 64-row wave tiles and two waves per SIMD, i.e. twice as many waves issuing loads.
+template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE>
+__global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const GemmArgs p) {
     typedef bf16 T;
-    constexpr int BM = 256, CE = 8;
-    constexpr int WM = 128, WN = BN / 2, MI = 4, NI = WN / 32;
+    constexpr int BM = 256, CE = 8, NW = WGN * WGM;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     constexpr int ROWB = BK * 2, CPR = BK / 8, RPI = 64 / CPR;   // row bytes, chunks per row, rows per DMA instruction
     constexpr int KS = BK / 16;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
-    constexpr int A_SLOTS = A_BYTES / 4096, B_SLOTS = B_BYTES / 4096;   // 1 KB DMA instructions per wave per k-tile
+    constexpr int A_SLOTS = A_BYTES / (1024 * NW), B_SLOTS = B_BYTES / (1024 * NW);   // 1 KB DMA instructions per wave per k-tile
     constexpr int PD = S - 1;
     // chunk swizzle: 256 bytes of LDS (64 banks) hold 2 rows of 128 bytes or 4 rows of 64 bytes
     constexpr int SW_SHIFT = BK == 64 ? 1 : 2, SW_MASK = CPR - 1;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int g = lane >> 5, li = lane & 31;
 
     int tm, tn;
@@ -53,14 +54,14 @@ __global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
     const char* __restrict__ W = reinterpret_cast<const char*>(p.W);
 
     // --- loader state.  DMA instruction `slot` of this wave fills 1 KB of LDS = RPI consecutive rows of
-    // the A (or B) tile, row group rg = wave + 4 slot: lane l lands on row rg*RPI + l/CPR, physical
+    // the A (or B) tile, row group rg = wave + NW slot: lane l lands on row rg*RPI + l/CPR, physical
     // chunk l%CPR, so it must fetch the logical chunk (l%CPR) ^ swizzle(row) of that row.
     int aoff[A_SLOTS];          // byte offset of the lane's chunk from A (k = 0; conv: centre pixel)
     int ay[A_SLOTS], ax[A_SLOTS];
     int boff[B_SLOTS];
 #pragma unroll
     for (int s = 0; s < A_SLOTS; ++s) {
-        const int row = (wave + 4 * s) * RPI + lane / CPR;
+        const int row = (wave + NW * s) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ ((row >> SW_SHIFT) & SW_MASK);
         int r = m0 + row;
         r = r < p.M ? r : p.M - 1;
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
     }
 #pragma unroll
     for (int s = 0; s < B_SLOTS; ++s) {
-        const int row = (wave + 4 * s) * RPI + lane / CPR;
+        const int row = (wave + NW * s) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ ((row >> SW_SHIFT) & SW_MASK);
         boff[s] = (int)(((int64_t)(n0 + row) * p.K + c * CE) * 2);
     }
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
         if (AMODE == A_PLAIN) {
 #pragma unroll
             for (int s = 0; s < A_SLOTS; ++s)
-                __builtin_amdgcn_global_load_lds(VPE_GPTR(A + aoff[s] + k0 * 2), VPE_LPTR(sA + (wave + 4 * s) * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(VPE_GPTR(A + aoff[s] + k0 * 2), VPE_LPTR(sA + (wave + NW * s) * 1024), 16, 0, 0);
         } else {
             const int cc = kt / 9, tap = kt - cc * 9, c0 = cc * BK;    // chunk-major, tap-minor k order
             const int dy = tap / 3 - 1, dx = tap % 3 - 1;
@@ -103,13 +104,13 @@ __global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
                 const uint64_t mask = ok ? ~uint64_t(0) : uint64_t(0);
                 const uint64_t addr = (reinterpret_cast<uint64_t>(A + aoff[s] + shift) & mask) |
                                       (reinterpret_cast<uint64_t>(zptr) & ~mask);
-                __builtin_amdgcn_global_load_lds(VPE_GPTR(addr), VPE_LPTR(sA + (wave + 4 * s) * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(VPE_GPTR(addr), VPE_LPTR(sA + (wave + NW * s) * 1024), 16, 0, 0);
             }
         }
         const int kw = AMODE == A_PLAIN ? k0 : (kt % 9) * p.cC + (kt / 9) * BK;   // weight column of this k-tile
 #pragma unroll
         for (int s = 0; s < B_SLOTS; ++s)
-            __builtin_amdgcn_global_load_lds(VPE_GPTR(W + boff[s] + kw * 2), VPE_LPTR(sB + (wave + 4 * s) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(VPE_GPTR(W + boff[s] + kw * 2), VPE_LPTR(sB + (wave + NW * s) * 1024), 16, 0, 0);
     };
 
     f32x16 acc[MI][NI];
@@ -151,12 +152,15 @@ __global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
             // with an empty matrix pipe.  0x100 = DS read, 0x008 = MFMA.
             if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
             if (ks + 1 < KS) {
+                constexpr int PER = (MI * NI) / (MI + NI) > 0 ? (MI * NI) / (MI + NI) : 1;
+                constexpr int GROUPS = (MI * NI) / PER < MI + NI ? (MI * NI) / PER : MI + NI;
 #pragma unroll
-                for (int n = 0; n < MI + NI; ++n) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, (MI * NI) / (MI + NI), 0);
+                for (int n = 0; n < GROUPS; ++n) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI) * ((MI * NI) / (MI + NI)), 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, MI + NI - GROUPS, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - GROUPS * PER, 0);
             } else {
                 __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
             }
@@ -248,24 +252,25 @@ __global__ __launch_bounds__(256, 1) void gemm_dma_kernel(const GemmArgs p) {
     }
 }
 
-template <int BN, int BK, int S>
+template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1>
 static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
-    constexpr int lds = S * (256 + BN) * BK * 2;
-    static_assert(lds <= 160 * 1024, "LDS budget of one CU");
+    constexpr int stage_b = S * (256 + BN) * BK * 2, epi_b = WGM * WGN * 32 * (BN / WGN) * 4;
+    constexpr int lds = stage_b > epi_b ? stage_b : epi_b;
+    static_assert(lds * OCC <= 160 * 1024, "LDS budget of one CU");
     static bool configured = false;
     if (!configured) {
-        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, A_PLAIN>),
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc == hipSuccess)
-            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, A_CONV3>),
+            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc != hipSuccess) return rc;
         configured = true;
     }
     if (configure_only) return hipSuccess;
     const int tiles = cdiv(a.M, 256) * cdiv(a.N, BN);
-    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, A_PLAIN>), dim3(tiles), dim3(256), lds, s, a);
-    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, A_CONV3>), dim3(tiles), dim3(256), lds, s, a);
+    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN>), dim3(tiles), dim3(64 * WGM * WGN), lds, s, a);
+    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3>), dim3(tiles), dim3(64 * WGM * WGN), lds, s, a);
     return hipGetLastError();
 }
 

@@ -135,3 +135,14 @@ def test_cfg2_vits_bf16_476x630_three_heads():
     # benchmark configuration 2 (the headline one), whole, all three heads, as bench.py runs it
     spec = vi.CONFIGS["cfg2"]
     check_all(spec, *vi.SEEDS["cfg2"], flags=vpe.VPE_FLAG_GRAPHS)
+
+
+@pytest.mark.parametrize("tile", ["256", "128"])
+def test_large_tile_direct_to_lds_gemm_variant(tile, monkeypatch):
+    # the opt-in 256-row GEMM (global -> LDS loads) through every epilogue: QKV + transposed values,
+    # LayerScale residual, GELU and SwiGLU, patch embedding, 1x1 and 3x3 convolutions
+    monkeypatch.setenv("VPE_GEMM_TILE", tile)
+    check_all(vi.ModelSpec("medium_bf16_tile" + tile, dtype="bf16", **MEDIUM), 102, 202)
+    spec = vi.ModelSpec("swiglu_tile" + tile, dtype="bf16", **{**MEDIUM, "mlp_kind": vi.MLP_SWIGLU, "registers": 4,
+                                                                "batch": 3, "img_h": 70, "img_w": 98})
+    check_all(spec, 103, 203)
