@@ -19,6 +19,8 @@ def test_weights_are_truncated_seeded_and_bf16_exact():
     w2 = vi.make_backbone_weights(spec, 7)
     for k, v in w.items():
         assert np.array_equal(v, w2[k]), k
+        if k == "__blob__":
+            continue
         leaf = k.split(".")[-1]
         if leaf in ("ls1", "ls2"):
             assert np.all(v == vi.round_bf16(np.float32(0.1)))
@@ -44,6 +46,11 @@ def test_blob_layout_is_the_concatenation_in_order():
         assert np.array_equal(blob[off:off + n], w[name].reshape(-1)), name
         off += n
     assert w["blk0.fc1_w"].shape == (spec.dim, 2 * spec.mlp_hidden)
+    assert vi.pack_backbone(spec, w) is w["__blob__"]                       # no copy when nothing was replaced
+    w3 = dict(w)
+    w3["pos"] = w["pos"] * 2                                                # a replaced tensor forces a re-pack
+    b3 = vi.pack_backbone(spec, w3)
+    assert b3 is not w["__blob__"] and b3.size == blob.size and not np.array_equal(b3, blob)
     for kind in (vi.HEAD_SEG, vi.HEAD_DEPTH, vi.HEAD_DET):
         hw = vi.make_head_weights(spec, kind, 9)
         assert vi.pack_head(spec, kind, hw).size == vi.blob_floats(vi.head_layout(spec, kind))
@@ -77,3 +84,12 @@ def test_benchmark_config_shapes():
     assert c["cfg2"].gh == 34 and c["cfg2"].gw == 45
     assert all(s.dim == s.heads * 64 for s in c.values())
     assert c["cfg5"].fc1_out == 8192 and c["cfg5"].seg_classes == 150
+
+
+def test_sequence_frame_selection_does_not_change_the_frames():
+    spec = vi.small_spec()
+    full = list(vi.make_sequence(spec, 5, 6, 6))
+    part = list(vi.make_sequence(spec, 5, 6, 6, only={0, 4, 5}))
+    assert part[1] is None and part[2] is None and part[3] is None
+    for t in (0, 4, 5):
+        assert np.array_equal(full[t], part[t])

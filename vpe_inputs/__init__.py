@@ -21,6 +21,8 @@ available, so these generators stand in for it:
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field, replace
 from typing import Dict, List, Tuple
 
@@ -113,24 +115,23 @@ def with_(spec: ModelSpec, **kw) -> ModelSpec:
 # --------------------------------------------------------------------------------------
 def round_bf16(a: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bfloat16 (ties to even); result stays fp32."""
-    a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    u = (u + 0x7FFF + lsb) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    r &= np.uint32(0xFFFF0000)
+    return r.view(np.float32).reshape(np.shape(a))
 
 
 # --------------------------------------------------------------------------------------
 # weights
 # --------------------------------------------------------------------------------------
-def _trunc_normal(rng: np.random.Generator, shape, std: float = 0.02) -> np.ndarray:
-    n = int(np.prod(shape))
-    z = rng.standard_normal(n, dtype=np.float32)
-    bad = np.flatnonzero(np.abs(z) > 2.0)
+def _trunc_normal_into(rng: np.random.Generator, out: np.ndarray, std: float = 0.02) -> None:
+    """Fill the flat fp32 array `out` with N(0, std^2) truncated to +-2 std (by rejection)."""
+    rng.standard_normal(out.size, dtype=np.float32, out=out)
+    bad = np.flatnonzero(np.abs(out) > 2.0)
     while bad.size:
-        z[bad] = rng.standard_normal(bad.size, dtype=np.float32)
-        bad = bad[np.abs(z[bad]) > 2.0]
-    return (z * np.float32(std)).reshape(shape)
+        out[bad] = rng.standard_normal(bad.size, dtype=np.float32)
+        bad = bad[np.abs(out[bad]) > 2.0]
+    out *= np.float32(std)
 
 
 def backbone_layout(spec: ModelSpec) -> List[Tuple[str, Tuple[int, ...]]]:
@@ -188,32 +189,57 @@ def head_layout(spec: ModelSpec, kind: int) -> List[Tuple[str, Tuple[int, ...]]]
     raise ValueError(f"unknown head kind {kind}")
 
 
-def _fill(layout, rng, quantize: bool) -> Dict[str, np.ndarray]:
-    w: Dict[str, np.ndarray] = {}
-    for name, shape in layout:
+def _fill(layout, seed: int, quantize: bool) -> Dict[str, np.ndarray]:
+    """All tensors of a layout, generated straight into one flat blob (key "__blob__"); the named
+    entries are views of it.  Tensor i draws from its own stream PCG64(SeedSequence([seed, i])), so
+    tensors can be filled in parallel and do not depend on each other's sizes."""
+    sizes = [int(np.prod(shape)) for _, shape in layout]
+    blob = np.empty(int(sum(sizes)), dtype=np.float32)
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+
+    def one(i: int) -> None:
+        name, _ = layout[i]
+        dst = blob[offs[i]:offs[i + 1]]
         leaf = name.split(".")[-1]
         if leaf in ("ls1", "ls2"):
-            a = np.full(shape, 0.1, dtype=np.float32)
+            dst[:] = np.float32(0.1)
         else:
-            a = _trunc_normal(rng, shape)
+            _trunc_normal_into(np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, i]))), dst)
             if leaf in ("ln1_g", "ln2_g", "norm_g"):
-                a = a + np.float32(1.0)
-        w[name] = round_bf16(a) if quantize else a
+                dst += np.float32(1.0)
+        if quantize:
+            dst[:] = round_bf16(dst)
+
+    workers = max(1, min(16, os.cpu_count() or 1))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        list(ex.map(one, range(len(layout))))
+    w: Dict[str, np.ndarray] = {name: blob[offs[i]:offs[i + 1]].reshape(shape) for i, (name, shape) in enumerate(layout)}
+    w["__blob__"] = blob
     return w
 
 
 def make_backbone_weights(spec: ModelSpec, seed: int) -> Dict[str, np.ndarray]:
-    rng = np.random.Generator(np.random.PCG64(seed))
-    return _fill(backbone_layout(spec), rng, spec.dtype == "bf16")
+    return _fill(backbone_layout(spec), seed, spec.dtype == "bf16")
 
 
 def make_head_weights(spec: ModelSpec, kind: int, seed: int) -> Dict[str, np.ndarray]:
-    rng = np.random.Generator(np.random.PCG64(seed * 7919 + 17 * (kind + 1)))
-    return _fill(head_layout(spec, kind), rng, spec.dtype == "bf16")
+    return _fill(head_layout(spec, kind), seed * 7919 + 17 * (kind + 1), spec.dtype == "bf16")
 
 
 def pack(layout, w: Dict[str, np.ndarray]) -> np.ndarray:
-    """Concatenate tensors into the flat fp32 blob the C ABI takes."""
+    """The flat fp32 blob the C ABI takes: the tensors of `layout` concatenated in order.  A dict made by
+    make_*_weights already is one blob (unless an entry was replaced), which is returned without a copy."""
+    blob = w.get("__blob__")
+    if blob is not None:
+        off, same = 0, True
+        for name, shape in layout:
+            a = w[name]
+            n = int(np.prod(shape))
+            same = same and a.dtype == np.float32 and tuple(a.shape) == tuple(shape) and a.size == n and \
+                (n == 0 or (a.base is not None and a.__array_interface__["data"][0] == blob.__array_interface__["data"][0] + 4 * off))
+            off += n
+        if same and off == blob.size:
+            return blob
     parts = []
     for name, shape in layout:
         a = np.asarray(w[name], dtype=np.float32)
@@ -281,15 +307,24 @@ def make_batch(spec: ModelSpec, seed: int) -> np.ndarray:
     return np.stack([make_image(spec.img_h, spec.img_w, seed + b) for b in range(spec.batch)])
 
 
-def make_sequence(spec: ModelSpec, seed: int, shift_seed: int, frames: int):
+def make_sequence(spec: ModelSpec, seed: int, shift_seed: int, frames: int, only=None):
     """Generator of [B, 3, H, W] frames: each one is the previous view translated by a
-    random 0..4 px per axis (accumulated, evaluated analytically) plus new noise."""
+    random 0..4 px per axis (accumulated, evaluated analytically) plus new noise.
+
+    only: optional set of frame indices to materialise; other frames yield None but still
+    advance the shift and noise generators, so frame t is the same whatever `only` is."""
     rngs = [np.random.Generator(np.random.PCG64(seed + b)) for b in range(spec.batch)]
     fields = [make_field(spec.img_h, spec.img_w, r) for r in rngs]
     srng = np.random.Generator(np.random.PCG64(shift_seed))
     dx = dy = 0
+    shape = (3, spec.img_h, spec.img_w)
     for t in range(frames):
         if t:
             dx += int(srng.integers(0, 5))
             dy += int(srng.integers(0, 5))
-        yield np.stack([_finish(f.evaluate(dx, dy), r) for f, r in zip(fields, rngs)])
+        if only is None or t in only:
+            yield np.stack([_finish(f.evaluate(dx, dy), r) for f, r in zip(fields, rngs)])
+        else:
+            for r in rngs:
+                r.normal(0.0, 0.05, shape)      # keep the noise stream in step
+            yield None
