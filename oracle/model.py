@@ -136,8 +136,10 @@ def depth_head(spec, hw, feats, return_stages: bool = False) -> Dict[str, np.nda
         if return_stages:
             stages.append({"p": p, "z": z, "r": r})
     d = ops.conv1x1(y, hw["out_w"], hw["out_b"])
-    depth = np.maximum(ops.bilinear(d, spec.img_h, spec.img_w), 0.0)[0]
-    out = {"depth": depth}
+    pre = ops.bilinear(d, spec.img_h, spec.img_w)[0]
+    # "pre_relu" is returned as the yardstick for errors: with random weights the map can be clipped
+    # almost everywhere, and max |depth| then says nothing about the size of the signal
+    out = {"depth": np.maximum(pre, 0.0), "pre_relu": pre}
     if return_stages:
         out["stages"] = stages
         out["d16"] = d

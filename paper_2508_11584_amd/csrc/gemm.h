@@ -369,14 +369,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
         return;
     }
     if (p.epi == EPI_QKV && n0 >= 2 * p.dim) {
-        // value columns: written transposed, vt[(b dim + c)][token]; a thread takes one column and 8 tokens
-        constexpr int RG = NT / BN;
-        const int cc = tid % BN, c2 = n0 + cc - 2 * p.dim;
+        // value columns: written transposed, vt[(b dim + c)][token].  A thread takes one column and 8
+        // consecutive tokens (one 16-byte store); consecutive threads take consecutive token groups of
+        // the same column, so a column's BM tokens leave as one contiguous run.
+        constexpr int RGN = BM / 8;
         T* vt = reinterpret_cast<T*>(p.out2);
-        const float bias = p.bias[n0 + cc];
-        for (int rr = (tid / BN) * 8; rr < BM; rr += RG * 8) {
-            const int r = m0 + rr;
-            if (r >= p.M) break;
+        for (int it = tid; it < BN * RGN; it += NT) {
+            const int cc = it / RGN, rr = (it % RGN) * 8;
+            const int r = m0 + rr, c2 = n0 + cc - 2 * p.dim;
+            if (r >= p.M) continue;
+            const float bias = p.bias[n0 + cc];
             float v[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * BN + cc] + bias;

@@ -1,4 +1,4 @@
-// bf16-operand instantiations of the register-staged MFMA GEMM, and the choice between it and
+// bf16-operand instantiations of the register-staged MFMA GEMM, and the choice between them and
 // the large-tile direct-to-LDS kernel.
 #include <cstdlib>
 
@@ -6,22 +6,47 @@
 namespace vpe {
 hipError_t launch_gemm_dma_bf16(int bn, const GemmArgs& a, int amode, hipStream_t s);
 
+namespace {
+// Candidate tilings with the number of workgroups a 256-CU chip holds at once and a relative
+// efficiency per unit of tile area, from measurements on MI355X (3x3 conv 256->256 at 272x360 and
+// M=10992 N=8192 K=1536: 256x128 direct-to-LDS 920-970 TFLOP/s, 256x256 910, 128x128 register-staged
+// 770-840; the small tiles are latency-bound, their factors only rank them).
+struct Cand { int kind, bm, bn, slots; float q; };
+constexpr Cand kCands[] = {
+    {128, 256, 128, 512, 1.00f},   // direct-to-LDS, two workgroups per CU
+    {256, 256, 256, 256, 0.93f},   // direct-to-LDS, 16 waves, one workgroup per CU
+    {1, 128, 128, 512, 0.82f},     // register-staged
+    {2, 64, 128, 768, 0.40f},
+    {3, 64, 64, 1024, 0.30f},
+};
+}  // namespace
+
 hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
-    // Large problems go to the 256-row tiles (one workgroup per CU): they need enough tiles to
-    // occupy most of the 256 CUs, and byte offsets that fit 31 bits (the loader keeps them in ints).
     const char* env = getenv("VPE_GEMM_TILE");
     const int forced = env ? atoi(env) : 0;
+    // the direct-to-LDS loader keeps byte offsets in 32-bit ints
     const int64_t a_rows = amode == A_PLAIN ? (int64_t)(a.M / a.a_rpi + 1) * (a.a_istride > a.a_rpi ? a.a_istride : a.a_rpi)
                                             : (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride;
     const bool fits = a_rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
-    const int64_t t256 = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 256), t128 = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 128);
-    // Problems with enough 256 x 128 tiles to keep two workgroups on every CU busy go to the
-    // direct-to-LDS kernel; everything else stays on the register-staged tiles.
-    (void)t256;
-    int bn = fits && t128 >= 448 ? 128 : 0;
-    if (forced == 256 || forced == 128) bn = fits ? forced : 0;
-    if (forced == 1) bn = 0;
-    if (bn) return launch_gemm_dma_bf16(bn, a, amode, s);
-    return launch_gemm_t<bf16>(a, amode, s);
+    // estimated time = (tiles / resident workgroups, at least 1) x tile area / efficiency
+    int best = 3;
+    float best_cost = 0.0f;
+    for (const Cand& c : kCands) {
+        if (c.kind >= 128 && !fits) continue;
+        if (c.kind == 3 && a.epi == EPI_SWIGLU) continue;       // needs 64-column wave tiles
+        const int64_t tiles = (int64_t)cdiv(a.M, c.bm) * cdiv(a.N, c.bn);
+        // workgroups do not run in lockstep rounds: measured times grow linearly with tiles / slots
+        const float rounds = tiles > c.slots ? (float)tiles / c.slots : 1.0f;
+        const float cost = rounds * c.bm * c.bn / c.q;
+        if (best_cost == 0.0f || cost < best_cost) { best_cost = cost; best = c.kind; }
+    }
+    if ((forced == 256 || forced == 128) && fits) best = forced;
+    if (forced == 1) best = a.epi == EPI_SWIGLU ? 2 : 3;
+    switch (best) {
+        case 128: case 256: return launch_gemm_dma_bf16(best, a, amode, s);
+        case 1: return launch_tile<bf16, 128, 128, 2, 2>(a, amode, s);
+        case 2: return launch_tile<bf16, 64, 128, 2, 2>(a, amode, s);
+        default: return launch_tile<bf16, 64, 64, 2, 2>(a, amode, s);
+    }
 }
 }  // namespace vpe

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
             // value columns, written transposed: one column and 8 consecutive tokens per lane
             T* vt = reinterpret_cast<T*>(p.out2);
             for (int it = lane; it < WN * 4; it += 64) {
-                const int cc = it % WN, rr = (it / WN) * 8;
+                const int cc = it >> 2, rr = (it & 3) * 8;      // 4 lanes = 32 consecutive tokens of a column
                 const int r = rblk + rr, c2 = wcol0 + cc - 2 * p.dim;
                 if (r < p.M && wcol0 + cc < p.N) {
                     const float bias = p.bias[wcol0 + cc];

@@ -39,3 +39,11 @@ def relerr(got, ref) -> float:
     got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+def depth_err(got, ref) -> float:
+    """Depth error: max |got - depth| / max |depth before its final ReLU|.  ReLU is 1-Lipschitz, so this
+    bounds the error of the un-clipped signal; normalising by max |depth| itself would blow up on the
+    (random-weight) maps that the ReLU clips almost everywhere."""
+    got = np.asarray(got, dtype=np.float64)
+    return float(np.max(np.abs(got - ref["depth"])) / max(np.max(np.abs(ref["pre_relu"])), 1e-300))

@@ -13,7 +13,7 @@ import torch
 
 import paper_2508_11584_amd as vpe
 import vpe_inputs as vi
-from helpers import make_engine, relerr
+from helpers import depth_err, make_engine, relerr
 from oracle import model
 from test_gpu_parity import check_all
 
@@ -48,7 +48,7 @@ def test_cfg3_vitb_sequence_rates_and_parity():
     for t, g in got.items():
         feats = model.encode_image(spec, w, g["host"][0])
         e = {"feat3": relerr(g["feat3"], feats[3]),
-             "depth": relerr(g["depth"], model.depth_head(spec, hw[0], feats)["depth"])}
+             "depth": depth_err(g["depth"], model.depth_head(spec, hw[0], feats))}
         if g["seg"] is not None:
             e["seg_agree"] = float(np.mean(g["seg"] == model.seg_head(spec, hw[1], feats)["classmap"]))
         if g["det"] is not None:

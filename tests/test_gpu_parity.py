@@ -10,7 +10,7 @@ import torch
 
 import paper_2508_11584_amd as vpe
 import vpe_inputs as vi
-from helpers import make_engine, relerr
+from helpers import depth_err, make_engine, relerr
 from oracle import model, ops
 
 pytestmark = pytest.mark.gpu
@@ -72,7 +72,7 @@ def check_all(spec, seed, img_seed, kinds=("seg", "depth", "det"), flags=0, batc
             else:
                 o = model.depth_head(spec, hw[hi], ofe)
                 d = eng.head_output(hi, 0).cpu().numpy()[b]
-                report[f"b{b}.depth"] = relerr(d, o["depth"])
+                report[f"b{b}.depth"] = depth_err(d, o)
                 assert d.min() >= 0.0
     print(spec.name, {k: (v if isinstance(v, bool) else round(v, 6) if v < 0.5 else round(v, 4))
                       for k, v in report.items()}, flush=True)
