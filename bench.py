@@ -17,6 +17,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+# HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
+# calibrated against a 1 GiB copy (profiles/conv3x3_cfg2_hbm_traffic.txt); only the workload measured has one.
+TRAFFIC_BYTES = {"vits14_bf16_476x630": 125.2e6}
 
 
 def backbone_flops(spec) -> float:
@@ -37,6 +40,12 @@ def main() -> None:
     ap.add_argument("--no-graphs", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=50)
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="one frame, a 1 GiB device copy (counter calibration) and the dominant-kernel timing leg only; "
+                         "the mode the rocprofv3 --pmc passes are taken in")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel from the --pmc passes (FETCH_SIZE + WRITE_SIZE, "
+                         "calibrated); reported as roofline.traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -86,14 +95,29 @@ def main() -> None:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    if args.roofline_only:
+        shared_step(0)
+        eng.sync()
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        ms, fl, by = eng.time_kernel(3 if "depth" in kinds else 0, args.kernel_reps)
+        print(json.dumps({"mode": "roofline-only", "kernel_us": round(ms * 1e3, 2), "tflops": round(fl / ms / 1e9, 2),
+                          "algorithmic_bytes": by, "copy_bytes_each_way": 4 * a.numel()}))
+        eng.close()
+        return
+
     t_shared = timed(shared_step, args.steps, args.warmup)
     t_seq = timed(sequential_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
     t_enc = timed(encode_step, args.steps, args.warmup)
     fps = spec.batch / t_shared
     bb_tflops = backbone_flops(spec) / t_enc / 1e12
 
-    # roofline of the dominant kernel: the depth head's 3x3 convolutions (implicit GEMM on MFMA),
-    # timed with HIP events on the stream they are launched on
+    # roofline of the dominant kernel: the depth head's largest 3x3 convolution (implicit GEMM on MFMA,
+    # 43 % of the frame's FLOP in one launch), timed with HIP events on the stream it is launched on
     roofline = None
     kern = {}
     shared_step(0)
@@ -105,7 +129,8 @@ def main() -> None:
             peak = MFMA_PEAK_TFLOPS[spec.dtype]
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
-                        "frac": round(ach / peak, 4), "traffic": None, "us_per_launch": round(ms * 1e3, 2)}
+                        "frac": round(ach / peak, 4), "traffic": args.traffic_bytes if args.traffic_bytes is not None else TRAFFIC_BYTES.get(spec.name), "us_per_launch": round(ms * 1e3, 2),
+                        "algorithmic_bytes": by, "algorithmic_flops": fl}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

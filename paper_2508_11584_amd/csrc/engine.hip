@@ -731,14 +731,12 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
             } else if (which == 2) {
                 HIPCHK(e, launch_layernorm(dt, e->x, T, D, e->blk[0].ln1_g, e->blk[0].ln1_b, e->cfg.ln_eps, e->u, s));
             } else {
-                // the three large 3x3 convolutions of the depth head (stages 1..3), same shapes and
-                // buffers as in a head run; timing does not depend on the values in z
-                for (int st = 1; st < 4; ++st) {
-                    const int hs = e->gh << st, wsz = e->gw << st;
-                    GemmArgs a = conv3_gemm(*e, dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[st], dh->fuse_b[st], dh->ch);
-                    a.out = dh->r; a.ldo = dh->ch;
-                    HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
-                }
+                // the largest 3x3 convolution of the depth head (last fusion stage, 8x the patch grid), same
+                // shape, weights and buffers as in a head run; its timing does not depend on the values in z
+                const int hs = e->gh << 3, wsz = e->gw << 3;
+                GemmArgs a = conv3_gemm(*e, dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[3], dh->fuse_b[3], dh->ch);
+                a.out = dh->r; a.ldo = dh->ch;
+                HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
             }
         }
         if (timed) HIPCHK(e, hipEventRecord(t1, s));
@@ -758,8 +756,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
     else if (which == 1) { fl = 4.0 * e->B * (double)e->N * e->N * D; by = esz * 4.0 * T * D; }
     else if (which == 2) { fl = 8.0 * T * D; by = (4.0 + esz) * T * D; }
     else {
-        launches = 3 * reps;
-        const double ch = dh->ch, pix = (double)e->B * e->P * (4 + 16 + 64) / 3.0;   // mean over the three launches
+        const double ch = dh->ch, pix = (double)e->B * e->P * 64.0;
         fl = 2.0 * 9.0 * ch * ch * pix;
         by = esz * (2.0 * pix * ch + 9.0 * ch * ch);
     }
