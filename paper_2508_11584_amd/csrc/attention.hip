@@ -15,14 +15,9 @@ static hipError_t launch_variant(int variant, const AttnArgs& a, hipStream_t s, 
     if constexpr (sizeof(T) == 2) {
         switch (variant) {
             case 214: return launch_attention_variant<T, 2, 1, 4>(a, s, cfg);
-            case 218: return launch_attention_variant<T, 2, 1, 8>(a, s, cfg);
-            case 118: return launch_attention_variant<T, 1, 1, 8>(a, s, cfg);
             case 122: return launch_attention_variant<T, 1, 2, 2>(a, s, cfg);
             case 124: return launch_attention_variant<T, 1, 2, 4>(a, s, cfg);
-            case 222: return launch_attention_variant<T, 2, 2, 2>(a, s, cfg);
             case 224: return launch_attention_variant<T, 2, 2, 4>(a, s, cfg);
-            case 241: return launch_attention_variant<T, 2, 4, 1>(a, s, cfg);
-            case 221: return launch_attention_variant<T, 2, 2, 1>(a, s, cfg);
             default: break;
         }
     }
@@ -31,7 +26,7 @@ static hipError_t launch_variant(int variant, const AttnArgs& a, hipStream_t s, 
 
 // LDS opt-in for every instantiation; called once at engine creation, outside any stream capture.
 hipError_t configure_attention() {
-    static const int all[] = {114, 141, 214, 218, 118, 122, 124, 222, 224, 241, 221};
+    static const int all[] = {114, 141, 214, 122, 124, 224};
     AttnArgs a{};
     for (int v : all) {
         hipError_t rc = launch_variant<bf16>(v, a, nullptr, true);
@@ -45,7 +40,10 @@ hipError_t configure_attention() {
 hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {
     const char* env = getenv("VPE_ATTN_VARIANT");
     const int forced = env ? atoi(env) : 0;
-    // few (batch x head) pairs: split the keys over the waves of a workgroup; many: share key tiles
+    // Workgroup shapes measured on MI355X (QB, QW, KW = query blocks per wave, query waves, key waves):
+    //   ViT-S 476x630 (6 heads, N = 1531):   (1,2,4) 16 us   (1,2,2) 20   (2,1,4) 23   (2,2,4) 24   (1,1,4) 30   (1,4,1) 32
+    //   ViT-L 518x518 batch 4 (64 x N 1374): (2,2,4) 76 us   (1,4,1) 82   (1,2,2) 84   (1,2,4) 97   (2,1,4) 158  (1,1,4) 211
+    // VPE_ATTN_VARIANT = 100 QB + 10 QW + KW overrides the choice (tuning aid).
     const int64_t qblocks = (int64_t)cdiv(a.N, 32) * a.B * a.heads;
     int variant = qblocks >= 2048 ? 224 : 124;
     if (forced) variant = forced;

@@ -183,6 +183,96 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& p, int r, int c, 
     }
 }
 
+// Block-level epilogue shared by the register-staged kernels.  The accumulators go through LDS
+// (`smem`, free after the k loop, at least BM * BN * 4 bytes) as a row-major fp32 tile, so that
+// each thread then owns 8 consecutive columns of a row: one row-index computation and 16-byte
+// coalesced global accesses per chunk instead of 64 scattered 2-byte stores per lane.
+// accumulator element v of lane (g, li) in block (i, j): row = 32 i + 8 (v / 4) + 4 g + v % 4, col = 32 j + li
+template <typename T, int BM, int BN, int WGM, int WGN>
+__device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                               char* smem, int m0, int n0) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int g = lane >> 5, li = lane & 31;
+    float* sC = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                sC[(wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * BN + wn * WN + j * 32 + li] = acc[i][j][v];
+    __syncthreads();
+
+    if (p.epi == EPI_SWIGLU) {
+        // physical columns come in groups of 64: 32 gate columns, then their 32 linear partners;
+        // a thread takes 8 gate columns and their partners and writes 8 hidden units
+        constexpr int CG = BN / 16, RPASS = NT / CG;
+        const int cg = tid % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
+        const int ca = n0 + grp * 64 + j0;            // physical gate column
+        if (ca + 40 <= p.N) {
+            const int oc = (ca >> 6) * 32 + j0;       // hidden unit index
+            T* out = reinterpret_cast<T*>(p.out);
+            for (int rr = tid / CG; rr < BM; rr += RPASS) {
+                const int r = m0 + rr;
+                if (r >= p.M) break;
+                const float* src = sC + rr * BN + grp * 64 + j0;
+                float h[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float a = src[i] + p.bias[ca + i], b = src[32 + i] + p.bias[ca + 32 + i];
+                    h[i] = a / (1.0f + __expf(-a)) * b;
+                }
+                store8(out + (int64_t)r * p.ldo + oc, h);
+            }
+        }
+        return;
+    }
+    if (p.epi == EPI_QKV && n0 >= 2 * p.dim) {
+        // value columns: written transposed, vt[(b dim + c)][token].  A thread takes one column and 8
+        // consecutive tokens (one 16-byte store); consecutive threads take consecutive token groups of
+        // the same column, so a column's BM tokens leave as one contiguous run.
+        constexpr int RGN = BM / 8;
+        T* vt = reinterpret_cast<T*>(p.out2);
+        for (int it = tid; it < BN * RGN; it += NT) {
+            const int cc = it / RGN, rr = (it % RGN) * 8;
+            const int r = m0 + rr, c2 = n0 + cc - 2 * p.dim;
+            if (r >= p.M) continue;
+            const float bias = p.bias[n0 + cc];
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * BN + cc] + bias;
+            const int b = r / p.ntok, n = r % p.ntok;
+            if (n + 8 <= p.ntok && (n & 7) == 0) {
+                store8(vt + ((int64_t)b * p.dim + c2) * p.npad + n, v);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int rk = r + k;
+                    if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
+                }
+            }
+        }
+        return;
+    }
+    {
+        constexpr int CG = BN / 8, RPASS = NT / CG;
+        const int cg = tid % CG, c = n0 + cg * 8;
+        if (c < p.N) {
+            for (int rr = tid / CG; rr < BM; rr += RPASS) {
+                const int r = m0 + rr;
+                if (r >= p.M) break;
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8 + 4);
+                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                epilogue_chunk<T>(p, r, c, v);
+            }
+        }
+    }
+}
+
 template <typename T, int BM, int BN, int WGM, int WGN, int AMODE>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs p) {
     constexpr int NT = 64 * WGM * WGN;
@@ -328,87 +418,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
         __syncthreads();
     }
 
-    // ---------------------------------------------------------------- epilogue
-    // The accumulators go through LDS (free after the k loop) as a row-major fp32 tile, so that
-    // each thread then owns 8 consecutive columns of a row: one row-index computation and
-    // 16-byte coalesced global accesses per chunk instead of 64 scattered 2-byte stores per lane.
-    // accumulator element v of lane (g, li) in block (i, j): row = 32 i + 8 (v / 4) + 4 g + v % 4, col = 32 j + li
     static_assert(BM * BN * 4 <= 2 * STAGE, "accumulator tile must fit the stage buffers");
-    float* sC = reinterpret_cast<float*>(smem);
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                sC[(wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * BN + wn * WN + j * 32 + li] = acc[i][j][v];
-    __syncthreads();
-
-    if (p.epi == EPI_SWIGLU) {
-        // physical columns come in groups of 64: 32 gate columns, then their 32 linear partners;
-        // a thread takes 8 gate columns and their partners and writes 8 hidden units
-        constexpr int CG = BN / 16, RPASS = NT / CG;
-        const int cg = tid % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
-        const int ca = n0 + grp * 64 + j0;            // physical gate column
-        if (ca + 40 <= p.N) {
-            const int oc = (ca >> 6) * 32 + j0;       // hidden unit index
-            T* out = reinterpret_cast<T*>(p.out);
-            for (int rr = tid / CG; rr < BM; rr += RPASS) {
-                const int r = m0 + rr;
-                if (r >= p.M) break;
-                const float* src = sC + rr * BN + grp * 64 + j0;
-                float h[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float a = src[i] + p.bias[ca + i], b = src[32 + i] + p.bias[ca + 32 + i];
-                    h[i] = a / (1.0f + __expf(-a)) * b;
-                }
-                store8(out + (int64_t)r * p.ldo + oc, h);
-            }
-        }
-        return;
-    }
-    if (p.epi == EPI_QKV && n0 >= 2 * p.dim) {
-        // value columns: written transposed, vt[(b dim + c)][token].  A thread takes one column and 8
-        // consecutive tokens (one 16-byte store); consecutive threads take consecutive token groups of
-        // the same column, so a column's BM tokens leave as one contiguous run.
-        constexpr int RGN = BM / 8;
-        T* vt = reinterpret_cast<T*>(p.out2);
-        for (int it = tid; it < BN * RGN; it += NT) {
-            const int cc = it / RGN, rr = (it % RGN) * 8;
-            const int r = m0 + rr, c2 = n0 + cc - 2 * p.dim;
-            if (r >= p.M) continue;
-            const float bias = p.bias[n0 + cc];
-            float v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * BN + cc] + bias;
-            const int b = r / p.ntok, n = r % p.ntok;
-            if (n + 8 <= p.ntok && (n & 7) == 0) {
-                store8(vt + ((int64_t)b * p.dim + c2) * p.npad + n, v);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int rk = r + k;
-                    if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
-                }
-            }
-        }
-        return;
-    }
-    {
-        constexpr int CG = BN / 8, RPASS = NT / CG;
-        const int cg = tid % CG, c = n0 + cg * 8;
-        if (c < p.N) {
-            for (int rr = tid / CG; rr < BM; rr += RPASS) {
-                const int r = m0 + rr;
-                if (r >= p.M) break;
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8);
-                const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8 + 4);
-                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                epilogue_chunk<T>(p, r, c, v);
-            }
-        }
-    }
+    block_epilogue<T, BM, BN, WGM, WGN>(p, acc, smem, m0, n0);
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN>

@@ -6,12 +6,6 @@
 
 namespace vpe {
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
 // LayerNorm over the last axis of the fp32 residual stream: y = g (x - mean) / sqrt(var + eps) + b
 // with the biased variance; statistics in fp32 (mean first, then centred second moment, both
 // from registers).  One wave per row, 4 rows per workgroup.  D multiple of 64, D <= 64 * 32.
@@ -135,19 +129,28 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const T* __restrict__ in, i
     if (lane == 0) out[row] = acc + bias;
 }
 
-// Per-row argmax over the first C of `ld` fp32 values (ties -> lowest index); one thread per row.
+// Per-row argmax over the first C of `ld` fp32 values (ties -> lowest index); one wave per row:
+// each lane scans a strided subset in ascending order, then a butterfly keeps the larger value and,
+// among equal values, the lower index.
 __global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ in, int64_t rows, int C,
                                                           int ld, uint8_t* __restrict__ out) {
-    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (r >= rows) return;
     const float* p = in + r * ld;
-    int best = 0;
-    float bv = p[0];
-    for (int c = 1; c < C; ++c) {
+    float bv = -INFINITY;
+    int best = 0x7fffffff;
+    for (int c = lane; c < C; c += 64) {
         const float v = p[c];
         if (v > bv) { bv = v; best = c; }
     }
-    out[r] = (uint8_t)best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o);
+        const int oi = __shfl_xor(best, o);
+        if (ov > bv || (ov == bv && oi < best)) { bv = ov; best = oi; }
+    }
+    if (lane == 0) out[r] = (uint8_t)best;
 }
 
 }  // namespace vpe

@@ -42,7 +42,7 @@ hipError_t launch_rowdot(int dtype, const void* in, int64_t rows, int C, const f
 }
 
 hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint8_t* out, hipStream_t s) {
-    hipLaunchKernelGGL(argmax_rows_kernel, dim3(blocks_for(rows, 256)), dim3(256), 0, s, in, rows, C, ld, out);
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(blocks_for(rows, 4)), dim3(256), 0, s, in, rows, C, ld, out);
     return hipGetLastError();
 }
 
