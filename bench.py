@@ -38,6 +38,9 @@ def main() -> None:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload)")
     ap.add_argument("--no-graphs", action="store_true")
+    ap.add_argument("--ring-slots", type=int, default=2)
+    ap.add_argument("--encoder-lanes", type=int, default=1,
+                    help="2 = the encoder passes of consecutive frames overlap on the GPU (throughput pipelining)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--roofline-only", action="store_true",
@@ -61,7 +64,7 @@ def main() -> None:
     wseed, iseed = vi.SEEDS[args.config]
     kinds = ("seg",) if args.config == "cfg1" else ("seg", "depth", "det")
     flags = 0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS
-    eng, w, hw = make_engine(spec, wseed, kinds=kinds, ring_slots=2, flags=flags)
+    eng, w, hw = make_engine(spec, wseed, kinds=kinds, ring_slots=args.ring_slots, flags=flags, encoder_lanes=args.encoder_lanes)
     images_np = vi.make_batch(spec, iseed)
     # two distinct resident frames, alternated, so no step can reuse the previous step's result
     frames = [torch.from_numpy(images_np).cuda(), torch.from_numpy(np.ascontiguousarray(images_np[..., ::-1])).cuda()]
@@ -150,7 +153,7 @@ def main() -> None:
         "ms_per_step": round(t_shared * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "batch": spec.batch, "img": [spec.img_h, spec.img_w], "tokens": spec.tokens,
-                   "heads": list(kinds), "ring_slots": 2, "hip_graphs": not args.no_graphs},
+                   "heads": list(kinds), "ring_slots": args.ring_slots, "encoder_lanes": args.encoder_lanes, "hip_graphs": not args.no_graphs},
         "backbone_tflops": round(bb_tflops, 2), "backbone_ms": round(t_enc * 1e3, 4),
         "backbone_mfma_frac": round(bb_tflops / MFMA_PEAK_TFLOPS[spec.dtype], 4),
         "sequential_baseline_fps": round(spec.batch / t_seq, 2), "shared_vs_sequential": round(t_seq / t_shared, 3),

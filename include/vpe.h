@@ -18,7 +18,7 @@
  *   - "device" pointers are HIP device addresses on the current device; "host" pointers
  *     are ordinary process memory.
  *   - streams are hipStream_t passed as void*; NULL selects the engine's own stream for
- *     that call (one encoder stream, one stream per head, all at default priority).
+  *     that call (one stream per encoder lane, one stream per head, all at default priority).
  *   - vpe_encode and vpe_run_head only enqueue work; vpe_sync blocks until it is done.
  *   - an engine may be driven from one host thread at a time.
  */
@@ -82,7 +82,9 @@ typedef struct {
     int32_t ring_slots;   /* >= 1; 2 or more lets encode(f+1) overlap heads(f) */
     int32_t flags;        /* VPE_FLAG_* */
     float   ln_eps;
-    int32_t reserved;
+    int32_t encoder_lanes; /* 1 or 2 (0 = 1): encoder scratch sets and streams; with 2 (and ring_slots >= 2) the
+                              encoder passes of consecutive frames overlap on the GPU -- throughput pipelining,
+                              per-frame results are unchanged */
     const void* weights;  /* host, fp32 */
     uint64_t weights_bytes;
 } vpe_backbone_cfg;

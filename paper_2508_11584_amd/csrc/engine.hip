@@ -87,18 +87,27 @@ struct vpe_engine {
     std::vector<BlockW> blk;
     // encoder scratch
     void* zeros = nullptr;               // 256 bytes that stay zero (padding taps of the 3x3 convolutions)
-    void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
-    float* x = nullptr;
+    // Encoder lanes: `lanes` complete scratch sets, each with its own stream.  Frame f is encoded on lane
+    // f % lanes, so with two lanes the encoder passes of consecutive frames overlap on the GPU (the ViT-S
+    // kernels are too small to fill 256 CUs on their own); results per frame are unchanged.
+    struct Lane {
+        void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
+        float* x = nullptr;
+        hipStream_t stream = nullptr;
+        hipEvent_t done = nullptr;      // completion of the lane's most recent encode
+        bool used = false;
+    };
+    int lanes = 1;
+    Lane lane[2];
     // ring
     std::vector<void*> feat;             // [S][4]
     std::vector<int64_t> slot_frame;     // frame held by each slot, -1 = none
     std::vector<hipEvent_t> ready;       // [S]
     std::vector<hipEvent_t> done;        // [S][n_heads]
     std::vector<char> done_set;          // [S][n_heads]
-    std::vector<hipGraphExec_t> enc_graphs;   // [S]
-    int last_enc_slot = -1;
+    std::vector<hipGraphExec_t> enc_graphs;   // [S][lanes]
     std::vector<Head> heads;
-    hipStream_t enc_stream = nullptr, cap_stream = nullptr;
+    hipStream_t cap_stream = nullptr;
     int64_t frames = 0;
     std::string err;
 
@@ -189,6 +198,7 @@ void derive(vpe_engine& e, const vpe_backbone_cfg& c, const vpe_head_cfg* heads,
     e.N = 1 + e.R + e.P; e.T = e.B * e.N;
     e.npad = (int)rup(e.N, 64);
     e.S = c.ring_slots;
+    e.lanes = c.encoder_lanes >= 2 && c.ring_slots >= 2 ? 2 : 1;     // two encodes in flight need two slots
     e.heads.assign(n_heads, Head());
     for (int i = 0; i < n_heads; ++i) {
         e.heads[i].kind = heads[i].kind;
@@ -221,13 +231,16 @@ void layout(vpe_engine& e, Bump& b) {
     }
     e.norm_g = f32(D); e.norm_b = f32(D);
     e.zeros = b.take(256);
-    e.apatch = b.take(B * P * KPATCH_PAD * esz);
-    e.x = f32(T * D);
-    e.u = b.take(T * D * esz);
-    e.qk = b.take(T * 2 * D * esz);
-    e.vt = b.take(B * D * e.npad * esz);
-    e.att = b.take(T * D * esz);
-    e.hid = b.take(T * e.Mh * esz);
+    for (int l = 0; l < e.lanes; ++l) {
+        vpe_engine::Lane& L = e.lane[l];
+        L.apatch = b.take(B * P * KPATCH_PAD * esz);
+        L.x = f32(T * D);
+        L.u = b.take(T * D * esz);
+        L.qk = b.take(T * 2 * D * esz);
+        L.vt = b.take(B * D * e.npad * esz);
+        L.att = b.take(T * D * esz);
+        L.hid = b.take(T * e.Mh * esz);
+    }
     e.feat.resize((size_t)e.S * 4);
     for (auto& f : e.feat) f = b.take(T * D * esz);
     for (auto& h : e.heads) {
@@ -366,47 +379,48 @@ GemmArgs plain_gemm(const void* A, int64_t lda, const void* W, const float* bias
 }
 
 // ------------------------------------------------------------------ launch sequences
-int enqueue_encoder_body(vpe_engine& e, int slot, hipStream_t s) {
+int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
     const int D = e.D, T = e.T, dt = e.bf;
+    const vpe_engine::Lane& L = e.lane[lane];
     {   // patch embedding: [B P][640] x [D][640]^T + bias + pos -> residual stream rows of the patches
-        GemmArgs a = plain_gemm(e.apatch, KPATCH_PAD, e.patch_w, e.patch_b, e.B * e.P, D, KPATCH_PAD);
-        a.epi = EPI_PATCH; a.out = e.x; a.ldo = D; a.pos = e.pos;
+        GemmArgs a = plain_gemm(L.apatch, KPATCH_PAD, e.patch_w, e.patch_b, e.B * e.P, D, KPATCH_PAD);
+        a.epi = EPI_PATCH; a.out = L.x; a.ldo = D; a.pos = e.pos;
         a.o_rpi = e.P; a.o_istride = e.N; a.o_off = 1 + e.R;
         HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
     }
     int tap = 0;
     for (int l = 0; l < e.L; ++l) {
         const BlockW& w = e.blk[l];
-        HIPCHK(&e, launch_layernorm(dt, e.x, T, D, w.ln1_g, w.ln1_b, e.cfg.ln_eps, e.u, s));
+        HIPCHK(&e, launch_layernorm(dt, L.x, T, D, w.ln1_g, w.ln1_b, e.cfg.ln_eps, L.u, s));
         {
-            GemmArgs a = plain_gemm(e.u, D, w.qkv_w, w.qkv_b, T, 3 * D, D);
-            a.epi = EPI_QKV; a.out = e.qk; a.ldo = 2 * D; a.out2 = e.vt; a.ntok = e.N; a.npad = e.npad; a.dim = D;
+            GemmArgs a = plain_gemm(L.u, D, w.qkv_w, w.qkv_b, T, 3 * D, D);
+            a.epi = EPI_QKV; a.out = L.qk; a.ldo = 2 * D; a.out2 = L.vt; a.ntok = e.N; a.npad = e.npad; a.dim = D;
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         {
-            AttnArgs a{e.qk, e.vt, e.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f};
+            AttnArgs a{L.qk, L.vt, L.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f};
             HIPCHK(&e, launch_attention(dt, a, s));
         }
         {
-            GemmArgs a = plain_gemm(e.att, D, w.proj_w, w.proj_b, T, D, D);
-            a.epi = EPI_RESID; a.out = e.x; a.ldo = D; a.gamma = w.ls1;
+            GemmArgs a = plain_gemm(L.att, D, w.proj_w, w.proj_b, T, D, D);
+            a.epi = EPI_RESID; a.out = L.x; a.ldo = D; a.gamma = w.ls1;
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
-        HIPCHK(&e, launch_layernorm(dt, e.x, T, D, w.ln2_g, w.ln2_b, e.cfg.ln_eps, e.u, s));
+        HIPCHK(&e, launch_layernorm(dt, L.x, T, D, w.ln2_g, w.ln2_b, e.cfg.ln_eps, L.u, s));
         {
-            GemmArgs a = plain_gemm(e.u, D, w.fc1_w, w.fc1_b, T, e.F, D);
-            a.out = e.hid; a.ldo = e.Mh;
+            GemmArgs a = plain_gemm(L.u, D, w.fc1_w, w.fc1_b, T, e.F, D);
+            a.out = L.hid; a.ldo = e.Mh;
             if (e.cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
             else a.act = ACT_GELU;
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         {
-            GemmArgs a = plain_gemm(e.hid, e.Mh, w.fc2_w, w.fc2_b, T, D, e.Mh);
-            a.epi = EPI_RESID; a.out = e.x; a.ldo = D; a.gamma = w.ls2;
+            GemmArgs a = plain_gemm(L.hid, e.Mh, w.fc2_w, w.fc2_b, T, D, e.Mh);
+            a.epi = EPI_RESID; a.out = L.x; a.ldo = D; a.gamma = w.ls2;
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         if (tap < 4 && l + 1 == e.cfg.taps[tap]) {
-            HIPCHK(&e, launch_layernorm(dt, e.x, T, D, e.norm_g, e.norm_b, e.cfg.ln_eps, e.feat[slot * 4 + tap], s));
+            HIPCHK(&e, launch_layernorm(dt, L.x, T, D, e.norm_g, e.norm_b, e.cfg.ln_eps, e.feat[slot * 4 + tap], s));
             ++tap;
         }
     }
@@ -494,7 +508,10 @@ void destroy_engine(vpe_engine* e) {
         }
         for (auto ev : e->ready) if (ev) (void)hipEventDestroy(ev);
         for (auto ev : e->done) if (ev) (void)hipEventDestroy(ev);
-        if (e->enc_stream) (void)hipStreamDestroy(e->enc_stream);
+        for (auto& L : e->lane) {
+            if (L.stream) (void)hipStreamDestroy(L.stream);
+            if (L.done) (void)hipEventDestroy(L.done);
+        }
         if (e->cap_stream) (void)hipStreamDestroy(e->cap_stream);
         if (e->owns_ws && e->ws) (void)hipFree(e->ws);
     }
@@ -572,7 +589,10 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     (void)hipFree(staging);
     if (rc) return bail(rc);
 
-    if (hip(hipStreamCreateWithFlags(&e->enc_stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+    for (int l = 0; l < e->lanes; ++l) {
+        if (hip(hipStreamCreateWithFlags(&e->lane[l].stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+        if (hip(hipEventCreateWithFlags(&e->lane[l].done, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
+    }
     if (hip(hipStreamCreateWithFlags(&e->cap_stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
     e->ready.assign(e->S, nullptr);
     e->done.assign((size_t)e->S * std::max(nh, 1), nullptr);
@@ -580,7 +600,7 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
         if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
     for (auto& ev : e->done)
         if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
-    e->enc_graphs.assign(e->S, nullptr);
+    e->enc_graphs.assign((size_t)e->S * e->lanes, nullptr);
     for (auto& h : e->heads) {
         if (hip(hipStreamCreateWithFlags(&h.stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
         h.graphs.assign(e->S, nullptr);
@@ -598,25 +618,29 @@ int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out) 
     const int slot = (int)(frame % e->S);
     const int nh = (int)e->heads.size();
     if (!e->host_only) {
-        hipStream_t s = stream ? (hipStream_t)stream : e->enc_stream;
-        // the slot's previous frame may still be read by heads: wait for them on the GPU
+        const int ln = (int)(frame % e->lanes);
+        vpe_engine::Lane& L = e->lane[ln];
+        hipStream_t s = stream ? (hipStream_t)stream : L.stream;
+        // the slot's previous frame may still be read by heads (or still be written): wait on the GPU
         for (int h = 0; h < nh; ++h)
             if (e->done_set[(size_t)slot * nh + h]) HIPCHK(e, hipStreamWaitEvent(s, e->done[(size_t)slot * nh + h], 0));
-        // the encoder's scratch is single-instance: order after the previous encode
-        if (e->last_enc_slot >= 0) HIPCHK(e, hipStreamWaitEvent(s, e->ready[e->last_enc_slot], 0));
-        HIPCHK(e, launch_im2col(e->bf, images, e->B, e->H, e->W, KPATCH_PAD, e->apatch, e->special, 1 + e->R,
-                                e->N, e->D, e->x, s));
+        if (e->slot_frame[slot] >= 0) HIPCHK(e, hipStreamWaitEvent(s, e->ready[slot], 0));
+        // a lane's scratch is single-instance: order after the lane's previous encode
+        if (L.used) HIPCHK(e, hipStreamWaitEvent(s, L.done, 0));
+        HIPCHK(e, launch_im2col(e->bf, images, e->B, e->H, e->W, KPATCH_PAD, L.apatch, e->special, 1 + e->R,
+                                e->N, e->D, L.x, s));
         if (e->graphs) {
-            if (!e->enc_graphs[slot])
-                TRY(capture(*e, &e->enc_graphs[slot], [&](hipStream_t cs) { return enqueue_encoder_body(*e, slot, cs); }));
-            HIPCHK(e, hipGraphLaunch(e->enc_graphs[slot], s));
+            hipGraphExec_t& ge = e->enc_graphs[(size_t)slot * e->lanes + ln];
+            if (!ge) TRY(capture(*e, &ge, [&](hipStream_t cs) { return enqueue_encoder_body(*e, slot, ln, cs); }));
+            HIPCHK(e, hipGraphLaunch(ge, s));
         } else {
-            TRY(enqueue_encoder_body(*e, slot, s));
+            TRY(enqueue_encoder_body(*e, slot, ln, s));
         }
+        HIPCHK(e, hipEventRecord(L.done, s));
+        L.used = true;
         HIPCHK(e, hipEventRecord(e->ready[slot], s));
     }
     for (int h = 0; h < nh; ++h) e->done_set[(size_t)slot * nh + h] = 0;
-    e->last_enc_slot = slot;
     e->slot_frame[slot] = frame;
     e->frames = frame + 1;
     out->slot = slot;
@@ -709,7 +733,8 @@ int vpe_stats(vpe_engine* e, int64_t* frames, int64_t* head_runs, int64_t* head_
 int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes) {
     if (!e) return VPE_EINVAL;
     if (e->host_only || reps < 1 || !ms_per_launch) return e->fail(VPE_EINVAL, "bad arguments");
-    hipStream_t s = e->enc_stream;
+    hipStream_t s = e->lane[0].stream;
+    const vpe_engine::Lane& L0 = e->lane[0];
     hipEvent_t t0, t1;
     HIPCHK(e, hipEventCreate(&t0));
     HIPCHK(e, hipEventCreate(&t1));
@@ -722,14 +747,14 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
         if (timed) HIPCHK(e, hipEventRecord(t0, s));
         for (int i = 0; i < (timed ? reps : 1); ++i) {
             if (which == 0) {
-                GemmArgs a = plain_gemm(e->u, D, e->blk[0].qkv_w, e->blk[0].qkv_b, T, 3 * D, D);
-                a.epi = EPI_QKV; a.out = e->qk; a.ldo = 2 * D; a.out2 = e->vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
+                GemmArgs a = plain_gemm(L0.u, D, e->blk[0].qkv_w, e->blk[0].qkv_b, T, 3 * D, D);
+                a.epi = EPI_QKV; a.out = L0.qk; a.ldo = 2 * D; a.out2 = L0.vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
             } else if (which == 1) {
-                AttnArgs a{e->qk, e->vt, e->att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f};
+                AttnArgs a{L0.qk, L0.vt, L0.att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f};
                 HIPCHK(e, launch_attention(dt, a, s));
             } else if (which == 2) {
-                HIPCHK(e, launch_layernorm(dt, e->x, T, D, e->blk[0].ln1_g, e->blk[0].ln1_b, e->cfg.ln_eps, e->u, s));
+                HIPCHK(e, launch_layernorm(dt, L0.x, T, D, e->blk[0].ln1_g, e->blk[0].ln1_b, e->cfg.ln_eps, L0.u, s));
             } else {
                 // the largest 3x3 convolution of the depth head (last fusion stage, 8x the patch grid), same
                 // shape, weights and buffers as in a head run; its timing does not depend on the values in z

@@ -113,11 +113,14 @@ def test_single_slot_ring_and_back_to_back_frames_stay_correct():
         eng.close()
 
 
-def test_unsynchronised_stream_of_frames_ends_in_the_right_state():
-    # 40 frames pushed without any host sync, ring of 2, rates 1/2/3: the final outputs must be those of
-    # the last frame each head was due on, computed in isolation
+@pytest.mark.parametrize("lanes,slots", [(1, 2), (2, 2), (2, 3)])
+def test_unsynchronised_stream_of_frames_ends_in_the_right_state(lanes, slots):
+    # 40 frames pushed without any host sync, rates 1/2/3, one or two encoder lanes (two = the encoder
+    # passes of consecutive frames overlap): the final outputs must be those of the last frame each head
+    # was due on, computed in isolation
     fs = frames(4, seed=500)
-    eng, _, _ = make_engine(SPEC, 15, every_n=(1, 2, 3), flags=vpe.VPE_FLAG_GRAPHS)
+    eng, _, _ = make_engine(SPEC, 15, every_n=(1, 2, 3), flags=vpe.VPE_FLAG_GRAPHS, ring_slots=slots,
+                            encoder_lanes=lanes)
     n = 40
     for i in range(n):
         fh = eng.encode(fs[i % 4])
@@ -196,3 +199,27 @@ def test_batch_elements_are_independent_on_the_device():
         assert torch.equal(eng1.head_output(1, 0)[0], batched[1][b])
         assert torch.equal(eng1.head_output(2, 0)[0], batched[2][b])
     eng1.close()
+
+
+def test_two_encoder_lanes_give_the_same_frames_as_one():
+    fs = frames(6, seed=700)
+    res = {}
+    for lanes in (1, 2):
+        eng, _, _ = make_engine(SPEC, 19, flags=vpe.VPE_FLAG_GRAPHS, ring_slots=2, encoder_lanes=lanes)
+        feats = []
+        handles = []
+        for f in fs[:2]:                          # two frames in flight before anything is read
+            handles.append(eng.encode(f))
+        eng.sync()
+        feats += [eng.feat_view(h, 3).clone() for h in handles]
+        for f in fs[2:]:
+            fh = eng.encode(f)
+            for h in range(3):
+                eng.run_head(h, fh)
+            eng.sync()
+            feats.append(eng.feat_view(fh, 3).clone())
+            feats += outputs(eng)
+        res[lanes] = feats
+        eng.close()
+    for a, b in zip(res[1], res[2]):
+        assert torch.equal(a, b)
