@@ -38,8 +38,8 @@ def main() -> None:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload)")
     ap.add_argument("--no-graphs", action="store_true")
-    ap.add_argument("--ring-slots", type=int, default=2)
-    ap.add_argument("--encoder-lanes", type=int, default=1,
+    ap.add_argument("--ring-slots", type=int, default=3)
+    ap.add_argument("--encoder-lanes", type=int, default=2,
                     help="2 = the encoder passes of consecutive frames overlap on the GPU (throughput pipelining)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=50)
@@ -117,6 +117,16 @@ def main() -> None:
     t_seq = timed(sequential_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
     t_enc = timed(encode_step, args.steps, args.warmup)
     fps = spec.batch / t_shared
+
+    # unloaded latency of one frame as the host sees it: submit encode + heads on an idle GPU, wait for all
+    lat = []
+    for i in range(min(args.steps, 100)):
+        t0 = time.perf_counter()
+        shared_step(i)
+        eng.sync()
+        lat.append((time.perf_counter() - t0) * 1e3)
+    lat.sort()
+    latency = {"p10": round(lat[len(lat) // 10], 4), "median": round(lat[len(lat) // 2], 4), "p90": round(lat[(9 * len(lat)) // 10], 4)}
     bb_tflops = backbone_flops(spec) / t_enc / 1e12
 
     # roofline of the dominant kernel: the depth head's largest 3x3 convolution (implicit GEMM on MFMA,
@@ -157,7 +167,7 @@ def main() -> None:
         "backbone_tflops": round(bb_tflops, 2), "backbone_ms": round(t_enc * 1e3, 4),
         "backbone_mfma_frac": round(bb_tflops / MFMA_PEAK_TFLOPS[spec.dtype], 4),
         "sequential_baseline_fps": round(spec.batch / t_seq, 2), "shared_vs_sequential": round(t_seq / t_shared, 3),
-        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "frame_latency_ms": latency, "kernels": kern, "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))
     eng.close()

@@ -82,9 +82,13 @@ typedef struct {
     int32_t ring_slots;   /* >= 1; 2 or more lets encode(f+1) overlap heads(f) */
     int32_t flags;        /* VPE_FLAG_* */
     float   ln_eps;
-    int32_t encoder_lanes; /* 1 or 2 (0 = 1): encoder scratch sets and streams; with 2 (and ring_slots >= 2) the
-                              encoder passes of consecutive frames overlap on the GPU -- throughput pipelining,
+    int32_t encoder_lanes; /* 1..4 (0 = 1; at most ring_slots): encoder scratch sets and streams; with k >= 2 the
+                              encoder passes of k consecutive frames overlap on the GPU -- throughput pipelining,
                               per-frame results are unchanged */
+    int32_t head_streams; /* streams the heads are spread over (heaviest head first, onto the least loaded);
+                              0 = as many as heads, within the four hardware queues a process gets by default
+                              minus the encoder lanes (at least 1).  Heads sharing a stream run in call order */
+    int32_t reserved;
     const void* weights;  /* host, fp32 */
     uint64_t weights_bytes;
 } vpe_backbone_cfg;

@@ -31,7 +31,8 @@ class vpe_backbone_cfg(C.Structure):
     _fields_ = [("dim", C.c_int32), ("depth", C.c_int32), ("heads", C.c_int32), ("mlp_hidden", C.c_int32),
                 ("mlp_kind", C.c_int32), ("registers", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32),
                 ("batch", C.c_int32), ("dtype", C.c_int32), ("taps", C.c_int32 * 4), ("ring_slots", C.c_int32),
-                ("flags", C.c_int32), ("ln_eps", C.c_float), ("encoder_lanes", C.c_int32), ("weights", C.c_void_p),
+                ("flags", C.c_int32), ("ln_eps", C.c_float), ("encoder_lanes", C.c_int32), ("head_streams", C.c_int32),
+                ("reserved", C.c_int32), ("weights", C.c_void_p),
                 ("weights_bytes", C.c_uint64)]
 
 
@@ -185,7 +186,7 @@ class Engine:
 
     def __init__(self, *, dim, depth, heads, mlp_hidden, img_h, img_w, weights: np.ndarray, taps,
                  mlp_kind=VPE_MLP_GELU, registers=0, batch=1, dtype=VPE_BF16, ring_slots=2, flags=0, ln_eps=1e-6,
-                 encoder_lanes=1,
+                 encoder_lanes=1, head_streams=0,
                  head_cfgs: Sequence[HeadCfg] = (), torch_workspace: bool = True):
         self._keep = [np.ascontiguousarray(weights, dtype=np.float32)]
         cfg = vpe_backbone_cfg()
@@ -193,6 +194,7 @@ class Engine:
         cfg.registers, cfg.img_h, cfg.img_w, cfg.batch, cfg.dtype = registers, img_h, img_w, batch, dtype
         cfg.taps = (C.c_int32 * 4)(*taps)
         cfg.ring_slots, cfg.flags, cfg.ln_eps, cfg.encoder_lanes = ring_slots, flags, ln_eps, encoder_lanes
+        cfg.head_streams = head_streams
         cfg.weights = self._keep[0].ctypes.data
         cfg.weights_bytes = self._keep[0].nbytes
         self.n_heads = len(head_cfgs)

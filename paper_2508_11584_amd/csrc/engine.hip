@@ -27,6 +27,8 @@ thread_local std::string g_create_error;
 constexpr int KPATCH = 588;      // 3 * 14 * 14
 constexpr int KPATCH_PAD = 640;  // next multiple of the k-tile
 constexpr int NPAD = 256;        // weight rows are padded to the widest GEMM tile
+constexpr int MAX_LANES = 4;
+constexpr int HW_QUEUES = 4;      // hardware queues a process gets by default
 
 struct Bump {
     char* base = nullptr;  // null: only count
@@ -65,7 +67,7 @@ struct Head {
     void *z = nullptr, *r = nullptr;
     float *d8 = nullptr, *depth = nullptr;
     // scheduling
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;     // one of the engine's head streams (shared when heads outnumber them)
     hipEvent_t last_done = nullptr;   // completion of the most recent run (any slot)
     bool ran = false;
     int64_t runs = 0, skips = 0;
@@ -98,7 +100,7 @@ struct vpe_engine {
         bool used = false;
     };
     int lanes = 1;
-    Lane lane[2];
+    Lane lane[MAX_LANES];
     // ring
     std::vector<void*> feat;             // [S][4]
     std::vector<int64_t> slot_frame;     // frame held by each slot, -1 = none
@@ -107,7 +109,7 @@ struct vpe_engine {
     std::vector<char> done_set;          // [S][n_heads]
     std::vector<hipGraphExec_t> enc_graphs;   // [S][lanes]
     std::vector<Head> heads;
-    hipStream_t cap_stream = nullptr;
+    std::vector<hipStream_t> head_streams;
     int64_t frames = 0;
     std::string err;
 
@@ -140,6 +142,9 @@ int64_t head_floats(const vpe_backbone_cfg& c, const vpe_head_cfg& h) {
     }
     return -1;
 }
+
+// Multiply-accumulate work of one head run (x2 = FLOP), for balancing heads over streams.
+double head_flops(const vpe_engine& e, const Head& h);
 
 // Returns an empty string when the configuration is acceptable.
 std::string validate(const vpe_backbone_cfg* c, const vpe_head_cfg* heads, int n_heads) {
@@ -198,7 +203,7 @@ void derive(vpe_engine& e, const vpe_backbone_cfg& c, const vpe_head_cfg* heads,
     e.N = 1 + e.R + e.P; e.T = e.B * e.N;
     e.npad = (int)rup(e.N, 64);
     e.S = c.ring_slots;
-    e.lanes = c.encoder_lanes >= 2 && c.ring_slots >= 2 ? 2 : 1;     // two encodes in flight need two slots
+    e.lanes = std::max(1, std::min({c.encoder_lanes, c.ring_slots, MAX_LANES}));   // k encodes in flight need k slots
     e.heads.assign(n_heads, Head());
     for (int i = 0; i < n_heads; ++i) {
         e.heads[i].kind = heads[i].kind;
@@ -209,6 +214,15 @@ void derive(vpe_engine& e, const vpe_backbone_cfg& c, const vpe_head_cfg* heads,
 }
 
 // Hands out every device region; with b.base == nullptr it only measures.
+double head_flops(const vpe_engine& e, const Head& h) {
+    const double P = (double)e.B * e.P;
+    switch (h.kind) {
+        case VPE_HEAD_SEG: return P * e.D * h.classes;
+        case VPE_HEAD_DET: return P * (9.0 * e.D * 2 * h.ch + 2.0 * h.ch * (h.classes + 4));
+        default: return P * (4.0 * e.D * h.ch + 85.0 * 9 * h.ch * h.ch);   // four 3x3 stages on 1 + 4 + 16 + 64 grids
+    }
+}
+
 void layout(vpe_engine& e, Bump& b) {
     const uint64_t esz = e.esz;
     const uint64_t D = e.D, T = e.T, P = e.P, B = e.B;
@@ -482,13 +496,18 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
     return 0;
 }
 
-// Capture `body` on the engine's capture stream into an executable graph.
+// Capture `body` into an executable graph.  The capture stream exists only for the duration of the capture:
+// a standing extra stream would hold a share of a hardware queue next to the streams that do the work.
 template <typename Fn>
 int capture(vpe_engine& e, hipGraphExec_t* out, Fn body) {
-    HIPCHK(&e, hipStreamBeginCapture(e.cap_stream, hipStreamCaptureModeRelaxed));
-    const int rc = body(e.cap_stream);
+    hipStream_t cs = nullptr;
+    HIPCHK(&e, hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+    hipError_t eb = hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed);
+    if (eb != hipSuccess) { (void)hipStreamDestroy(cs); HIPCHK(&e, eb); }
+    const int rc = body(cs);
     hipGraph_t g = nullptr;
-    const hipError_t ec = hipStreamEndCapture(e.cap_stream, &g);
+    const hipError_t ec = hipStreamEndCapture(cs, &g);
+    (void)hipStreamDestroy(cs);
     if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
     HIPCHK(&e, ec);
     const hipError_t ei = hipGraphInstantiate(out, g, nullptr, nullptr, 0);
@@ -504,15 +523,14 @@ void destroy_engine(vpe_engine* e) {
         for (auto g : e->enc_graphs) if (g) (void)hipGraphExecDestroy(g);
         for (auto& h : e->heads) {
             for (auto g : h.graphs) if (g) (void)hipGraphExecDestroy(g);
-            if (h.stream) (void)hipStreamDestroy(h.stream);
         }
+        for (auto hs : e->head_streams) if (hs) (void)hipStreamDestroy(hs);
         for (auto ev : e->ready) if (ev) (void)hipEventDestroy(ev);
         for (auto ev : e->done) if (ev) (void)hipEventDestroy(ev);
         for (auto& L : e->lane) {
             if (L.stream) (void)hipStreamDestroy(L.stream);
             if (L.done) (void)hipEventDestroy(L.done);
         }
-        if (e->cap_stream) (void)hipStreamDestroy(e->cap_stream);
         if (e->owns_ws && e->ws) (void)hipFree(e->ws);
     }
     delete e;
@@ -589,11 +607,30 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     (void)hipFree(staging);
     if (rc) return bail(rc);
 
+    // Streams.  A process gets few hardware queues (four by default) and streams beyond that number share
+    // them, which serialises work that was meant to overlap; so the engine keeps its concurrently active
+    // streams within that budget: `lanes` encoder streams plus head streams, heads sharing a stream (heaviest
+    // first onto the least loaded) when they outnumber what is left.
     for (int l = 0; l < e->lanes; ++l) {
         if (hip(hipStreamCreateWithFlags(&e->lane[l].stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
         if (hip(hipEventCreateWithFlags(&e->lane[l].done, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
     }
-    if (hip(hipStreamCreateWithFlags(&e->cap_stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+    if (nh > 0) {
+        int ns = cfg->head_streams > 0 ? cfg->head_streams : std::max(1, HW_QUEUES - e->lanes);
+        ns = std::min(ns, nh);
+        e->head_streams.assign(ns, nullptr);
+        for (auto& hs : e->head_streams)
+            if (hip(hipStreamCreateWithFlags(&hs, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
+        std::vector<int> order(nh);
+        for (int i = 0; i < nh; ++i) order[i] = i;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return head_flops(*e, e->heads[a]) > head_flops(*e, e->heads[b]); });
+        std::vector<double> load(ns, 0.0);
+        for (int i : order) {
+            const int k = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+            e->heads[i].stream = e->head_streams[k];
+            load[k] += head_flops(*e, e->heads[i]);
+        }
+    }
     e->ready.assign(e->S, nullptr);
     e->done.assign((size_t)e->S * std::max(nh, 1), nullptr);
     for (auto& ev : e->ready)
@@ -601,10 +638,7 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     for (auto& ev : e->done)
         if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
     e->enc_graphs.assign((size_t)e->S * e->lanes, nullptr);
-    for (auto& h : e->heads) {
-        if (hip(hipStreamCreateWithFlags(&h.stream, hipStreamNonBlocking), "hipStreamCreate")) return bail(VPE_EHIP);
-        h.graphs.assign(e->S, nullptr);
-    }
+    for (auto& h : e->heads) h.graphs.assign(e->S, nullptr);
     if (hip(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(VPE_EHIP);
     *out = e;
     return VPE_OK;

@@ -23,13 +23,13 @@ def head_cfgs(spec, seed, kinds, every_n=None):
 
 
 def make_engine(spec, seed, kinds=("seg", "depth", "det"), every_n=None, ring_slots=2, flags=0, weights=None,
-                torch_workspace=True, encoder_lanes=1):
+                torch_workspace=True, encoder_lanes=1, head_streams=0):
     w = weights if weights is not None else vi.make_backbone_weights(spec, seed)
     hc, hd = head_cfgs(spec, seed, kinds, every_n)
     eng = vpe.Engine(dim=spec.dim, depth=spec.depth, heads=spec.heads, mlp_hidden=spec.mlp_hidden,
                      mlp_kind=spec.mlp_kind, registers=spec.registers, img_h=spec.img_h, img_w=spec.img_w,
                      batch=spec.batch, dtype=vpe.VPE_BF16 if spec.dtype == "bf16" else vpe.VPE_F32,
-                     taps=spec.taps, ring_slots=ring_slots, flags=flags, ln_eps=spec.ln_eps, encoder_lanes=encoder_lanes,
+                     taps=spec.taps, ring_slots=ring_slots, flags=flags, ln_eps=spec.ln_eps, encoder_lanes=encoder_lanes, head_streams=head_streams,
                      weights=vi.pack_backbone(spec, w), head_cfgs=hc, torch_workspace=torch_workspace)
     return eng, w, hd
 

@@ -24,6 +24,32 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), n
 
 
+def test_binding_structs_match_the_header_layout(tmp_path):
+    # the header compiled as plain C (it must be one) reports size and field offsets of every struct;
+    # the ctypes mirrors must agree field by field
+    structs = {"vpe_feat": vpe.binding.vpe_feat, "vpe_backbone_cfg": vpe.binding.vpe_backbone_cfg,
+               "vpe_head_cfg": vpe.binding.vpe_head_cfg}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "vpe.h"', 'int main(void) {']
+    for name, st in structs.items():
+        lines.append(f'printf("{name} size %zu\\n", sizeof({name}));')
+        for f, _ in st._fields_:
+            lines.append(f'printf("{name} {f} %zu\\n", offsetof({name}, {f}));')
+    lines += ["return 0; }"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = 0
+    for ln in filter(None, out):
+        name, field, val = ln.split()
+        st = structs[name]
+        assert int(val) == (C.sizeof(st) if field == "size" else getattr(st, field).offset), ln
+        seen += 1
+    assert seen == sum(len(st._fields_) + 1 for st in structs.values())
+
+
 def test_product_does_not_import_the_oracle():
     for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2508_11584_amd")):
         for f in files:

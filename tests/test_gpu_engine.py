@@ -113,14 +113,14 @@ def test_single_slot_ring_and_back_to_back_frames_stay_correct():
         eng.close()
 
 
-@pytest.mark.parametrize("lanes,slots", [(1, 2), (2, 2), (2, 3)])
-def test_unsynchronised_stream_of_frames_ends_in_the_right_state(lanes, slots):
-    # 40 frames pushed without any host sync, rates 1/2/3, one or two encoder lanes (two = the encoder
-    # passes of consecutive frames overlap): the final outputs must be those of the last frame each head
-    # was due on, computed in isolation
+@pytest.mark.parametrize("lanes,slots,head_streams", [(1, 2, 0), (2, 2, 0), (2, 3, 0), (2, 3, 1), (3, 4, 2), (4, 4, 3)])
+def test_unsynchronised_stream_of_frames_ends_in_the_right_state(lanes, slots, head_streams):
+    # 40 frames pushed without any host sync, rates 1/2/3, one to four encoder lanes (the encoder passes of
+    # consecutive frames overlap) and heads on own or shared streams: the final outputs must be those of
+    # the last frame each head was due on, computed in isolation
     fs = frames(4, seed=500)
     eng, _, _ = make_engine(SPEC, 15, every_n=(1, 2, 3), flags=vpe.VPE_FLAG_GRAPHS, ring_slots=slots,
-                            encoder_lanes=lanes)
+                            encoder_lanes=lanes, head_streams=head_streams)
     n = 40
     for i in range(n):
         fh = eng.encode(fs[i % 4])
@@ -201,11 +201,11 @@ def test_batch_elements_are_independent_on_the_device():
     eng1.close()
 
 
-def test_two_encoder_lanes_give_the_same_frames_as_one():
+def test_encoder_lanes_and_shared_head_streams_give_the_same_frames_as_one_lane():
     fs = frames(6, seed=700)
     res = {}
-    for lanes in (1, 2):
-        eng, _, _ = make_engine(SPEC, 19, flags=vpe.VPE_FLAG_GRAPHS, ring_slots=2, encoder_lanes=lanes)
+    for lanes, slots, hs in ((1, 2, 0), (2, 2, 0), (3, 3, 1)):
+        eng, _, _ = make_engine(SPEC, 19, flags=vpe.VPE_FLAG_GRAPHS, ring_slots=slots, encoder_lanes=lanes, head_streams=hs)
         feats = []
         handles = []
         for f in fs[:2]:                          # two frames in flight before anything is read
@@ -221,5 +221,6 @@ def test_two_encoder_lanes_give_the_same_frames_as_one():
             feats += outputs(eng)
         res[lanes] = feats
         eng.close()
-    for a, b in zip(res[1], res[2]):
-        assert torch.equal(a, b)
+    for other in (2, 3):
+        for a, b in zip(res[1], res[other]):
+            assert torch.equal(a, b)
