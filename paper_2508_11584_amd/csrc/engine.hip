@@ -276,7 +276,7 @@ void layout(vpe_engine& e, Bump& b) {
             for (int s = 0; s < 4; ++s) h.p[s] = b.take(BP * ch * esz);
             h.z = b.take(BP * 64 * ch * esz);
             h.r = b.take(BP * 64 * ch * esz);
-            h.d8 = f32(BP * 64);
+            h.d8 = f32((int64_t)(ch / 64) * BP * 64);   // one partial projection per 64 channels
             h.depth = f32(B * e.H * e.W);
         }
     }
@@ -487,11 +487,16 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
                 in = h.z;
             }
             GemmArgs a = conv3_gemm(e, in, h.ch, e.B, hs, wsz, hs * wsz, 0, h.fuse_w[st], h.fuse_b[st], h.ch);
-            a.out = h.r; a.ldo = h.ch;
+            if (st < 3) {
+                a.out = h.r; a.ldo = h.ch;
+            } else {
+                // last stage: the 1-channel projection is taken in the epilogue (per 64-channel group), the
+                // 256-channel map itself is never written
+                a.epi = EPI_ROWDOT; a.gamma = h.out_w; a.out = h.d8; a.ldo = (int64_t)BP * 64;
+            }
             HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
         }
-        HIPCHK(&e, launch_rowdot(dt, h.r, (int64_t)BP * 64, h.ch, h.out_w, h.out_b, h.d8, s));
-        HIPCHK(&e, launch_depth_output(h.d8, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
+        HIPCHK(&e, launch_depth_output(h.d8, h.ch / 64, (int64_t)BP * 64, h.out_b, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
     }
     return 0;
 }
@@ -794,7 +799,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 // shape, weights and buffers as in a head run; its timing does not depend on the values in z
                 const int hs = e->gh << 3, wsz = e->gw << 3;
                 GemmArgs a = conv3_gemm(*e, dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[3], dh->fuse_b[3], dh->ch);
-                a.out = dh->r; a.ldo = dh->ch;
+                a.epi = EPI_ROWDOT; a.gamma = dh->out_w; a.out = dh->d8; a.ldo = (int64_t)e->B * e->P * 64;
                 HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
             }
         }
@@ -817,7 +822,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
     else {
         const double ch = dh->ch, pix = (double)e->B * e->P * 64.0;
         fl = 2.0 * 9.0 * ch * ch * pix;
-        by = esz * (2.0 * pix * ch + 9.0 * ch * ch);
+        by = esz * (pix * ch + 9.0 * ch * ch) + 4.0 * pix;     // input map + weights in, one projected value per pixel out
     }
     *ms_per_launch = ms / launches;
     if (flops) *flops = fl;

@@ -14,7 +14,7 @@
 namespace vpe {
 
 enum AMode { A_PLAIN = 0, A_CONV3 = 1 };
-enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3, EPI_PATCH = 4 };
+enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3, EPI_PATCH = 4, EPI_ROWDOT = 5 };
 enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 
 struct GemmArgs {
@@ -32,7 +32,9 @@ struct GemmArgs {
     void* out;           // T or float (out_f32); RESID/PATCH: float residual stream
     int64_t ldo;
     int o_rpi, o_istride, o_off;   // output row map, as for A
-    const float* gamma;  // RESID: LayerScale vector
+    const float* gamma;  // RESID: LayerScale vector.  ROWDOT: projection vector w[N]; the tile itself is not stored,
+                         //   out (float) receives out[(c / 64) * ldo + r] = sum over the 64 columns of group c / 64 of
+                         //   act(acc + bias)[col] * w[col]  (N multiple of 64; the caller adds the N / 64 partial sums)
     const float* pos;    // PATCH: positional rows [o_rpi][N]
     void* out2;          // QKV: transposed values  vt[(b * dim + c)][npad]
     int ntok, npad, dim; // QKV
@@ -183,6 +185,20 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& p, int r, int c, 
     }
 }
 
+// ROWDOT: contribution of 8 consecutive columns (starting at c) of one row to the row's projection.
+__device__ __forceinline__ float rowdot_chunk(const GemmArgs& p, int c, const float* v) {
+    const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + c), b1 = *reinterpret_cast<const f32x4*>(p.bias + c + 4);
+    const f32x4 w0 = *reinterpret_cast<const f32x4*>(p.gamma + c), w1 = *reinterpret_cast<const f32x4*>(p.gamma + c + 4);
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float a = v[i] + b0[i], b = v[4 + i] + b1[i];
+        if (p.act == ACT_RELU) { a = fmaxf(a, 0.0f); b = fmaxf(b, 0.0f); }
+        s += a * w0[i] + b * w1[i];
+    }
+    return s;
+}
+
 // Block-level epilogue shared by the register-staged kernels.  The accumulators go through LDS
 // (`smem`, free after the k loop, at least BM * BN * 4 bytes) as a row-major fp32 tile, so that
 // each thread then owns 8 consecutive columns of a row: one row-index computation and 16-byte
@@ -254,6 +270,28 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[
                     if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
                 }
             }
+        }
+        return;
+    }
+    if (p.epi == EPI_ROWDOT) {
+        // 8 consecutive lanes hold the 8 chunks of one 64-column group of a row: every lane takes part in
+        // the exchange (out-of-range rows / columns contribute zero), the first lane of a group writes
+        constexpr int CG = BN / 8, RPASS = NT / CG;
+        const int cg = tid % CG, c = n0 + cg * 8;
+        float* out = reinterpret_cast<float*>(p.out);
+        for (int rr = tid / CG; rr < BM; rr += RPASS) {
+            const int r = m0 + rr;
+            float sum = 0.0f;
+            if (r < p.M && c < p.N) {
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8 + 4);
+                const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                sum = rowdot_chunk(p, c, v);
+            }
+            sum += __shfl_xor(sum, 1);
+            sum += __shfl_xor(sum, 2);
+            sum += __shfl_xor(sum, 4);
+            if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)(c >> 6) * p.ldo + r] = sum;
         }
         return;
     }

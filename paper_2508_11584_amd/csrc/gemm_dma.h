@@ -236,6 +236,27 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
                     }
                 }
             }
+        } else if (p.epi == EPI_ROWDOT) {
+            // a wave's 64 columns are one projection group: 8 consecutive lanes hold a row's 8 chunks
+            if constexpr (WN == 64) {
+                float* out = reinterpret_cast<float*>(p.out);
+#pragma unroll
+                for (int it = lane; it < 32 * 8; it += 64) {
+                    const int rr = it >> 3, cg = it & 7;
+                    const int r = rblk + rr, c = wcol0 + cg * 8;
+                    float sum = 0.0f;
+                    if (r < p.M && c < p.N) {
+                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
+                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
+                        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        sum = rowdot_chunk(p, c, v);
+                    }
+                    sum += __shfl_xor(sum, 1);
+                    sum += __shfl_xor(sum, 2);
+                    sum += __shfl_xor(sum, 4);
+                    if (cg == 0 && r < p.M && c < p.N) out[(int64_t)(c >> 6) * p.ldo + r] = sum;
+                }
+            }
         } else {
             constexpr int CG = WN / 8;
             for (int it = lane; it < 32 * CG; it += 64) {

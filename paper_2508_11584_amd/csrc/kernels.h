@@ -21,13 +21,12 @@ hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int k
 hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, int n_cols, int64_t rs,
                            int64_t cs, int mode, int cin, int swiglu_half, int64_t dst_ld, int row_off,
                            int col_off, hipStream_t s);
-hipError_t launch_rowdot(int dtype, const void* in, int64_t rows, int C, const float* w, float bias,
-                         float* out, hipStream_t s);
 hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint8_t* out, hipStream_t s);
 hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const void* r, int B, int Hs, int Ws,
                                 int C, void* z, hipStream_t s);
 hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw, int C, int H, int W,
                                       uint8_t* cls, hipStream_t s);
-hipError_t launch_depth_output(const float* d, int B, int h8, int w8, int H, int W, float* depth, hipStream_t s);
+hipError_t launch_depth_output(const float* d, int nparts, int64_t part_stride, float bias, int B, int h8, int w8,
+                               int H, int W, float* depth, hipStream_t s);
 
 }  // namespace vpe

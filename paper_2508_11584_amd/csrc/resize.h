@@ -110,9 +110,12 @@ __global__ __launch_bounds__(256) void seg_upsample_argmax_kernel(const float* _
     cls[idx] = (uint8_t)best;
 }
 
-// Depth output: depth = ReLU(bilinear(bilinear_x2(d) -> H x W)) with d fp32 [B][h8][w8].
-// The x2 map is evaluated on the fly at the four positions the final resize reads.
-__global__ __launch_bounds__(256) void depth_output_kernel(const float* __restrict__ d, int B, int h8, int w8,
+// Depth output: depth = ReLU(bilinear(bilinear_x2(d) -> H x W)) with d fp32 [B][h8][w8] given as
+// d = bias + the sum of `nparts` partial maps `part_stride` floats apart (the convolution before it leaves
+// the 1-channel projection as one partial sum per 64 channels).  The x2 map is evaluated on the fly at the
+// four positions the final resize reads.
+__global__ __launch_bounds__(256) void depth_output_kernel(const float* __restrict__ d, int nparts,
+                                                           int64_t part_stride, float bias, int B, int h8, int w8,
                                                            int H, int W, float* __restrict__ depth) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)B * H * W) return;
@@ -120,10 +123,15 @@ __global__ __launch_bounds__(256) void depth_output_kernel(const float* __restri
     const int y = (int)((idx / W) % H), b = (int)(idx / ((int64_t)W * H));
     const int h16 = 2 * h8, w16 = 2 * w8;
     const float* src = d + (int64_t)b * h8 * w8;
+    auto at = [&](int i) {
+        float v = bias;
+        for (int k = 0; k < nparts; ++k) v += src[k * part_stride + i];     // fixed order: deterministic
+        return v;
+    };
     auto up2 = [&](int yy, int xx) {
         const Tap ty = bilinear_tap(yy, h8, h16), tx = bilinear_tap(xx, w8, w16);
-        const float top = (1.0f - tx.w1) * src[ty.i0 * w8 + tx.i0] + tx.w1 * src[ty.i0 * w8 + tx.i1];
-        const float bot = (1.0f - tx.w1) * src[ty.i1 * w8 + tx.i0] + tx.w1 * src[ty.i1 * w8 + tx.i1];
+        const float top = (1.0f - tx.w1) * at(ty.i0 * w8 + tx.i0) + tx.w1 * at(ty.i0 * w8 + tx.i1);
+        const float bot = (1.0f - tx.w1) * at(ty.i1 * w8 + tx.i0) + tx.w1 * at(ty.i1 * w8 + tx.i1);
         return (1.0f - ty.w1) * top + ty.w1 * bot;
     };
     const Tap ty = bilinear_tap(y, h16, H), tx = bilinear_tap(x, w16, W);

@@ -1,5 +1,5 @@
 // Bandwidth-bound row kernels: LayerNorm, patch gathering (im2col), weight re-layout at
-// engine creation, per-pixel dot products and channel argmax.  All are coalesced along the
+// engine creation and channel argmax.  All are coalesced along the
 // contiguous (channel) axis; one wavefront owns one row.
 #pragma once
 #include "common.h"
@@ -109,24 +109,6 @@ __global__ __launch_bounds__(256) void relayout_kernel(const float* __restrict__
         si = ((int64_t)nl * cin + ci) * 9 + tap;
     }
     dst[(int64_t)(row_off + n) * dst_ld + col_off + k] = from_f32<T>(src[si]);
-}
-
-// out[r] = bias + sum_c in[r][c] * w[c]: the depth head's 1-channel projection, one wave per pixel.
-template <typename T>
-__global__ __launch_bounds__(256) void rowdot_kernel(const T* __restrict__ in, int64_t rows, int C,
-                                                     const float* __restrict__ w, float bias,
-                                                     float* __restrict__ out) {
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (row >= rows) return;
-    const T* r = in + row * C;
-    float acc = 0.0f;
-    for (int c = lane * 4; c < C; c += 256) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc += to_f32(r[c + i]) * w[c + i];
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) out[row] = acc + bias;
 }
 
 // Per-row argmax over the first C of `ld` fp32 values (ties -> lowest index); one wave per row:

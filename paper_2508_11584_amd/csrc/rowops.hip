@@ -34,13 +34,6 @@ hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, i
     return hipGetLastError();
 }
 
-hipError_t launch_rowdot(int dtype, const void* in, int64_t rows, int C, const float* w, float bias,
-                         float* out, hipStream_t s) {
-    if (dtype) hipLaunchKernelGGL(rowdot_kernel<bf16>, dim3(blocks_for(rows, 4)), dim3(256), 0, s, (const bf16*)in, rows, C, w, bias, out);
-    else hipLaunchKernelGGL(rowdot_kernel<float>, dim3(blocks_for(rows, 4)), dim3(256), 0, s, (const float*)in, rows, C, w, bias, out);
-    return hipGetLastError();
-}
-
 hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint8_t* out, hipStream_t s) {
     hipLaunchKernelGGL(argmax_rows_kernel, dim3(blocks_for(rows, 4)), dim3(256), 0, s, in, rows, C, ld, out);
     return hipGetLastError();
@@ -64,8 +57,9 @@ hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw
     return hipGetLastError();
 }
 
-hipError_t launch_depth_output(const float* d, int B, int h8, int w8, int H, int W, float* depth, hipStream_t s) {
-    hipLaunchKernelGGL(depth_output_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, d, B, h8, w8, H, W, depth);
+hipError_t launch_depth_output(const float* d, int nparts, int64_t part_stride, float bias, int B, int h8, int w8,
+                               int H, int W, float* depth, hipStream_t s) {
+    hipLaunchKernelGGL(depth_output_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, d, nparts, part_stride, bias, B, h8, w8, H, W, depth);
     return hipGetLastError();
 }
 
