@@ -276,7 +276,7 @@ void layout(vpe_engine& e, Bump& b) {
             for (int s = 0; s < 4; ++s) h.p[s] = b.take(BP * ch * esz);
             h.z = b.take(BP * 64 * ch * esz);
             h.r = b.take(BP * 64 * ch * esz);
-            h.d8 = f32((int64_t)(ch / 64) * BP * 64);   // one partial projection per 64 channels
+            h.d8 = f32((int64_t)(ch / 64) * BP * 64);   // [pixel][ch / 64]: one partial projection per 64 channels
             h.depth = f32(B * e.H * e.W);
         }
     }
@@ -474,9 +474,19 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
         HIPCHK(&e, launch_gemm(dt, o, A_PLAIN, s));
         HIPCHK(&e, launch_argmax_rows(h.logits, BP, h.classes, h.classes + 4, h.classmap, s));
     } else {
-        for (int st = 0; st < 4; ++st) {
+        // the four tap projections are independent problems of one shape: one batched launch when their
+        // operands are evenly spaced in memory (they are, by construction of the workspace layout)
+        const int64_t za = (const char*)f[2] - (const char*)f[3], zw = (const char*)h.proj_w[1] - (const char*)h.proj_w[0];
+        const int64_t zo = (const char*)h.p[1] - (const char*)h.p[0], zb = h.proj_b[1] - h.proj_b[0];
+        bool even = true;
+        for (int st = 1; st < 4; ++st)
+            even = even && (const char*)f[3 - st] - (const char*)f[3] == st * za &&
+                   (const char*)h.proj_w[st] - (const char*)h.proj_w[0] == st * zw &&
+                   (const char*)h.p[st] - (const char*)h.p[0] == st * zo && h.proj_b[st] - h.proj_b[0] == st * zb;
+        for (int st = 0; st < (even ? 1 : 4); ++st) {
             GemmArgs a = tokens_gemm(e, f[3 - st], h.proj_w[st], h.proj_b[st], h.ch);
             a.out = h.p[st]; a.ldo = h.ch;
+            if (even) { a.nz = 4; a.z_a = za; a.z_w = zw; a.z_out = zo; a.z_bias = zb; }
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         for (int st = 0; st < 4; ++st) {
@@ -492,11 +502,11 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
             } else {
                 // last stage: the 1-channel projection is taken in the epilogue (per 64-channel group), the
                 // 256-channel map itself is never written
-                a.epi = EPI_ROWDOT; a.gamma = h.out_w; a.out = h.d8; a.ldo = (int64_t)BP * 64;
+                a.epi = EPI_ROWDOT; a.gamma = h.out_w; a.out = h.d8; a.ldo = h.ch / 64;
             }
             HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
         }
-        HIPCHK(&e, launch_depth_output(h.d8, h.ch / 64, (int64_t)BP * 64, h.out_b, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
+        HIPCHK(&e, launch_depth_output(h.d8, h.ch / 64, h.out_b, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
     }
     return 0;
 }
@@ -799,7 +809,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 // shape, weights and buffers as in a head run; its timing does not depend on the values in z
                 const int hs = e->gh << 3, wsz = e->gw << 3;
                 GemmArgs a = conv3_gemm(*e, dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[3], dh->fuse_b[3], dh->ch);
-                a.epi = EPI_ROWDOT; a.gamma = dh->out_w; a.out = dh->d8; a.ldo = (int64_t)e->B * e->P * 64;
+                a.epi = EPI_ROWDOT; a.gamma = dh->out_w; a.out = dh->d8; a.ldo = dh->ch / 64;
                 HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
             }
         }

@@ -33,12 +33,28 @@ struct GemmArgs {
     int64_t ldo;
     int o_rpi, o_istride, o_off;   // output row map, as for A
     const float* gamma;  // RESID: LayerScale vector.  ROWDOT: projection vector w[N]; the tile itself is not stored,
-                         //   out (float) receives out[(c / 64) * ldo + r] = sum over the 64 columns of group c / 64 of
+                         //   out (float) receives out[r * ldo + c / 64] = sum over the 64 columns of group c / 64 of
                          //   act(acc + bias)[col] * w[col]  (N multiple of 64; the caller adds the N / 64 partial sums)
     const float* pos;    // PATCH: positional rows [o_rpi][N]
     void* out2;          // QKV: transposed values  vt[(b * dim + c)][npad]
     int ntok, npad, dim; // QKV
+    // batch of nz independent problems of the same shape in one launch (blockIdx.y = z): problem z uses
+    // A + z * z_a, W + z * z_w, out + z * z_out (byte strides, may be negative) and bias + z * z_bias (elements)
+    int nz;
+    int64_t z_a, z_w, z_out, z_bias;
 };
+
+// The arguments of problem blockIdx.y of a batched launch (a plain copy when the launch is not batched).
+__device__ __forceinline__ GemmArgs select_problem(const GemmArgs& in) {
+    GemmArgs p = in;
+    const int64_t z = blockIdx.y;
+    p.A = reinterpret_cast<const char*>(in.A) + z * in.z_a;
+    p.W = reinterpret_cast<const char*>(in.W) + z * in.z_w;
+    p.out = reinterpret_cast<char*>(in.out) + z * in.z_out;
+    if (in.bias) p.bias = in.bias + z * in.z_bias;
+    return p;
+}
+
 
 template <typename T> struct Mma;
 
@@ -291,7 +307,7 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[
             sum += __shfl_xor(sum, 1);
             sum += __shfl_xor(sum, 2);
             sum += __shfl_xor(sum, 4);
-            if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)(c >> 6) * p.ldo + r] = sum;
+            if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
         }
         return;
     }
@@ -312,7 +328,8 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN, int AMODE>
-__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs args) {
+    const GemmArgs p = select_problem(args);
     constexpr int NT = 64 * WGM * WGN;
     constexpr int CE = Elem<T>::CE;
     constexpr int BK = 8 * CE;
@@ -463,7 +480,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
 template <typename T, int BM, int BN, int WGM, int WGN>
 static inline hipError_t launch_tile(const GemmArgs& a, int amode, hipStream_t s) {
     const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN);
-    dim3 grid(tiles), block(64 * WGM * WGN);
+    dim3 grid(tiles, a.nz > 1 ? a.nz : 1), block(64 * WGM * WGN);
     if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, A_PLAIN>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, A_CONV3>), grid, block, 0, s, a);
     return hipGetLastError();
@@ -473,8 +490,9 @@ static inline hipError_t launch_tile(const GemmArgs& a, int amode, hipStream_t s
 // wave tiles of 64 columns (gate and linear partner in the same lane).
 template <typename T>
 static inline hipError_t launch_gemm_t(const GemmArgs& a, int amode, hipStream_t s) {
-    const int64_t t128 = (int64_t)cdiv(a.M, 128) * cdiv(a.N, 128);
-    const int64_t t64x128 = (int64_t)cdiv(a.M, 64) * cdiv(a.N, 128);
+    const int nz = a.nz > 1 ? a.nz : 1;
+    const int64_t t128 = (int64_t)cdiv(a.M, 128) * cdiv(a.N, 128) * nz;
+    const int64_t t64x128 = (int64_t)cdiv(a.M, 64) * cdiv(a.N, 128) * nz;
     if (t128 >= 384) return launch_tile<T, 128, 128, 2, 2>(a, amode, s);
     if (t64x128 >= 384 || a.epi == EPI_SWIGLU) return launch_tile<T, 64, 128, 2, 2>(a, amode, s);
     return launch_tile<T, 64, 64, 2, 2>(a, amode, s);

@@ -34,7 +34,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     for (const Cand& c : kCands) {
         if (c.kind >= 128 && !fits) continue;
         if (c.kind == 3 && a.epi == EPI_SWIGLU) continue;       // needs 64-column wave tiles
-        const int64_t tiles = (int64_t)cdiv(a.M, c.bm) * cdiv(a.N, c.bn);
+        const int64_t tiles = (int64_t)cdiv(a.M, c.bm) * cdiv(a.N, c.bn) * (a.nz > 1 ? a.nz : 1);
         // workgroups do not run in lockstep rounds: measured times grow linearly with tiles / slots
         const float rounds = tiles > c.slots ? (float)tiles / c.slots : 1.0f;
         const float cost = rounds * c.bm * c.bn / c.q;

@@ -29,7 +29,8 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // WGM x 2 waves: WGM = 2 gives 128-row wave tiles (256 accumulator registers, one wave per SIMD),
 // WGM = 4 gives 64-row wave tiles and two waves per SIMD, i.e. twice as many waves issuing loads.
 template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE>
-__global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const GemmArgs args) {
+    const GemmArgs p = select_problem(args);
     typedef bf16 T;
     constexpr int BM = 256, CE = 8, NW = WGN * WGM;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
                     sum += __shfl_xor(sum, 1);
                     sum += __shfl_xor(sum, 2);
                     sum += __shfl_xor(sum, 4);
-                    if (cg == 0 && r < p.M && c < p.N) out[(int64_t)(c >> 6) * p.ldo + r] = sum;
+                    if (cg == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
                 }
             }
         } else {
@@ -289,9 +290,9 @@ static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream
         configured = true;
     }
     if (configure_only) return hipSuccess;
-    const int tiles = cdiv(a.M, 256) * cdiv(a.N, BN);
-    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN>), dim3(tiles), dim3(64 * WGM * WGN), lds, s, a);
-    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3>), dim3(tiles), dim3(64 * WGM * WGN), lds, s, a);
+    const int tiles = cdiv(a.M, 256) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
+    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
+    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
     return hipGetLastError();
 }
 

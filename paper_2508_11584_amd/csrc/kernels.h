@@ -26,7 +26,7 @@ hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const 
                                 int C, void* z, hipStream_t s);
 hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw, int C, int H, int W,
                                       uint8_t* cls, hipStream_t s);
-hipError_t launch_depth_output(const float* d, int nparts, int64_t part_stride, float bias, int B, int h8, int w8,
+hipError_t launch_depth_output(const float* d, int nparts, float bias, int B, int h8, int w8,
                                int H, int W, float* depth, hipStream_t s);
 
 }  // namespace vpe

@@ -46,42 +46,99 @@ template <> struct Vec<float, 4> {
 };
 
 // Depth-head stage input  z = bilinear(p: gh x gw -> Hs x Ws) + bilinear(r: Hs/2 x Ws/2 -> Hs x Ws),
-// channels-last with C channels; r may be null (first stage with a resized tap).  One thread
-// per (pixel, 16-byte channel group).
-template <typename T>
+// channels-last with C channels; r may be null (first stage with a resized tap).
+//
+// One thread per (2 x 2 output block at even coordinates, 16-byte channel group).  The four outputs of a
+// block read overlapping source pixels, so the block is formed from at most 3 x 3 loads per source map
+// instead of 4 x 4, or from 2 x 2 when the map is enlarged by a multiple of 4 (both rows and both columns
+// of the block then fall between the same two source samples: `SHARED`).  Arithmetic per output
+// is the plain separable form: horizontal blend of each source row, then the vertical blend.
+template <typename T, int CE>
+struct BlockSrc {
+    // source rows a <= b <= c and, for the block's second output row, which of them its taps are
+    int ra, rb, rc;
+    bool lo1_is_a, hi1_is_b;
+    float w0, w1;
+    __device__ __forceinline__ void init(int y0, int in, int out) {
+        const Tap t0 = bilinear_tap(y0, in, out), t1 = bilinear_tap(y0 + 1, in, out);
+        ra = t0.i0; rb = t0.i1; rc = t1.i1;
+        lo1_is_a = t1.i0 == t0.i0;
+        hi1_is_b = t1.i1 == t0.i1;
+        w0 = t0.w1; w1 = t1.w1;
+    }
+};
+
+template <typename T, bool SHARED>
+__device__ __forceinline__ void add_block(const T* __restrict__ src, int b, int h, int w, int C, int cg, int y0, int x0,
+                                          int Hs, int Ws, float (&acc)[2][2][Elem<T>::CE]) {
+    constexpr int CE = Elem<T>::CE;
+    BlockSrc<T, CE> ys, xs;
+    ys.init(y0, h, Hs);
+    xs.init(x0, w, Ws);
+    const T* base = src + (int64_t)b * h * w * C + cg * CE;
+    const int rows[3] = {ys.ra, ys.rb, ys.rc};
+    // horizontal blends of each source row for the block's two output columns
+    float hz[3][2][CE];
+#pragma unroll
+    for (int i = 0; i < (SHARED ? 2 : 3); ++i) {
+        const T* rp = base + (int64_t)rows[i] * w * C;
+        float va[CE], vb[CE], vc[CE];
+        Vec<T, CE>::load(rp + (int64_t)xs.ra * C, va);
+        Vec<T, CE>::load(rp + (int64_t)xs.rb * C, vb);
+        if (!SHARED) Vec<T, CE>::load(rp + (int64_t)xs.rc * C, vc);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+            hz[i][0][e] = (1.0f - xs.w0) * va[e] + xs.w0 * vb[e];
+            if (SHARED) {
+                hz[i][1][e] = (1.0f - xs.w1) * va[e] + xs.w1 * vb[e];
+            } else {
+                const float lo = xs.lo1_is_a ? va[e] : vb[e], hi = xs.hi1_is_b ? vb[e] : vc[e];
+                hz[i][1][e] = (1.0f - xs.w1) * lo + xs.w1 * hi;
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+            acc[0][k][e] += (1.0f - ys.w0) * hz[0][k][e] + ys.w0 * hz[1][k][e];
+            if (SHARED) {
+                acc[1][k][e] += (1.0f - ys.w1) * hz[0][k][e] + ys.w1 * hz[1][k][e];
+            } else {
+                const float lo = ys.lo1_is_a ? hz[0][k][e] : hz[1][k][e], hi = ys.hi1_is_b ? hz[1][k][e] : hz[2][k][e];
+                acc[1][k][e] += (1.0f - ys.w1) * lo + ys.w1 * hi;
+            }
+        }
+}
+
+// PSHARED: the p map is enlarged by a multiple of 4 in both directions (decided by the launcher).
+template <typename T, bool PSHARED>
 __global__ __launch_bounds__(256) void fuse_upsample_kernel(const T* __restrict__ p, int gh, int gw,
                                                             const T* __restrict__ r, int B, int Hs, int Ws,
                                                             int C, T* __restrict__ z) {
     constexpr int CE = Elem<T>::CE;
-    const int groups = C / CE;
+    const int groups = C / CE, bw = Ws / 2, bh = Hs / 2;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)B * Hs * Ws * groups) return;
+    if (idx >= (int64_t)B * bh * bw * groups) return;
     const int cg = (int)(idx % groups);
-    int64_t pix = idx / groups;
-    const int x = (int)(pix % Ws);
-    pix /= Ws;
-    const int y = (int)(pix % Hs), b = (int)(pix / Hs);
-    float acc[CE];
+    int64_t blk = idx / groups;
+    const int x0 = 2 * (int)(blk % bw);
+    blk /= bw;
+    const int y0 = 2 * (int)(blk % bh), b = (int)(blk / bh);
+    float acc[2][2][CE];
 #pragma unroll
-    for (int i = 0; i < CE; ++i) acc[i] = 0.0f;
-    auto add = [&](const T* src, int h, int w) {
-        const Tap ty = bilinear_tap(y, h, Hs), tx = bilinear_tap(x, w, Ws);
-        const T* base = src + (int64_t)b * h * w * C + cg * CE;
-        float v00[CE], v01[CE], v10[CE], v11[CE];
-        Vec<T, CE>::load(base + ((int64_t)ty.i0 * w + tx.i0) * C, v00);
-        Vec<T, CE>::load(base + ((int64_t)ty.i0 * w + tx.i1) * C, v01);
-        Vec<T, CE>::load(base + ((int64_t)ty.i1 * w + tx.i0) * C, v10);
-        Vec<T, CE>::load(base + ((int64_t)ty.i1 * w + tx.i1) * C, v11);
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int i = 0; i < CE; ++i) {
-            const float top = (1.0f - tx.w1) * v00[i] + tx.w1 * v01[i];
-            const float bot = (1.0f - tx.w1) * v10[i] + tx.w1 * v11[i];
-            acc[i] += (1.0f - ty.w1) * top + ty.w1 * bot;
-        }
-    };
-    add(p, gh, gw);
-    if (r) add(r, Hs / 2, Ws / 2);
-    Vec<T, CE>::store(z + ((((int64_t)b * Hs + y) * Ws + x) * C) + cg * CE, acc);
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int e = 0; e < CE; ++e) acc[i][k][e] = 0.0f;
+    add_block<T, PSHARED>(p, b, gh, gw, C, cg, y0, x0, Hs, Ws, acc);
+    if (r) add_block<T, false>(r, b, bh, bw, C, cg, y0, x0, Hs, Ws, acc);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            Vec<T, CE>::store(z + ((((int64_t)b * Hs + y0 + i) * Ws + x0 + k) * C) + cg * CE, acc[i][k]);
 }
 
 // Segmentation output: class[b][y][x] = argmax_c bilinear(logits[b] : gh x gw -> H x W)[c],
@@ -111,21 +168,27 @@ __global__ __launch_bounds__(256) void seg_upsample_argmax_kernel(const float* _
 }
 
 // Depth output: depth = ReLU(bilinear(bilinear_x2(d) -> H x W)) with d fp32 [B][h8][w8] given as
-// d = bias + the sum of `nparts` partial maps `part_stride` floats apart (the convolution before it leaves
-// the 1-channel projection as one partial sum per 64 channels).  The x2 map is evaluated on the fly at the
-// four positions the final resize reads.
-__global__ __launch_bounds__(256) void depth_output_kernel(const float* __restrict__ d, int nparts,
-                                                           int64_t part_stride, float bias, int B, int h8, int w8,
-                                                           int H, int W, float* __restrict__ depth) {
+// d = bias + the sum of the `nparts` partial values stored per pixel (the convolution before it leaves the
+// 1-channel projection as one partial sum per 64 channels; summed here in index order, so the result does
+// not depend on scheduling).  NP = 4: the four partials are one 16-byte load; NP = 0: any count.
+// The x2 map is evaluated on the fly at the four positions the final resize reads.
+template <int NP>
+__global__ __launch_bounds__(256) void depth_output_kernel(const float* __restrict__ d, int nparts, float bias,
+                                                           int B, int h8, int w8, int H, int W,
+                                                           float* __restrict__ depth) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)B * H * W) return;
     const int x = (int)(idx % W);
     const int y = (int)((idx / W) % H), b = (int)(idx / ((int64_t)W * H));
     const int h16 = 2 * h8, w16 = 2 * w8;
-    const float* src = d + (int64_t)b * h8 * w8;
+    const float* src = d + (int64_t)b * h8 * w8 * nparts;
     auto at = [&](int i) {
+        if (NP == 4) {
+            const f32x4 q = *reinterpret_cast<const f32x4*>(src + 4 * (int64_t)i);
+            return (((bias + q[0]) + q[1]) + q[2]) + q[3];
+        }
         float v = bias;
-        for (int k = 0; k < nparts; ++k) v += src[k * part_stride + i];     // fixed order: deterministic
+        for (int k = 0; k < nparts; ++k) v += src[(int64_t)i * nparts + k];
         return v;
     };
     auto up2 = [&](int yy, int xx) {

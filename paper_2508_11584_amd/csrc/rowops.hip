@@ -41,12 +41,19 @@ hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint
 
 hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const void* r, int B, int Hs, int Ws,
                                 int C, void* z, hipStream_t s) {
+    if (Hs % 2 || Ws % 2 || Hs < 2 * gh || Ws < 2 * gw) return hipErrorInvalidValue;   // 2 x 2 output blocks of an enlargement
+    // both rows (columns) of an even-aligned block fall between the same two source samples when the factor f
+    // is a multiple of 4: a sample boundary lies between outputs y and y + 1 only if f (2 j + 1) = 2 y + 2,
+    // and for even y the right side is 2 mod 4
+    const bool shared = Hs % (4 * gh) == 0 && Ws % (4 * gw) == 0;
+    const int64_t n = (int64_t)B * (Hs / 2) * (Ws / 2) * (C / (dtype ? 8 : 4));
+    const dim3 grid(blocks_for(n, 256)), block(256);
     if (dtype) {
-        const int64_t n = (int64_t)B * Hs * Ws * (C / 8);
-        hipLaunchKernelGGL(fuse_upsample_kernel<bf16>, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const bf16*)p, gh, gw, (const bf16*)r, B, Hs, Ws, C, (bf16*)z);
+        if (shared) hipLaunchKernelGGL((fuse_upsample_kernel<bf16, true>), grid, block, 0, s, (const bf16*)p, gh, gw, (const bf16*)r, B, Hs, Ws, C, (bf16*)z);
+        else hipLaunchKernelGGL((fuse_upsample_kernel<bf16, false>), grid, block, 0, s, (const bf16*)p, gh, gw, (const bf16*)r, B, Hs, Ws, C, (bf16*)z);
     } else {
-        const int64_t n = (int64_t)B * Hs * Ws * (C / 4);
-        hipLaunchKernelGGL(fuse_upsample_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const float*)p, gh, gw, (const float*)r, B, Hs, Ws, C, (float*)z);
+        if (shared) hipLaunchKernelGGL((fuse_upsample_kernel<float, true>), grid, block, 0, s, (const float*)p, gh, gw, (const float*)r, B, Hs, Ws, C, (float*)z);
+        else hipLaunchKernelGGL((fuse_upsample_kernel<float, false>), grid, block, 0, s, (const float*)p, gh, gw, (const float*)r, B, Hs, Ws, C, (float*)z);
     }
     return hipGetLastError();
 }
@@ -57,9 +64,11 @@ hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw
     return hipGetLastError();
 }
 
-hipError_t launch_depth_output(const float* d, int nparts, int64_t part_stride, float bias, int B, int h8, int w8,
+hipError_t launch_depth_output(const float* d, int nparts, float bias, int B, int h8, int w8,
                                int H, int W, float* depth, hipStream_t s) {
-    hipLaunchKernelGGL(depth_output_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, d, nparts, part_stride, bias, B, h8, w8, H, W, depth);
+    const dim3 grid(blocks_for((int64_t)B * H * W, 256)), block(256);
+    if (nparts == 4) hipLaunchKernelGGL(depth_output_kernel<4>, grid, block, 0, s, d, nparts, bias, B, h8, w8, H, W, depth);
+    else hipLaunchKernelGGL(depth_output_kernel<0>, grid, block, 0, s, d, nparts, bias, B, h8, w8, H, W, depth);
     return hipGetLastError();
 }
 
