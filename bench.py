@@ -19,7 +19,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
 # calibrated against a 1 GiB copy (profiles/conv3x3_cfg2_hbm_traffic.txt); only the workload measured has one.
-TRAFFIC_BYTES = {"vits14_bf16_476x630": 125.2e6}
+TRAFFIC_BYTES = {"vits14_bf16_476x630": 72.2e6}
 
 
 def backbone_flops(spec) -> float:
@@ -38,9 +38,13 @@ def main() -> None:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload)")
     ap.add_argument("--no-graphs", action="store_true")
-    ap.add_argument("--ring-slots", type=int, default=3)
-    ap.add_argument("--encoder-lanes", type=int, default=2,
-                    help="2 = the encoder passes of consecutive frames overlap on the GPU (throughput pipelining)")
+    ap.add_argument("--encoder-lanes", type=int, default=None,
+                    help="k = the encoder passes of k consecutive frames overlap on the GPU (throughput pipelining); "
+                         "default 3 for the one-image configs 1-3, 2 for the batched configs 4-5")
+    ap.add_argument("--ring-slots", type=int, default=None, help="feature ring size; default encoder lanes + 1")
+    ap.add_argument("--hw-queues", type=int, default=5,
+                    help="hardware queues the HIP runtime may use in this process (GPU_MAX_HW_QUEUES; the default "
+                         "stream keeps one, the engine's lanes + head streams want four); 0 = leave the environment alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--roofline-only", action="store_true",
@@ -52,6 +56,12 @@ def main() -> None:
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+    if args.hw_queues > 0:
+        os.environ["GPU_MAX_HW_QUEUES"] = str(args.hw_queues)      # read by the runtime when it initialises (below)
+    if args.encoder_lanes is None:
+        args.encoder_lanes = 3 if args.config in ("cfg1", "cfg2", "cfg3") else 2
+    if args.ring_slots is None:
+        args.ring_slots = args.encoder_lanes + 1
 
     import numpy as np
     import torch
@@ -163,7 +173,7 @@ def main() -> None:
         "ms_per_step": round(t_shared * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "batch": spec.batch, "img": [spec.img_h, spec.img_w], "tokens": spec.tokens,
-                   "heads": list(kinds), "ring_slots": args.ring_slots, "encoder_lanes": args.encoder_lanes, "hip_graphs": not args.no_graphs},
+                   "heads": list(kinds), "ring_slots": args.ring_slots, "encoder_lanes": args.encoder_lanes, "hw_queues": args.hw_queues, "hip_graphs": not args.no_graphs},
         "backbone_tflops": round(bb_tflops, 2), "backbone_ms": round(t_enc * 1e3, 4),
         "backbone_mfma_frac": round(bb_tflops / MFMA_PEAK_TFLOPS[spec.dtype], 4),
         "sequential_baseline_fps": round(spec.batch / t_seq, 2), "shared_vs_sequential": round(t_seq / t_shared, 3),
