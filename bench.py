@@ -31,6 +31,81 @@ def backbone_flops(spec) -> float:
     return 2.0 * B * P * 588 * D + spec.depth * per_block
 
 
+def multihead_experiment(args, vpe, vi, make_engine, np, torch) -> None:
+    """Frame latency (submit one resident frame, wait for every head) against the number k of identical heads.
+
+    Arms, all on the same engine and kernels (paper, Sec. "Single Backbone vs. Independent Models" and
+    "Parallel vs. Sequential Processing"):
+      independent       k x (encoder pass + head) one after another on one stream: k separate full models
+      sequential_heads  one encoder pass, then the k heads one after another on that stream
+      concurrent        one encoder pass, the k heads spread over the engine's head streams
+    plus the pipelined rate of the concurrent arm (frames/s without waiting between frames, several encoder
+    lanes) and the device memory each added head costs."""
+    spec = vi.CONFIGS[args.config]
+    wseed, iseed = vi.SEEDS[args.config]
+    images_np = vi.make_batch(spec, iseed)
+    frames = [torch.from_numpy(images_np).cuda(), torch.from_numpy(np.ascontiguousarray(images_np[..., ::-1])).cuda()]
+    one = torch.cuda.Stream()
+    n = max(10, min(args.steps, 60))
+    rows = []
+    for kind in ("depth", "det"):
+        base_ws = None
+        for k in (1, 2, 4, 8):
+            eng, _, _ = make_engine(spec, wseed, kinds=(kind,) * k, ring_slots=2, flags=0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS)
+
+            def independent(i):
+                for h in range(k):
+                    fh = eng.encode(frames[i & 1], stream=one)
+                    eng.run_head(h, fh, stream=one)
+
+            def sequential_heads(i):
+                fh = eng.encode(frames[i & 1], stream=one)
+                for h in range(k):
+                    eng.run_head(h, fh, stream=one)
+
+            def concurrent(i):
+                fh = eng.encode(frames[i & 1])
+                for h in range(k):
+                    eng.run_head(h, fh)
+
+            def latency(fn):
+                lat = []
+                for i in range(n + 5):
+                    t0 = time.perf_counter()
+                    fn(i)
+                    eng.sync()
+                    lat.append((time.perf_counter() - t0) * 1e3)
+                lat = sorted(lat[5:])
+                return lat[len(lat) // 2]
+
+            row = {"head": kind, "k": k, "independent_ms": round(latency(independent), 4),
+                   "sequential_heads_ms": round(latency(sequential_heads), 4), "concurrent_ms": round(latency(concurrent), 4),
+                   "workspace_mb": round(eng.workspace_bytes / 1e6, 1)}
+            eng.close()
+            # pipelined rate: frames are pushed without waiting, consecutive encoder passes overlap
+            lanes = args.encoder_lanes or 3
+            eng, _, _ = make_engine(spec, wseed, kinds=(kind,) * k, ring_slots=lanes + 1, encoder_lanes=lanes,
+                                    flags=0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS)
+            for i in range(10):
+                concurrent(i)
+            eng.sync()
+            t0 = time.perf_counter()
+            for i in range(n):
+                concurrent(i)
+            eng.sync()
+            row["concurrent_pipelined_fps"] = round(n * spec.batch / (time.perf_counter() - t0), 1)
+            eng.close()
+            row["independent_over_concurrent"] = round(row["independent_ms"] / row["concurrent_ms"], 3)
+            row["sequential_over_concurrent"] = round(row["sequential_heads_ms"] / row["concurrent_ms"], 3)
+            if base_ws is None:
+                base_ws = row["workspace_mb"]
+            row["mb_per_added_head"] = round((row["workspace_mb"] - base_ws) / (k - 1), 1) if k > 1 else None
+            rows.append(row)
+            print(json.dumps(row), file=sys.stderr, flush=True)
+    print(json.dumps({"experiment": "multihead", "workload": spec.name, "frames_per_point": n, "hw_queues": args.hw_queues,
+                      "latency": "median ms, one frame at a time, inputs resident in HBM", "rows": rows}))
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +125,10 @@ def main() -> None:
     ap.add_argument("--roofline-only", action="store_true",
                     help="one frame, a 1 GiB device copy (counter calibration) and the dominant-kernel timing leg only; "
                          "the mode the rocprofv3 --pmc passes are taken in")
+    ap.add_argument("--experiment", choices=["multihead"], default=None,
+                    help="multihead: frame latency against the number of identical heads (1, 2, 4, 8), for depth heads "
+                         "(the paper's single-backbone-vs-independent-models experiment) and detection heads (its "
+                         "parallel-vs-sequential-heads experiment); prints its own JSON line instead of the benchmark's")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from the --pmc passes (FETCH_SIZE + WRITE_SIZE, "
                          "calibrated); reported as roofline.traffic")
@@ -69,6 +148,10 @@ def main() -> None:
     import paper_2508_11584_amd as vpe
     import vpe_inputs as vi
     from helpers import make_engine
+
+    if args.experiment == "multihead":
+        multihead_experiment(args, vpe, vi, make_engine, np, torch)
+        return
 
     spec = vi.CONFIGS[args.config]
     wseed, iseed = vi.SEEDS[args.config]
