@@ -42,7 +42,10 @@ struct Bump {
 };
 
 struct BlockW {
-    float *ln1_g, *ln1_b, *qkv_b, *proj_b, *ls1, *ln2_g, *ln2_b, *fc1_b, *fc2_b, *ls2;
+    // The two in-block LayerNorms are folded into the GEMMs that consume them: qkv_w / fc1_w are scaled by the
+    // LayerNorm gain along k, qkv_b / fc1_b hold b + beta W, and qkv_s / fc1_s the column sums of the scaled,
+    // rounded weights (see GemmArgs::ln_stats).  ln1_* / ln2_* are only kept for the upload.
+    float *ln1_g, *ln1_b, *qkv_b, *qkv_s, *proj_b, *ls1, *ln2_g, *ln2_b, *fc1_b, *fc1_s, *fc2_b, *ls2;
     void *qkv_w, *proj_w, *fc1_w, *fc2_w;
 };
 
@@ -93,8 +96,10 @@ struct vpe_engine {
     // f % lanes, so with two lanes the encoder passes of consecutive frames overlap on the GPU (the ViT-S
     // kernels are too small to fill 256 CUs on their own); results per frame are unchanged.
     struct Lane {
+        // x: fp32 residual stream; u: its copy in the engine dtype (the A operand of the LayerNorm-folded
+        // GEMMs; unused by fp32 engines, which read x); stats: per row and 64-column group (sum, sum of squares) of x
         void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
-        float* x = nullptr;
+        float *x = nullptr, *stats = nullptr;
         hipStream_t stream = nullptr;
         hipEvent_t done = nullptr;      // completion of the lane's most recent encode
         bool used = false;
@@ -235,11 +240,11 @@ void layout(vpe_engine& e, Bump& b) {
     e.blk.resize(e.L);
     for (auto& w : e.blk) {
         w.ln1_g = f32(D); w.ln1_b = f32(D);
-        w.qkv_w = b.take(wrows(3 * e.D) * D * esz); w.qkv_b = f32(3 * D);
+        w.qkv_w = b.take(wrows(3 * e.D) * D * esz); w.qkv_b = f32(3 * D); w.qkv_s = f32(3 * D);
         w.proj_w = b.take(wrows(e.D) * D * esz); w.proj_b = f32(D);
         w.ls1 = f32(D);
         w.ln2_g = f32(D); w.ln2_b = f32(D);
-        w.fc1_w = b.take(wrows(e.F) * D * esz); w.fc1_b = f32(e.F);
+        w.fc1_w = b.take(wrows(e.F) * D * esz); w.fc1_b = f32(e.F); w.fc1_s = f32(e.F);
         w.fc2_w = b.take(wrows(e.D) * e.Mh * esz); w.fc2_b = f32(D);
         w.ls2 = f32(D);
     }
@@ -249,6 +254,7 @@ void layout(vpe_engine& e, Bump& b) {
         vpe_engine::Lane& L = e.lane[l];
         L.apatch = b.take(B * P * KPATCH_PAD * esz);
         L.x = f32(T * D);
+        L.stats = f32(T * (D / 64) * 2);
         L.u = b.take(T * D * esz);
         L.qk = b.take(T * 2 * D * esz);
         L.vt = b.take(B * D * e.npad * esz);
@@ -295,16 +301,23 @@ struct Uploader {
     }
     // tensor of `count` floats -> dst rows/cols via relayout_kernel (see rowops.h)
     int relayout(int64_t count, void* dst, int n_rows, int n_cols, int64_t rs, int64_t cs, int mode, int cin,
-                 int swiglu_half, int64_t dst_ld, int row_off, int col_off) {
+                 int swiglu_half, int64_t dst_ld, int row_off, int col_off, const float* kscale = nullptr) {
         HIPCHK(e, hipMemcpy(staging, take(count), 4 * count, hipMemcpyHostToDevice));
         HIPCHK(e, launch_relayout(e->bf, staging, dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld,
-                                  row_off, col_off, nullptr));
+                                  row_off, col_off, kscale, nullptr));
         HIPCHK(e, hipStreamSynchronize(nullptr));
         return 0;
     }
     // y = x W + b weights stored [in][out]  ->  [out][in]
-    int linear(void* dst, int in, int out, int swiglu_half = 0) {
-        return relayout((int64_t)in * out, dst, out, in, 1, out, 0, 0, swiglu_half, in, 0, 0);
+    int linear(void* dst, int in, int out, int swiglu_half = 0, const float* kscale = nullptr) {
+        return relayout((int64_t)in * out, dst, out, in, 1, out, 0, 0, swiglu_half, in, 0, 0, kscale);
+    }
+    // after linear(.., gain) and the upload of `bias` (device, physical order): column sums and folded bias,
+    // from the fp32 weight still in `staging`
+    int fold_ln(int in, int out, int swiglu_half, const float* gain, const float* beta, float* colsum, float* bias) {
+        HIPCHK(e, launch_ln_fold(e->bf, staging, in, out, swiglu_half, gain, beta, colsum, bias, nullptr));
+        HIPCHK(e, hipStreamSynchronize(nullptr));
+        return 0;
     }
 };
 
@@ -328,11 +341,12 @@ int upload_backbone(vpe_engine& e, const float* blob, float* staging) {
     const bool sw = e.cfg.mlp_kind == VPE_MLP_SWIGLU;
     for (auto& w : e.blk) {
         TRY(up.f32(w.ln1_g, D)); TRY(up.f32(w.ln1_b, D));
-        TRY(up.linear(w.qkv_w, D, 3 * D)); TRY(up.f32(w.qkv_b, 3 * D));
+        TRY(up.linear(w.qkv_w, D, 3 * D, 0, w.ln1_g)); TRY(up.f32(w.qkv_b, 3 * D));
+        TRY(up.fold_ln(D, 3 * D, 0, w.ln1_g, w.ln1_b, w.qkv_s, w.qkv_b));
         TRY(up.linear(w.proj_w, D, D)); TRY(up.f32(w.proj_b, D));
         TRY(up.f32(w.ls1, D));
         TRY(up.f32(w.ln2_g, D)); TRY(up.f32(w.ln2_b, D));
-        TRY(up.linear(w.fc1_w, D, e.F, sw ? e.Mh : 0));
+        TRY(up.linear(w.fc1_w, D, e.F, sw ? e.Mh : 0, w.ln2_g));
         if (sw) {   // bias follows the same physical column order as the re-laid weight
             const float* b = up.take(e.F);
             std::vector<float> pb(e.F);
@@ -344,6 +358,7 @@ int upload_backbone(vpe_engine& e, const float* blob, float* staging) {
         } else {
             TRY(up.f32(w.fc1_b, e.F));
         }
+        TRY(up.fold_ln(D, e.F, sw ? e.Mh : 0, w.ln2_g, w.ln2_b, w.fc1_s, w.fc1_b));
         TRY(up.linear(w.fc2_w, e.Mh, D)); TRY(up.f32(w.fc2_b, D));
         TRY(up.f32(w.ls2, D));
     }
@@ -393,21 +408,36 @@ GemmArgs plain_gemm(const void* A, int64_t lda, const void* W, const float* bias
 }
 
 // ------------------------------------------------------------------ launch sequences
+// A GEMM that consumes LayerNorm(x) of the lane's residual stream with the LayerNorm folded in: A is the copy
+// of x in the engine dtype (x itself for fp32 engines), statistics come from the producers' epilogues.
+GemmArgs ln_gemm(const vpe_engine& e, const vpe_engine::Lane& L, const void* W, const float* bias, const float* colsum, int N) {
+    GemmArgs a = plain_gemm(e.bf ? (const void*)L.u : (const void*)L.x, e.D, W, bias, e.T, N, e.D);
+    a.ln_stats = L.stats; a.ln_colsum = colsum; a.ln_groups = e.D / 64; a.ln_eps = e.cfg.ln_eps;
+    return a;
+}
+
+// A GEMM whose epilogue updates the residual stream: also refreshes its copy and its row statistics.
+void produce_stats(const vpe_engine& e, const vpe_engine::Lane& L, GemmArgs& a) {
+    a.out = L.x; a.ldo = e.D;
+    a.st_out = L.stats;
+    a.xb_out = e.bf ? L.u : nullptr;
+}
+
 int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
     const int D = e.D, T = e.T, dt = e.bf;
     const vpe_engine::Lane& L = e.lane[lane];
     {   // patch embedding: [B P][640] x [D][640]^T + bias + pos -> residual stream rows of the patches
         GemmArgs a = plain_gemm(L.apatch, KPATCH_PAD, e.patch_w, e.patch_b, e.B * e.P, D, KPATCH_PAD);
-        a.epi = EPI_PATCH; a.out = L.x; a.ldo = D; a.pos = e.pos;
+        a.epi = EPI_PATCH; a.pos = e.pos;
         a.o_rpi = e.P; a.o_istride = e.N; a.o_off = 1 + e.R;
+        produce_stats(e, L, a);
         HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
     }
     int tap = 0;
     for (int l = 0; l < e.L; ++l) {
         const BlockW& w = e.blk[l];
-        HIPCHK(&e, launch_layernorm(dt, L.x, T, D, w.ln1_g, w.ln1_b, e.cfg.ln_eps, L.u, s));
         {
-            GemmArgs a = plain_gemm(L.u, D, w.qkv_w, w.qkv_b, T, 3 * D, D);
+            GemmArgs a = ln_gemm(e, L, w.qkv_w, w.qkv_b, w.qkv_s, 3 * D);
             a.epi = EPI_QKV; a.out = L.qk; a.ldo = 2 * D; a.out2 = L.vt; a.ntok = e.N; a.npad = e.npad; a.dim = D;
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
@@ -417,12 +447,12 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
         }
         {
             GemmArgs a = plain_gemm(L.att, D, w.proj_w, w.proj_b, T, D, D);
-            a.epi = EPI_RESID; a.out = L.x; a.ldo = D; a.gamma = w.ls1;
+            a.epi = EPI_RESID; a.gamma = w.ls1;
+            produce_stats(e, L, a);
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
-        HIPCHK(&e, launch_layernorm(dt, L.x, T, D, w.ln2_g, w.ln2_b, e.cfg.ln_eps, L.u, s));
         {
-            GemmArgs a = plain_gemm(L.u, D, w.fc1_w, w.fc1_b, T, e.F, D);
+            GemmArgs a = ln_gemm(e, L, w.fc1_w, w.fc1_b, w.fc1_s, e.F);
             a.out = L.hid; a.ldo = e.Mh;
             if (e.cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
             else a.act = ACT_GELU;
@@ -430,7 +460,8 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
         }
         {
             GemmArgs a = plain_gemm(L.hid, e.Mh, w.fc2_w, w.fc2_b, T, D, e.Mh);
-            a.epi = EPI_RESID; a.out = L.x; a.ldo = D; a.gamma = w.ls2;
+            a.epi = EPI_RESID; a.gamma = w.ls2;
+            produce_stats(e, L, a);
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         if (tap < 4 && l + 1 == e.cfg.taps[tap]) {
@@ -677,7 +708,7 @@ int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out) 
         // a lane's scratch is single-instance: order after the lane's previous encode
         if (L.used) HIPCHK(e, hipStreamWaitEvent(s, L.done, 0));
         HIPCHK(e, launch_im2col(e->bf, images, e->B, e->H, e->W, KPATCH_PAD, L.apatch, e->special, 1 + e->R,
-                                e->N, e->D, L.x, s));
+                                e->N, e->D, L.x, e->bf ? L.u : nullptr, L.stats, s));
         if (e->graphs) {
             hipGraphExec_t& ge = e->enc_graphs[(size_t)slot * e->lanes + ln];
             if (!ge) TRY(capture(*e, &ge, [&](hipStream_t cs) { return enqueue_encoder_body(*e, slot, ln, cs); }));
@@ -796,7 +827,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
         if (timed) HIPCHK(e, hipEventRecord(t0, s));
         for (int i = 0; i < (timed ? reps : 1); ++i) {
             if (which == 0) {
-                GemmArgs a = plain_gemm(L0.u, D, e->blk[0].qkv_w, e->blk[0].qkv_b, T, 3 * D, D);
+                GemmArgs a = ln_gemm(*e, L0, e->blk[0].qkv_w, e->blk[0].qkv_b, e->blk[0].qkv_s, 3 * D);
                 a.epi = EPI_QKV; a.out = L0.qk; a.ldo = 2 * D; a.out2 = L0.vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
             } else if (which == 1) {

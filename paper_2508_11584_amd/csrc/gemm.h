@@ -38,6 +38,19 @@ struct GemmArgs {
     const float* pos;    // PATCH: positional rows [o_rpi][N]
     void* out2;          // QKV: transposed values  vt[(b * dim + c)][npad]
     int ntok, npad, dim; // QKV
+    // LayerNorm folded into this GEMM (consumer side): A holds the UN-normalised rows (plain row map), W has
+    // been scaled by the LayerNorm gain along k and bias holds b + beta W; the accumulator of (row r, column c)
+    // becomes rstd_r * (acc - mean_r * ln_colsum[c]) before bias / activation, with ln_colsum[c] = sum_k W[c][k].
+    // ln_stats [M][ln_groups][2]: (sum, sum of squares) of every 64-column group of row r, as written by the
+    // producer below (fp32; the variance is E[x^2] - mean^2, adequate while |mean| is not >> the deviation).
+    const float* ln_stats;     // null: no LayerNorm
+    const float* ln_colsum;
+    int ln_groups;             // = K / 64
+    float ln_eps;
+    // Producer side (RESID / PATCH, N a multiple of 64): besides the fp32 rows, write their copy in T
+    // (xb_out, [rows][N], may be null) and the group statistics of the updated rows (st_out, may be null)
+    void* xb_out;
+    float* st_out;
     // batch of nz independent problems of the same shape in one launch (blockIdx.y = z): problem z uses
     // A + z * z_a, W + z * z_w, out + z * z_out (byte strides, may be negative) and bias + z * z_bias (elements)
     int nz;
@@ -215,6 +228,51 @@ __device__ __forceinline__ float rowdot_chunk(const GemmArgs& p, int c, const fl
     return s;
 }
 
+// (mean, rstd) of row r from its group statistics (sum, sum of squares of each 64-column group): all loads are
+// independent 16-byte loads of two groups each (ln_groups is even or 1 group is handled last).
+__device__ __forceinline__ void ln_row_stats(const GemmArgs& p, int r, float& mean, float& rstd) {
+    const float* st = p.ln_stats + (int64_t)r * p.ln_groups * 2;
+    float s = 0.0f, q = 0.0f;
+    int g = 0;
+#pragma unroll 4
+    for (; g + 2 <= p.ln_groups; g += 2) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(st + 2 * g);
+        s += v[0] + v[2];
+        q += v[1] + v[3];
+    }
+    if (g < p.ln_groups) { s += st[2 * g]; q += st[2 * g + 1]; }
+    const float n = 64.0f * (float)p.ln_groups;
+    mean = s / n;
+    const float var = fmaxf(q / n - mean * mean, 0.0f);
+    rstd = 1.0f / sqrtf(var + p.ln_eps);
+}
+
+// RESID / PATCH chunk with the producer-side extras.  Called by all 8 lanes that hold the 8 chunks of one
+// 64-column group of a row (consecutive lanes, chunk index = lane % 8); `active` is the same for all of them.
+template <typename T>
+__device__ __forceinline__ void resid_stats_chunk(const GemmArgs& p, int r, int c, float* v, bool active, int lane8) {
+    int64_t orow = r;
+    if (active) {
+        epilogue_chunk<T>(p, r, c, v);         // leaves the updated residual values in v
+        if (p.epi == EPI_PATCH) orow = (int64_t)(r / p.o_rpi) * p.o_istride + p.o_off + r % p.o_rpi;
+        if (p.xb_out) store8(reinterpret_cast<T*>(p.xb_out) + orow * p.ldo + c, v);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.0f;
+    }
+    if (!p.st_out) return;
+    float sum = 0.0f, sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { sum += v[i]; sq += v[i] * v[i]; }
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+        sum += __shfl_xor(sum, o);
+        sq += __shfl_xor(sq, o);
+    }
+    if (active && lane8 == 0)
+        *reinterpret_cast<f32x2*>(p.st_out + (orow * (p.N >> 6) + (c >> 6)) * 2) = f32x2{sum, sq};
+}
+
 // Block-level epilogue shared by the register-staged kernels.  The accumulators go through LDS
 // (`smem`, free after the k loop, at least BM * BN * 4 bytes) as a row-major fp32 tile, so that
 // each thread then owns 8 consecutive columns of a row: one row-index computation and 16-byte
@@ -222,13 +280,26 @@ __device__ __forceinline__ float rowdot_chunk(const GemmArgs& p, int c, const fl
 // accumulator element v of lane (g, li) in block (i, j): row = 32 i + 8 (v / 4) + 4 g + v % 4, col = 32 j + li
 template <typename T, int BM, int BN, int WGM, int WGN>
 __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
-                                               char* smem, int m0, int n0) {
+                                               char* smem, const float* lnrow, const float* lncs, int m0, int n0) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int g = lane >> 5, li = lane & 31;
     float* sC = reinterpret_cast<float*>(smem);
+    if (p.ln_stats) {
+        // folded LayerNorm: lnrow[2 row] = mean, lnrow[2 row + 1] = rstd of the tile's rows
+        // lncs[j]: column sum of this lane's column in block j, loaded before the k loop
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const f32x2 st = *reinterpret_cast<const f32x2*>(lnrow + 2 * row);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[i][j][v] = st[1] * (acc[i][j][v] - st[0] * lncs[j]);
+            }
+    }
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -289,6 +360,23 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[
         }
         return;
     }
+    if ((p.epi == EPI_RESID || p.epi == EPI_PATCH) && (p.st_out || p.xb_out)) {
+        constexpr int CG = BN / 8, RPASS = NT / CG;
+        const int cg = tid % CG, c = n0 + cg * 8;
+        for (int rr = tid / CG; rr < BM; rr += RPASS) {
+            const int r = m0 + rr;
+            const bool active = r < p.M && c < p.N;
+            float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (active) {
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * BN + cg * 8 + 4);
+                v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+                v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+            }
+            resid_stats_chunk<T>(p, r, c, v, active, cg & 7);
+        }
+        return;
+    }
     if (p.epi == EPI_ROWDOT) {
         // 8 consecutive lanes hold the 8 chunks of one 64-column group of a row: every lane takes part in
         // the exchange (out-of-range rows / columns contribute zero), the first lane of a group writes
@@ -339,6 +427,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of the loader pass");
     constexpr int STAGE = (BM + BN) * 128;
     __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
+    __shared__ __attribute__((aligned(8))) float lnrow[2 * BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -348,6 +437,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
     int tm, tn;
     tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
+
 
     const T* __restrict__ A = reinterpret_cast<const T*>(p.A);
     const T* __restrict__ W = reinterpret_cast<const T*>(p.W);
@@ -459,6 +549,22 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
     const int klast = KT - 1;
     gload(0, 0);
     gload(1, klast < 1 ? klast : 1);
+    // folded LayerNorm: statistics of this tile's rows, read by the epilogue (the k loop's barriers order
+    // them); placed behind the first tile loads so that it does not delay them
+    float lncs[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) lncs[j] = 0.0f;
+    if (p.ln_stats) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int c = n0 + wn * WN + j * 32 + li;
+            if (c < p.N) lncs[j] = p.ln_colsum[c];
+        }
+        if (tid < BM) {
+            const int r = m0 + tid < p.M ? m0 + tid : p.M - 1;
+            ln_row_stats(p, r, lnrow[2 * tid], lnrow[2 * tid + 1]);
+        }
+    }
     sstore(0, 0);
     __syncthreads();
     for (int kt = 0; kt < KT; kt += 2) {
@@ -474,7 +580,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
     }
 
     static_assert(BM * BN * 4 <= 2 * STAGE, "accumulator tile must fit the stage buffers");
-    block_epilogue<T, BM, BN, WGM, WGN>(p, acc, smem, m0, n0);
+    block_epilogue<T, BM, BN, WGM, WGN>(p, acc, smem, lnrow, lncs, m0, n0);
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN>

@@ -26,10 +26,11 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 // BK = 64 or 32 elements per k-tile (LDS rows of 128 or 64 bytes), S LDS stages: the loads of tile
 // kt + S - 1 are in flight while tile kt is multiplied, so a load has S - 1 tile times to arrive.
+// OCC workgroups per CU (the launch bound is given in waves per SIMD: OCC * waves / 4).
 // WGM x 2 waves: WGM = 2 gives 128-row wave tiles (256 accumulator registers, one wave per SIMD),
 // WGM = 4 gives 64-row wave tiles and two waves per SIMD, i.e. twice as many waves issuing loads.
 template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE>
-__global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const GemmArgs args) {
+__global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_kernel(const GemmArgs args) {
     const GemmArgs p = select_problem(args);
     typedef bf16 T;
     constexpr int BM = 256, CE = 8, NW = WGN * WGM;
@@ -50,6 +51,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
     int tm, tn;
     tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
+
+    // folded LayerNorm: (mean, rstd) of this tile's rows live behind the stage / staging buffers
+    constexpr int EPI_BYTES = NW * 32 * WN * 4;
+    float* lnrow = reinterpret_cast<float*>(smem + (S * STAGE > EPI_BYTES ? S * STAGE : EPI_BYTES));
 
     const char* __restrict__ A = reinterpret_cast<const char*>(p.A);
     const char* __restrict__ W = reinterpret_cast<const char*>(p.W);
@@ -175,6 +180,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
     const int KT = p.K / BK;
 #pragma unroll
     for (int s = 0; s < PD; ++s) dma(s, s < KT ? s : KT - 1);
+    if (p.ln_stats && tid < BM) {      // behind the first tile loads, ordered before the epilogue by the loop's barriers
+        const int r = m0 + tid < p.M ? m0 + tid : p.M - 1;
+        ln_row_stats(p, r, lnrow[2 * tid], lnrow[2 * tid + 1]);
+    }
     for (int kt = 0; kt < KT; ++kt) {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * (A_SLOTS + B_SLOTS)));
         __syncthreads();
@@ -191,6 +200,22 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
     const int wrow0 = m0 + wm * WM, wcol0 = n0 + wn * WN;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
+        if (p.ln_stats) {
+            // (column sums are loaded here, not before the k loop: this kernel has no registers to spare)
+            float lncs[NI];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int c = wcol0 + j * 32 + li;
+                lncs[j] = c < p.N ? p.ln_colsum[c] : 0.0f;
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const f32x2 st = *reinterpret_cast<const f32x2*>(lnrow + 2 * row);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[i][j][v] = st[1] * (acc[i][j][v] - st[0] * lncs[j]);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -237,6 +262,24 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
                     }
                 }
             }
+        } else if ((p.epi == EPI_RESID || p.epi == EPI_PATCH) && (p.st_out || p.xb_out)) {
+            // a wave's 64 columns are one statistics group: 8 consecutive lanes hold a row's 8 chunks
+            if constexpr (WN == 64) {
+#pragma unroll
+                for (int it = lane; it < 32 * 8; it += 64) {
+                    const int rr = it >> 3, cg = it & 7;
+                    const int r = rblk + rr, c = wcol0 + cg * 8;
+                    const bool active = r < p.M && c < p.N;
+                    float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (active) {
+                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
+                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
+                        v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+                        v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+                    }
+                    resid_stats_chunk<T>(p, r, c, v, active, cg);
+                }
+            }
         } else if (p.epi == EPI_ROWDOT) {
             // a wave's 64 columns are one projection group: 8 consecutive lanes hold a row's 8 chunks
             if constexpr (WN == 64) {
@@ -277,7 +320,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_dma_kernel(const Gem
 template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1>
 static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
     constexpr int stage_b = S * (256 + BN) * BK * 2, epi_b = WGM * WGN * 32 * (BN / WGN) * 4;
-    constexpr int lds = stage_b > epi_b ? stage_b : epi_b;
+    constexpr int lds = (stage_b > epi_b ? stage_b : epi_b) + 256 * 8;     // + (mean, rstd) of the tile's 256 rows
     static_assert(lds * OCC <= 160 * 1024, "LDS budget of one CU");
     static bool configured = false;
     if (!configured) {

@@ -17,10 +17,13 @@ hipError_t configure_gemm();
 hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const float* g, const float* b,
                             float eps, void* y, hipStream_t s);
 hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
-                         const float* special, int nspecial, int ntok, int D, float* x, hipStream_t s);
+                         const float* special, int nspecial, int ntok, int D, float* x, void* xb, float* stats,
+                         hipStream_t s);
 hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, int n_cols, int64_t rs,
                            int64_t cs, int mode, int cin, int swiglu_half, int64_t dst_ld, int row_off,
-                           int col_off, hipStream_t s);
+                           int col_off, const float* kscale, hipStream_t s);
+hipError_t launch_ln_fold(int dtype, const float* src, int K, int n_out, int swiglu_half, const float* gain,
+                          const float* beta, float* colsum, float* bias, hipStream_t s);
 hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint8_t* out, hipStream_t s);
 hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const void* r, int B, int Hs, int Ws,
                                 int C, void* z, hipStream_t s);

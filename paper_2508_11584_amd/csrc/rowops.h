@@ -58,12 +58,15 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 // Patch gathering for the 14x14 stride-14 embedding: row (b, p) of `cols` receives the 588
 // pixels of patch p in (channel, row, column) order, zero-padded to kpad columns.  The same
 // launch also fills the non-patch rows of the residual stream (CLS + pos[0], then registers)
-// from the `special` table [1 + R][D].  blocks [0, B*P) gather; the rest write special rows.
+// from the `special` table [1 + R][D], together with their copy in T (xb, may be null) and the (sum, sum
+// of squares) of each of their 64-column groups (stats [rows][D / 64][2], may be null) -- what
+// the GEMM epilogues produce for the other rows.  blocks [0, B*P) gather; the rest write special rows.
 template <typename T>
 __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ img, int B, int H, int W,
                                                      int kpad, T* __restrict__ cols,
                                                      const float* __restrict__ special, int nspecial,
-                                                     int ntok, int D, float* __restrict__ x) {
+                                                     int ntok, int D, float* __restrict__ x,
+                                                     T* __restrict__ xb, float* __restrict__ stats) {
     const int gw = W / 14, P = (H / 14) * gw;
     int blk = blockIdx.x;
     if (blk < B * P) {
@@ -80,7 +83,19 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ i
     } else {
         blk -= B * P;
         const int b = blk / nspecial, r = blk % nspecial;
-        for (int d = threadIdx.x; d < D; d += 256) x[((int64_t)b * ntok + r) * D + d] = special[(int64_t)r * D + d];
+        const int64_t row = (int64_t)b * ntok + r;
+        const int lane = threadIdx.x & 63;
+        for (int grp = threadIdx.x >> 6; grp < D / 64; grp += 4) {      // one wave per 64-column group
+            const int d = grp * 64 + lane;
+            const float v = special[(int64_t)r * D + d];
+            x[row * D + d] = v;
+            if (xb) xb[row * D + d] = from_f32<T>(v);
+            const float sum = wave_sum(v), sq = wave_sum(v * v);
+            if (stats && lane == 0) {
+                stats[(row * (D / 64) + grp) * 2] = sum;
+                stats[(row * (D / 64) + grp) * 2 + 1] = sq;
+            }
+        }
     }
 }
 
@@ -89,26 +104,51 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ i
 //   mode 1: src is a conv kernel [n][cin][3][3]; k = tap * cin + ci -> src[(n * cin + ci) * 9 + tap]
 //   swiglu != 0: physical row n reads logical row  32 (n / 64) + n % 64          if n % 64 < 32
 //                                                  half + 32 (n / 64) + n % 64 - 32   otherwise
+//   kscale != null: element (n, k) is multiplied by kscale[k] before rounding (a LayerNorm gain folded in)
+__device__ __forceinline__ int swiglu_row(int n, int swiglu_half) {
+    if (!swiglu_half) return n;
+    const int grp = n >> 6, j = n & 63;
+    return j < 32 ? 32 * grp + j : swiglu_half + 32 * grp + j - 32;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void relayout_kernel(const float* __restrict__ src, T* __restrict__ dst,
                                                        int n_rows, int n_cols, int64_t rs, int64_t cs,
                                                        int mode, int cin, int swiglu_half, int64_t dst_ld,
-                                                       int row_off, int col_off) {
+                                                       int row_off, int col_off, const float* __restrict__ kscale) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)n_rows * n_cols) return;
     const int n = (int)(idx / n_cols), k = (int)(idx % n_cols);
-    int nl = n;
-    if (swiglu_half) {
-        const int grp = n >> 6, j = n & 63;
-        nl = j < 32 ? 32 * grp + j : swiglu_half + 32 * grp + j - 32;
-    }
+    const int nl = swiglu_row(n, swiglu_half);
     int64_t si;
     if (mode == 0) si = nl * rs + k * cs;
     else {
         const int tap = k / cin, ci = k % cin;
         si = ((int64_t)nl * cin + ci) * 9 + tap;
     }
-    dst[(int64_t)(row_off + n) * dst_ld + col_off + k] = from_f32<T>(src[si]);
+    dst[(int64_t)(row_off + n) * dst_ld + col_off + k] = from_f32<T>(kscale ? src[si] * kscale[k] : src[si]);
+}
+
+// Companion of a re-layout with a folded LayerNorm (y = LN(x) W + b with gain g and shift beta):
+//   colsum[n] = sum_k w'[n][k]  with w' = the re-laid, gain-scaled and ROUNDED weight (what the MFMA multiplies),
+//   bias[n]  += sum_k beta[k] * w[k][n]   (unscaled, unrounded weight),
+// for physical row n (SwiGLU order as in relayout_kernel).  src is the linear weight [K][n_out] in fp32.
+// One thread per output column; the K-long sums run in double.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fold_kernel(const float* __restrict__ src, int K, int n_out, int swiglu_half,
+                                                      const float* __restrict__ gain, const float* __restrict__ beta,
+                                                      float* __restrict__ colsum, float* __restrict__ bias) {
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= n_out) return;
+    const int nl = swiglu_row(n, swiglu_half);
+    double cs = 0.0, bb = 0.0;
+    for (int k = 0; k < K; ++k) {
+        const float w = src[(int64_t)k * n_out + nl];
+        cs += (double)to_f32(from_f32<T>(w * gain[k]));
+        bb += (double)beta[k] * (double)w;
+    }
+    colsum[n] = (float)cs;
+    bias[n] += (float)bb;
 }
 
 // Per-row argmax over the first C of `ld` fp32 values (ties -> lowest index); one wave per row:

@@ -16,21 +16,29 @@ hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const fl
 }
 
 hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
-                         const float* special, int nspecial, int ntok, int D, float* x, hipStream_t s) {
+                         const float* special, int nspecial, int ntok, int D, float* x, void* xb, float* stats,
+                         hipStream_t s) {
     const int P = (H / 14) * (W / 14);
     const unsigned nb = (unsigned)(B * P + B * nspecial);
-    if (dtype) hipLaunchKernelGGL(im2col_kernel<bf16>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (bf16*)cols, special, nspecial, ntok, D, x);
-    else hipLaunchKernelGGL(im2col_kernel<float>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (float*)cols, special, nspecial, ntok, D, x);
+    if (dtype) hipLaunchKernelGGL(im2col_kernel<bf16>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (bf16*)cols, special, nspecial, ntok, D, x, (bf16*)xb, stats);
+    else hipLaunchKernelGGL(im2col_kernel<float>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (float*)cols, special, nspecial, ntok, D, x, (float*)xb, stats);
     return hipGetLastError();
 }
 
 hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, int n_cols, int64_t rs,
                            int64_t cs, int mode, int cin, int swiglu_half, int64_t dst_ld, int row_off,
-                           int col_off, hipStream_t s) {
+                           int col_off, const float* kscale, hipStream_t s) {
     const int64_t n = (int64_t)n_rows * n_cols;
     if (n <= 0) return hipSuccess;
-    if (dtype) hipLaunchKernelGGL(relayout_kernel<bf16>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, (bf16*)dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off, col_off);
-    else hipLaunchKernelGGL(relayout_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, (float*)dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off, col_off);
+    if (dtype) hipLaunchKernelGGL(relayout_kernel<bf16>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, (bf16*)dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off, col_off, kscale);
+    else hipLaunchKernelGGL(relayout_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, (float*)dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off, col_off, kscale);
+    return hipGetLastError();
+}
+
+hipError_t launch_ln_fold(int dtype, const float* src, int K, int n_out, int swiglu_half, const float* gain,
+                          const float* beta, float* colsum, float* bias, hipStream_t s) {
+    if (dtype) hipLaunchKernelGGL(ln_fold_kernel<bf16>, dim3(blocks_for(n_out, 256)), dim3(256), 0, s, src, K, n_out, swiglu_half, gain, beta, colsum, bias);
+    else hipLaunchKernelGGL(ln_fold_kernel<float>, dim3(blocks_for(n_out, 256)), dim3(256), 0, s, src, K, n_out, swiglu_half, gain, beta, colsum, bias);
     return hipGetLastError();
 }
 
