@@ -139,12 +139,29 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
  * the GPU) for heads still reading that slot, runs the encoder, and returns the handle. */
 int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out);
 
+/* As vpe_encode, for a frame captured at time t_seconds (any monotonic clock of the caller's: a camera
+ * timestamp, or frame index / frame rate).  The time is kept with the frame and is what per-head limits in
+ * Hz (vpe_set_head_rate_hz) are measured against; frames encoded with vpe_encode carry no time and are
+ * not limited in Hz.  t_seconds must not decrease from one frame to the next (VPE_EINVAL). */
+int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_seconds, vpe_feat* out);
+
 /* Run head `head` on a frame's features.  Returns VPE_SKIPPED when fh.frame % every_n != 0,
  * VPE_ESTALE when the slot has been reused by a later frame. */
 int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream);
 
 /* Change a head's rate; takes effect from the next vpe_run_head.  every_n_frames < 1 -> VPE_EINVAL. */
 int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames);
+
+/* Upper limit on a head's rate in runs per second of frame time (paper, Sec. "Dynamic Frequency Control"
+ * and Appendix "Rate-Limiting Experiment": each head's rate can be set at run time, and over 300 frames at
+ * 30 Hz the delivered counts stay within one frame of rate x duration); 0 = no limit.
+ * The head keeps a due time: a frame stamped t (vpe_encode_at) is processed iff t >= due (less a millionth
+ * of a period, for rounding), and the due time then advances by one period 1 / max_hz (it accumulates, so a limit that is not
+ * a divisor of the input rate is met on average: over any span the number of runs differs from
+ * span * max_hz by at most one); after a gap of more than a period the due time restarts from the
+ * frame's time.  A frame that is not due returns VPE_SKIPPED, like the frame divider, which still applies
+ * (both must pass).  Takes effect from the next vpe_run_head; max_hz < 0 or not finite -> VPE_EINVAL. */
+int vpe_set_head_rate_hz(vpe_engine* e, int head, double max_hz);
 
 /* Borrowed DEVICE pointer to feature map `tap` (0..3, 3 = final tokens) of a frame:
  * [batch][N][dim] in the engine's dtype.  Valid until the slot is reused. */

@@ -63,6 +63,8 @@ def load_library(path: Optional[str] = None):
     L.vpe_encode.argtypes = [vp, vp, vp, C.POINTER(vpe_feat)]
     L.vpe_run_head.argtypes = [vp, i32, vpe_feat, vp]
     L.vpe_set_head_rate.argtypes = [vp, i32, i32]
+    L.vpe_encode_at.argtypes = [vp, vp, vp, C.c_double, C.POINTER(vpe_feat)]
+    L.vpe_set_head_rate_hz.argtypes = [vp, i32, C.c_double]
     L.vpe_feat_view.argtypes = [vp, vpe_feat, i32, C.POINTER(vp), i64p]
     L.vpe_head_output.argtypes = [vp, i32, i32, C.POINTER(vp), i64p]
     L.vpe_sync.argtypes = [vp]
@@ -72,7 +74,8 @@ def load_library(path: Optional[str] = None):
     L.vpe_last_error.restype = C.c_char_p
     L.vpe_destroy.argtypes = [vp]
     L.vpe_destroy.restype = None
-    for n in ("vpe_workspace_bytes", "vpe_create", "vpe_encode", "vpe_run_head", "vpe_set_head_rate", "vpe_feat_view",
+    for n in ("vpe_workspace_bytes", "vpe_create", "vpe_encode", "vpe_encode_at", "vpe_run_head", "vpe_set_head_rate",
+              "vpe_set_head_rate_hz", "vpe_feat_view",
               "vpe_head_output", "vpe_sync", "vpe_stats", "vpe_time_kernel"):
         getattr(L, n).restype = C.c_int
     if path is None:
@@ -113,6 +116,14 @@ def vpe_encode(engine, images_ptr: int, stream_ptr: Optional[int] = None) -> vpe
     return fh
 
 
+def vpe_encode_at(engine, images_ptr: int, stream_ptr: Optional[int], t_seconds: float) -> vpe_feat:
+    fh = vpe_feat()
+    rc = lib().vpe_encode_at(engine, images_ptr, stream_ptr, t_seconds, C.byref(fh))
+    if rc:
+        raise VpeError(rc, vpe_last_error(engine))
+    return fh
+
+
 def vpe_run_head(engine, head: int, fh: vpe_feat, stream_ptr: Optional[int] = None) -> int:
     rc = lib().vpe_run_head(engine, head, fh, stream_ptr)
     if rc < 0:
@@ -122,6 +133,12 @@ def vpe_run_head(engine, head: int, fh: vpe_feat, stream_ptr: Optional[int] = No
 
 def vpe_set_head_rate(engine, head: int, every_n_frames: int) -> None:
     rc = lib().vpe_set_head_rate(engine, head, every_n_frames)
+    if rc:
+        raise VpeError(rc, vpe_last_error(engine))
+
+
+def vpe_set_head_rate_hz(engine, head: int, max_hz: float) -> None:
+    rc = lib().vpe_set_head_rate_hz(engine, head, max_hz)
     if rc:
         raise VpeError(rc, vpe_last_error(engine))
 
@@ -219,19 +236,24 @@ class Engine:
         self.handle = vpe_create(cfg, harr, self.n_heads, ws_ptr, ws_bytes)
 
     # -- calls
-    def encode(self, images, stream=None) -> vpe_feat:
-        """images: torch float32 CUDA tensor [B,3,H,W] (contiguous) -- or None in host-only mode."""
-        if self.host_only:
-            return vpe_encode(self.handle, None, None)
-        assert images.is_cuda and images.is_contiguous() and images.dtype.is_floating_point and images.element_size() == 4
-        assert tuple(images.shape) == (self.cfg.batch, 3, self.cfg.img_h, self.cfg.img_w), images.shape
-        return vpe_encode(self.handle, images.data_ptr(), None if stream is None else stream.cuda_stream)
+    def encode(self, images, stream=None, t: Optional[float] = None) -> vpe_feat:
+        """images: torch float32 CUDA tensor [B,3,H,W] (contiguous) -- or None in host-only mode.
+        t: capture time of the frame in seconds (for per-head limits in Hz), or None."""
+        ptr = sp = None
+        if not self.host_only:
+            assert images.is_cuda and images.is_contiguous() and images.dtype.is_floating_point and images.element_size() == 4
+            assert tuple(images.shape) == (self.cfg.batch, 3, self.cfg.img_h, self.cfg.img_w), images.shape
+            ptr, sp = images.data_ptr(), None if stream is None else stream.cuda_stream
+        return vpe_encode(self.handle, ptr, sp) if t is None else vpe_encode_at(self.handle, ptr, sp, t)
 
     def run_head(self, head: int, fh: vpe_feat, stream=None) -> int:
         return vpe_run_head(self.handle, head, fh, None if stream is None else stream.cuda_stream)
 
     def set_head_rate(self, head: int, every_n: int) -> None:
         vpe_set_head_rate(self.handle, head, every_n)
+
+    def set_head_rate_hz(self, head: int, max_hz: float) -> None:
+        vpe_set_head_rate_hz(self.handle, head, max_hz)
 
     def sync(self) -> None:
         vpe_sync(self.handle)

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -74,6 +75,9 @@ struct Head {
     hipEvent_t last_done = nullptr;   // completion of the most recent run (any slot)
     bool ran = false;
     int64_t runs = 0, skips = 0;
+    double period = 0.0;              // 1 / max_hz, 0 = no limit in Hz
+    double due = 0.0;                 // frame time from which the next run is allowed
+    bool due_set = false;
     std::vector<hipGraphExec_t> graphs;   // per slot
 };
 
@@ -109,6 +113,9 @@ struct vpe_engine {
     // ring
     std::vector<void*> feat;             // [S][4]
     std::vector<int64_t> slot_frame;     // frame held by each slot, -1 = none
+    std::vector<double> slot_time;       // its capture time, NaN = none given
+    double last_time = 0.0;
+    bool have_time = false;
     std::vector<hipEvent_t> ready;       // [S]
     std::vector<hipEvent_t> done;        // [S][n_heads]
     std::vector<char> done_set;          // [S][n_heads]
@@ -612,6 +619,7 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     auto bail = [&](int code) { g_create_error = e->err; destroy_engine(e); return code; };
     const int nh = (int)e->heads.size();
     e->slot_frame.assign(e->S, -1);
+    e->slot_time.assign(e->S, std::nan(""));
     e->done_set.assign((size_t)e->S * std::max(nh, 1), 0);
     if (e->host_only) { *out = e; return VPE_OK; }
 
@@ -691,9 +699,19 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
 }
 
 int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out) {
+    return vpe_encode_at(e, images, stream, std::nan(""), out);
+}
+
+int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_seconds, vpe_feat* out) {
     if (!e) return VPE_EINVAL;
     if (!out) return e->fail(VPE_EINVAL, "out is null");
     if (!images && !e->host_only) return e->fail(VPE_EINVAL, "images is null");
+    if (std::isinf(t_seconds)) return e->fail(VPE_EINVAL, "frame time is not finite");
+    if (!std::isnan(t_seconds)) {
+        if (e->have_time && t_seconds < e->last_time) return e->fail(VPE_EINVAL, "frame time went backwards");
+        e->last_time = t_seconds;
+        e->have_time = true;
+    }
     const int64_t frame = e->frames;
     const int slot = (int)(frame % e->S);
     const int nh = (int)e->heads.size();
@@ -722,6 +740,7 @@ int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out) 
     }
     for (int h = 0; h < nh; ++h) e->done_set[(size_t)slot * nh + h] = 0;
     e->slot_frame[slot] = frame;
+    e->slot_time[slot] = t_seconds;
     e->frames = frame + 1;
     out->slot = slot;
     out->reserved = 0;
@@ -737,6 +756,13 @@ int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream) {
     Head& h = e->heads[head];
     if (fh.frame % h.every_n != 0) { ++h.skips; return VPE_SKIPPED; }
     if (e->slot_frame[fh.slot] != fh.frame) return e->fail(VPE_ESTALE, "slot has been reused by a later frame");
+    const double t = e->slot_time[fh.slot];
+    if (h.period > 0.0 && !std::isnan(t)) {
+        if (h.due_set && t < h.due - 1e-6 * h.period) { ++h.skips; return VPE_SKIPPED; }
+        // accumulate while the head keeps up; after a gap of more than a period start again from this frame
+        h.due = h.due_set && t - h.due < h.period ? h.due + h.period : t + h.period;
+        h.due_set = true;
+    }
     const int nh = (int)e->heads.size();
     if (!e->host_only) {
         hipStream_t s = stream ? (hipStream_t)stream : h.stream;
@@ -765,6 +791,16 @@ int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames) {
     if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
     if (every_n_frames < 1) return e->fail(VPE_EINVAL, "every_n_frames must be >= 1");
     e->heads[head].every_n = every_n_frames;
+    return VPE_OK;
+}
+
+int vpe_set_head_rate_hz(vpe_engine* e, int head, double max_hz) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    if (!(max_hz >= 0.0) || std::isinf(max_hz)) return e->fail(VPE_EINVAL, "max_hz must be finite and >= 0");
+    Head& h = e->heads[head];
+    h.period = max_hz > 0.0 ? 1.0 / max_hz : 0.0;
+    h.due_set = false;
     return VPE_OK;
 }
 

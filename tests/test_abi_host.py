@@ -130,6 +130,68 @@ def test_rate_divider_counts_are_exact_over_300_frames():
     assert frames == 300 and runs == [300, 150, 100] and skips == [0, 150, 200]
 
 
+def test_rate_limits_in_hz_hold_within_one_frame_over_300_frames():
+    # the paper's rate-limiting experiment (Appendix "Rate-Limiting Experiment" and its table: 300 images fed
+    # at 30 Hz over 10 s, components limited to 5 / 10 / 15 / 20 / 25 / 30 Hz, ideal counts 50 .. 300, every
+    # count within one frame of the ideal), with frame times as the clock; plus an odd rate, no limit, and a
+    # limit above the input rate
+    limits = [30.0, 15.0, 10.0, 20.0, 7.0, 0.0, 45.0, 5.0, 25.0]
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg",) * len(limits), flags=vpe.VPE_FLAG_HOST_ONLY)
+    for h, hz in enumerate(limits):
+        eng.set_head_rate_hz(h, hz)
+    ran = [[] for _ in limits]
+    for f in range(300):
+        fh = eng.encode(None, t=f / 30.0)
+        for h in range(len(limits)):
+            if eng.run_head(h, fh) == 0:
+                ran[h].append(f)
+    for h, hz in enumerate(limits):
+        want = 300 if hz == 0.0 or hz >= 30.0 else hz * 10.0
+        assert abs(len(ran[h]) - want) <= 1, (hz, len(ran[h]))
+        if 0.0 < hz < 30.0:
+            gaps = np.diff(ran[h]) / 30.0
+            # accumulating due times: single gaps may be one frame short of the period, never more, and any
+            # two consecutive gaps together respect it
+            assert gaps.min() >= 1.0 / hz - 1.0 / 30.0 - 1e-9
+            assert gaps.max() <= 1.0 / hz + 1.0 / 30.0 + 1e-9
+    assert ran[1] == list(range(0, 300, 2)) and ran[2] == list(range(0, 300, 3))
+    assert ran[3][:5] == [0, 2, 3, 5, 6]                      # 20 Hz out of 30 Hz: two of every three frames
+    assert [len(ran[h]) for h in (7, 2, 1, 3, 8, 0)] == [50, 100, 150, 200, 250, 300]     # the table's ideal counts
+    frames, runs, skips = eng.stats()
+    assert all(r + s == 300 for r, s in zip(runs, skips))
+
+
+def test_rate_limit_in_hz_restarts_after_a_gap_and_combines_with_the_divider():
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg", "seg"), every_n=(1, 2), flags=vpe.VPE_FLAG_HOST_ONLY)
+    eng.set_head_rate_hz(0, 10.0)
+    eng.set_head_rate_hz(1, 10.0)
+    times = [i / 100.0 for i in range(100)] + [6.0 + i / 100.0 for i in range(100)]     # 1 s, a 5 s pause, 1 s
+    ran = [[], []]
+    for t in times:
+        fh = eng.encode(None, t=t)
+        for h in range(2):
+            if eng.run_head(h, fh) == 0:
+                ran[h].append(t)
+    for h in range(2):
+        assert len(ran[h]) == 20                                  # 10 per second of input, no burst after the pause
+        assert np.diff(ran[h]).min() >= 0.1 - 1e-9
+        assert 6.0 in ran[h]                                      # the first frame after the pause runs at once
+    # frames without a time are never limited in Hz; the limit can be lifted again
+    fh = eng.encode(None)
+    assert eng.run_head(0, fh) == 0
+    eng.set_head_rate_hz(0, 0.0)
+    for t in (7.0, 7.001, 7.002):
+        assert eng.run_head(0, eng.encode(None, t=t)) == 0
+    with pytest.raises(vpe.VpeError, match="backwards"):
+        eng.encode(None, t=6.5)
+    with pytest.raises(vpe.VpeError, match="max_hz"):
+        eng.set_head_rate_hz(0, -1.0)
+    with pytest.raises(vpe.VpeError, match="max_hz"):
+        eng.set_head_rate_hz(0, float("nan"))
+    with pytest.raises(vpe.VpeError, match="unknown head"):
+        eng.set_head_rate_hz(5, 1.0)
+
+
 def test_rate_can_change_at_run_time():
     eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg",), flags=vpe.VPE_FLAG_HOST_ONLY)
     ran = []

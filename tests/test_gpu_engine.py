@@ -224,3 +224,32 @@ def test_encoder_lanes_and_shared_head_streams_give_the_same_frames_as_one_lane(
     for other in (2, 3):
         for a, b in zip(res[1], res[other]):
             assert torch.equal(a, b)
+
+
+def test_rate_limit_in_hz_on_the_device():
+    # 12 frames stamped at 30 Hz, depth limited to 15 Hz and detection to 10 Hz: the outputs left at the end
+    # are those of the last frame each head was allowed to run on (seg 11, depth 10, det 9)
+    fs = frames(4, seed=900)
+    eng, _, _ = make_engine(SPEC, 21, flags=vpe.VPE_FLAG_GRAPHS, ring_slots=3, encoder_lanes=2)
+    eng.set_head_rate_hz(1, 15.0)
+    eng.set_head_rate_hz(2, 10.0)
+    ran = {0: [], 1: [], 2: []}
+    for i in range(12):
+        fh = eng.encode(fs[i % 4], t=i / 30.0)
+        for h in range(3):
+            if eng.run_head(h, fh) == 0:
+                ran[h].append(i)
+    eng.sync()
+    got = outputs(eng)
+    eng.close()
+    assert ran == {0: list(range(12)), 1: [0, 2, 4, 6, 8, 10], 2: [0, 3, 6, 9]}
+    eng, _, _ = make_engine(SPEC, 21)
+    exp = {}
+    for h in range(3):
+        fh = eng.encode(fs[ran[h][-1] % 4])
+        eng.run_head(h, fh)
+        eng.sync()
+        exp[h] = outputs(eng)
+    for a, b in zip(got, [exp[0][0], exp[0][1], exp[1][2], exp[2][3], exp[2][4]]):
+        assert torch.equal(a, b)
+    eng.close()
