@@ -139,6 +139,23 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
  * the GPU) for heads still reading that slot, runs the encoder, and returns the handle. */
 int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out);
 
+/* Camera-frame transform in front of vpe_encode (paper, Sec. "Transforms": the pre-processing adapter between
+ * user data and the foundation model -- type conversion, resizing, normalisation -- runs on the GPU).
+ *   frames: DEVICE uint8 [batch][src_h][src_w][3], interleaved RGB;  images: DEVICE fp32 [batch][3][dst_h][dst_w];
+ *   images[c] = (bilinear(frames[..., c] / 255 -> dst_h x dst_w) - mean[c]) / std[c], half-pixel centres, no
+ *   antialiasing filter (the paper does not say how its 1920x1080 frames reach the model's resolution);
+ *   mean, std: HOST, 3 floats each, std > 0.
+ * Needs no engine; only enqueues (stream NULL = the default stream); the caller owns both buffers.  Returns
+ * VPE_EINVAL on null pointers, non-positive sizes or std <= 0, VPE_EHIP on a launch failure. */
+int vpe_preprocess_u8(const uint8_t* frames, int batch, int src_h, int src_w, float* images, int dst_h, int dst_w,
+                      const float mean[3], const float std[3], void* stream);
+
+/* The engine-owned stream that the next vpe_encode / vpe_encode_at with stream == NULL will run on (one per
+ * encoder lane, taken in turn).  Work the caller enqueues on it first -- vpe_preprocess_u8, a host-to-device
+ * copy of the frame -- is ordered before that encode without an event and without another stream competing
+ * for a hardware queue.  Borrowed: do not destroy it.  host-only engines return NULL in *stream. */
+int vpe_next_encode_stream(vpe_engine* e, void** stream);
+
 /* As vpe_encode, for a frame captured at time t_seconds (any monotonic clock of the caller's: a camera
  * timestamp, or frame index / frame rate).  The time is kept with the frame and is what per-head limits in
  * Hz (vpe_set_head_rate_hz) are measured against; frames encoded with vpe_encode carry no time and are

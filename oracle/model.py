@@ -22,6 +22,21 @@ from . import ops
 MLP_SWIGLU = 1
 
 
+def preprocess_u8(frame, H: int, W: int, mean, std) -> np.ndarray:
+    """Camera-frame transform (paper, Sec. "Transforms": type conversion, resizing, normalisation).
+
+    frame [Hs][Ws][3] uint8 interleaved RGB -> [3][H][W]: each channel scaled to 0..1, resized bilinearly
+    (half-pixel centres, no antialiasing filter; nothing is rounded back to integers), then (v - mean_c) / std_c.
+    """
+    f = np.asarray(frame)
+    assert f.dtype == np.uint8 and f.ndim == 3 and f.shape[2] == 3
+    planes = np.ascontiguousarray(f.transpose(2, 0, 1)).astype(np.float64) / 255.0
+    r = ops.bilinear(planes, H, W)
+    m = np.asarray(mean, dtype=np.float64).reshape(3, 1, 1)
+    s = np.asarray(std, dtype=np.float64).reshape(3, 1, 1)
+    return (r - m) / s
+
+
 def tokens_from_image(spec, w, img) -> np.ndarray:
     """x0 [N][D]: CLS + pos[0]; registers (no positional term); patch p + pos[1+p].
 

@@ -63,6 +63,8 @@ def load_library(path: Optional[str] = None):
     L.vpe_encode.argtypes = [vp, vp, vp, C.POINTER(vpe_feat)]
     L.vpe_run_head.argtypes = [vp, i32, vpe_feat, vp]
     L.vpe_set_head_rate.argtypes = [vp, i32, i32]
+    L.vpe_next_encode_stream.argtypes = [vp, C.POINTER(C.c_void_p)]
+    L.vpe_preprocess_u8.argtypes = [vp, i32, i32, i32, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
     L.vpe_encode_at.argtypes = [vp, vp, vp, C.c_double, C.POINTER(vpe_feat)]
     L.vpe_set_head_rate_hz.argtypes = [vp, i32, C.c_double]
     L.vpe_feat_view.argtypes = [vp, vpe_feat, i32, C.POINTER(vp), i64p]
@@ -75,7 +77,7 @@ def load_library(path: Optional[str] = None):
     L.vpe_destroy.argtypes = [vp]
     L.vpe_destroy.restype = None
     for n in ("vpe_workspace_bytes", "vpe_create", "vpe_encode", "vpe_encode_at", "vpe_run_head", "vpe_set_head_rate",
-              "vpe_set_head_rate_hz", "vpe_feat_view",
+              "vpe_set_head_rate_hz", "vpe_preprocess_u8", "vpe_next_encode_stream", "vpe_feat_view",
               "vpe_head_output", "vpe_sync", "vpe_stats", "vpe_time_kernel"):
         getattr(L, n).restype = C.c_int
     if path is None:
@@ -114,6 +116,34 @@ def vpe_encode(engine, images_ptr: int, stream_ptr: Optional[int] = None) -> vpe
     if rc:
         raise VpeError(rc, vpe_last_error(engine))
     return fh
+
+
+def vpe_preprocess_u8(frames_ptr: int, batch: int, src_h: int, src_w: int, images_ptr: int, dst_h: int, dst_w: int,
+                      mean, std, stream_ptr: Optional[int] = None) -> None:
+    m = (C.c_float * 3)(*[float(v) for v in mean])
+    s = (C.c_float * 3)(*[float(v) for v in std])
+    rc = lib().vpe_preprocess_u8(frames_ptr, batch, src_h, src_w, images_ptr, dst_h, dst_w, m, s, stream_ptr)
+    if rc:
+        raise VpeError(rc, vpe_last_error(None))
+
+
+def preprocess_u8(frames, out, mean, std, stream=None) -> None:
+    """frames: torch uint8 CUDA tensor [B, Hs, Ws, 3]; out: torch float32 CUDA tensor [B, 3, H, W] (written).
+    stream: a torch stream, a raw hipStream_t as int (e.g. Engine.next_encode_stream()), or None."""
+    assert frames.is_cuda and frames.is_contiguous() and frames.element_size() == 1 and frames.dim() == 4 and frames.shape[3] == 3
+    assert out.is_cuda and out.is_contiguous() and out.dtype.is_floating_point and out.element_size() == 4
+    assert out.dim() == 4 and out.shape[0] == frames.shape[0] and out.shape[1] == 3
+    vpe_preprocess_u8(frames.data_ptr(), frames.shape[0], frames.shape[1], frames.shape[2], out.data_ptr(),
+                      out.shape[2], out.shape[3], mean, std,
+                      None if stream is None else stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+def vpe_next_encode_stream(engine) -> Optional[int]:
+    out = C.c_void_p()
+    rc = lib().vpe_next_encode_stream(engine, C.byref(out))
+    if rc:
+        raise VpeError(rc, vpe_last_error(engine))
+    return out.value
 
 
 def vpe_encode_at(engine, images_ptr: int, stream_ptr: Optional[int], t_seconds: float) -> vpe_feat:
@@ -248,6 +278,10 @@ class Engine:
 
     def run_head(self, head: int, fh: vpe_feat, stream=None) -> int:
         return vpe_run_head(self.handle, head, fh, None if stream is None else stream.cuda_stream)
+
+    def next_encode_stream(self) -> Optional[int]:
+        """Raw handle of the engine stream the next encode() without a stream argument will run on."""
+        return vpe_next_encode_stream(self.handle)
 
     def set_head_rate(self, head: int, every_n: int) -> None:
         vpe_set_head_rate(self.handle, head, every_n)

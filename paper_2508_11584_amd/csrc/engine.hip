@@ -698,6 +698,26 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     return VPE_OK;
 }
 
+int vpe_preprocess_u8(const uint8_t* frames, int batch, int src_h, int src_w, float* images, int dst_h, int dst_w,
+                      const float mean[3], const float std[3], void* stream) {
+    if (!frames || !images || !mean || !std) { g_create_error = "null pointer"; return VPE_EINVAL; }
+    if (batch < 1 || src_h < 1 || src_w < 1 || dst_h < 1 || dst_w < 1) { g_create_error = "sizes must be positive"; return VPE_EINVAL; }
+    // 32-bit indices inside a frame
+    if ((int64_t)src_h * src_w * 3 >= (int64_t(1) << 31) || (int64_t)dst_h * dst_w >= (int64_t(1) << 31)) { g_create_error = "frame too large"; return VPE_EINVAL; }
+    for (int c = 0; c < 3; ++c)
+        if (!(std[c] > 0.0f) || !std::isfinite(mean[c]) || !std::isfinite(std[c])) { g_create_error = "std must be positive and finite, mean finite"; return VPE_EINVAL; }
+    const hipError_t rc = launch_preprocess_u8(frames, batch, src_h, src_w, dst_h, dst_w, mean, std, images, (hipStream_t)stream);
+    if (rc != hipSuccess) { g_create_error = std::string("preprocess launch: ") + hipGetErrorString(rc); return VPE_EHIP; }
+    return VPE_OK;
+}
+
+int vpe_next_encode_stream(vpe_engine* e, void** stream) {
+    if (!e) return VPE_EINVAL;
+    if (!stream) return e->fail(VPE_EINVAL, "stream is null");
+    *stream = e->host_only ? nullptr : (void*)e->lane[e->frames % e->lanes].stream;
+    return VPE_OK;
+}
+
 int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out) {
     return vpe_encode_at(e, images, stream, std::nan(""), out);
 }

@@ -32,4 +32,7 @@ hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw
 hipError_t launch_depth_output(const float* d, int nparts, float bias, int B, int h8, int w8,
                                int H, int W, float* depth, hipStream_t s);
 
+hipError_t launch_preprocess_u8(const uint8_t* src, int B, int sh, int sw, int H, int W, const float* mean,
+                                const float* stdev, float* dst, hipStream_t s);
+
 }  // namespace vpe

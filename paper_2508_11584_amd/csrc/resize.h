@@ -10,13 +10,29 @@ namespace vpe {
 struct Tap { int i0, i1; float w1; };
 
 __device__ __forceinline__ Tap bilinear_tap(int y, int in, int out) {
-    // (2 y + 1) * in is exact in integers; one division, one subtraction
-    float s = (float)((2 * y + 1) * in) / (float)(2 * out) - 0.5f;
-    s = fminf(fmaxf(s, 0.0f), (float)(in - 1));
+    // s = ((2 y + 1) in - out) / (2 out), in exact integers: the tap index is an integer quotient and the
+    // weight a single rounded ratio (a float s would carry an absolute error that grows with the image size)
+    const int n = (2 * y + 1) * in - out, d = 2 * out;
     Tap t;
-    t.i0 = (int)s;
+    if (n <= 0) {                       // s <= 0: clamped to the first sample
+        t.i0 = 0;
+        t.w1 = 0.0f;
+    } else {
+        // quotient by a float reciprocal, made exact by one correction step (|estimate - n / d| < 1 for the
+        // image sizes that fit the 32-bit numerator)
+        const float rd = 1.0f / (float)d;
+        int q = (int)((float)n * rd);
+        int rem = n - q * d;
+        if (rem < 0) { --q; rem += d; }
+        else if (rem >= d) { ++q; rem -= d; }
+        t.i0 = q;
+        t.w1 = (float)rem * rd;
+        if (t.i0 >= in - 1) {           // s >= in - 1: clamped to the last sample
+            t.i0 = in - 1;
+            t.w1 = 0.0f;
+        }
+    }
     t.i1 = t.i0 + 1 < in ? t.i0 + 1 : in - 1;
-    t.w1 = s - (float)t.i0;
     return t;
 }
 
@@ -201,6 +217,34 @@ __global__ __launch_bounds__(256) void depth_output_kernel(const float* __restri
     const float top = (1.0f - tx.w1) * up2(ty.i0, tx.i0) + tx.w1 * up2(ty.i0, tx.i1);
     const float bot = (1.0f - tx.w1) * up2(ty.i1, tx.i0) + tx.w1 * up2(ty.i1, tx.i1);
     depth[idx] = fmaxf((1.0f - ty.w1) * top + ty.w1 * bot, 0.0f);
+}
+
+// Camera-frame transform (paper, Sec. "Transforms": type conversion, resizing and normalisation in front of
+// the foundation model): src uint8 [B][sh][sw][3] interleaved RGB -> dst fp32 [B][3][H][W] with
+//   dst[c] = (bilinear(src[..., c] / 255 : sh x sw -> H x W) - mean[c]) / std[c],
+// half-pixel centres, no antialiasing filter.  scale[c] = 1 / (255 std[c]), shift[c] = -mean[c] / std[c].
+// One thread per output pixel; the three channel planes are written with unit stride along x.
+struct Affine3 { float scale[3], shift[3]; };
+
+__global__ __launch_bounds__(256) void preprocess_u8_kernel(const uint8_t* __restrict__ src, int B, int sh, int sw,
+                                                            int H, int W, Affine3 a, float* __restrict__ dst) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)B * H * W) return;
+    const int x = (int)(idx % W);
+    const int y = (int)((idx / W) % H), b = (int)(idx / ((int64_t)W * H));
+    const Tap ty = bilinear_tap(y, sh, H), tx = bilinear_tap(x, sw, W);
+    const uint8_t* base = src + (int64_t)b * sh * sw * 3;
+    const uint8_t* p00 = base + ((int64_t)ty.i0 * sw + tx.i0) * 3;
+    const uint8_t* p01 = base + ((int64_t)ty.i0 * sw + tx.i1) * 3;
+    const uint8_t* p10 = base + ((int64_t)ty.i1 * sw + tx.i0) * 3;
+    const uint8_t* p11 = base + ((int64_t)ty.i1 * sw + tx.i1) * 3;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const float top = (1.0f - tx.w1) * (float)p00[c] + tx.w1 * (float)p01[c];
+        const float bot = (1.0f - tx.w1) * (float)p10[c] + tx.w1 * (float)p11[c];
+        const float v = (1.0f - ty.w1) * top + ty.w1 * bot;
+        dst[(((int64_t)b * 3 + c) * H + y) * W + x] = v * a.scale[c] + a.shift[c];
+    }
 }
 
 }  // namespace vpe

@@ -80,4 +80,15 @@ hipError_t launch_depth_output(const float* d, int nparts, float bias, int B, in
     return hipGetLastError();
 }
 
+hipError_t launch_preprocess_u8(const uint8_t* src, int B, int sh, int sw, int H, int W, const float* mean,
+                                const float* stdev, float* dst, hipStream_t s) {
+    Affine3 a;
+    for (int c = 0; c < 3; ++c) {
+        a.scale[c] = 1.0f / (255.0f * stdev[c]);
+        a.shift[c] = -mean[c] / stdev[c];
+    }
+    hipLaunchKernelGGL(preprocess_u8_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, src, B, sh, sw, H, W, a, dst);
+    return hipGetLastError();
+}
+
 }  // namespace vpe

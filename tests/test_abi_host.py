@@ -253,3 +253,18 @@ def test_create_without_a_device_fails_loudly():
     with pytest.raises(vpe.VpeError) as ei:
         make_engine(vi.small_spec(), 1, kinds=("seg",), torch_workspace=False)
     assert ei.value.code in (vpe.VPE_ENOMEM, vpe.VPE_EHIP)
+
+
+def test_next_encode_stream_is_null_without_a_device():
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg",), flags=vpe.VPE_FLAG_HOST_ONLY)
+    assert eng.next_encode_stream() is None
+
+
+def test_preprocess_rejects_bad_arguments_before_touching_the_device():
+    ok = dict(frames_ptr=4096, batch=1, src_h=8, src_w=8, images_ptr=8192, dst_h=4, dst_w=4, mean=(0, 0, 0), std=(1, 1, 1))
+    for over, needle in [(dict(frames_ptr=None), "null"), (dict(images_ptr=None), "null"), (dict(batch=0), "positive"),
+                         (dict(src_w=0), "positive"), (dict(dst_h=-3), "positive"), (dict(std=(1, 0, 1)), "std"),
+                         (dict(std=(1, 1, float("nan"))), "std"), (dict(mean=(float("inf"), 0, 0)), "mean"),
+                         (dict(src_h=40000, src_w=40000), "too large")]:
+        with pytest.raises(vpe.VpeError, match=needle):
+            vpe.vpe_preprocess_u8(**{**ok, **over})

@@ -146,3 +146,42 @@ def test_large_tile_direct_to_lds_gemm_variant(tile, monkeypatch):
     spec = vi.ModelSpec("swiglu_tile" + tile, dtype="bf16", **{**MEDIUM, "mlp_kind": vi.MLP_SWIGLU, "registers": 4,
                                                                 "batch": 3, "img_h": 70, "img_w": 98})
     check_all(spec, 103, 203)
+
+
+# ---------------------------------------------------------------- camera-frame transform
+@pytest.mark.parametrize("src,dst,batch", [((1080, 1920), (476, 630), 1),      # the paper's camera frames -> cfg 2
+                                           ((1080, 1920), (518, 518), 2),      # -> cfgs 3-5, two views
+                                           ((37, 53), (98, 154), 1),           # enlargement, odd sizes
+                                           ((224, 224), (224, 224), 1),        # same size: conversion only
+                                           ((1, 1), (14, 14), 1),              # degenerate source
+                                           ((300, 7), (14, 700), 3)])          # ragged: shrink one axis, stretch the other
+def test_preprocess_u8_matches_the_oracle(src, dst, batch):
+    frames = np.stack([vi.make_camera_frame(src[0], src[1], 40 + b) for b in range(batch)])
+    dev = torch.from_numpy(frames).cuda()
+    out = torch.full((batch, 3, dst[0], dst[1]), float("nan"), dtype=torch.float32, device="cuda")
+    vpe.preprocess_u8(dev, out, vi.CAMERA_MEAN, vi.CAMERA_STD)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for b in range(batch):
+        ref = model.preprocess_u8(frames[b], dst[0], dst[1], vi.CAMERA_MEAN, vi.CAMERA_STD)
+        err = float(np.max(np.abs(got[b] - ref)) / np.max(np.abs(ref)))
+        print("preprocess", src, dst, b, err, flush=True)
+        assert err <= 2e-6                      # exact tap positions; fp32 weights, blend, one scale and one shift
+
+
+def test_preprocessed_camera_frame_runs_through_the_engine():
+    # the transform's output is a valid engine input: same features as feeding the oracle's transform
+    spec = vi.small_spec()
+    eng, w, _ = make_engine(spec, 7, kinds=("seg",))
+    frame = vi.make_camera_frame(90, 160, 77)
+    dev = torch.from_numpy(frame[None]).cuda()
+    img = torch.empty((1, 3, spec.img_h, spec.img_w), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()                   # the frame upload; from here on the engine's own stream orders the work
+    vpe.preprocess_u8(dev, img, vi.CAMERA_MEAN, vi.CAMERA_STD, stream=eng.next_encode_stream())
+    fh = eng.encode(img)
+    eng.sync()
+    got = eng.feat_view(fh, 3).float().cpu().numpy()[0]
+    ref_img = model.preprocess_u8(frame, spec.img_h, spec.img_w, vi.CAMERA_MEAN, vi.CAMERA_STD)
+    feats = model.encode_image(spec, w, ref_img.astype(np.float32))
+    assert relerr(got, feats[3]) <= (1e-4 if spec.dtype == "f32" else 2e-2)
+    eng.close()

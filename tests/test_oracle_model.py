@@ -289,3 +289,55 @@ def test_fp32_rounding_of_inputs_bounds_oracle_sensitivity():
     img_pert = img.astype(np.float64) * (1.0 + 6e-8)
     f2 = model.encode_image(spec, w, img_pert)[3]
     assert relerr(f2, f) < 1e-5
+
+
+# ---------------------------------------------------------------- camera-frame transform
+def test_preprocess_equals_library_resize_and_hand_loops():
+    mean, std = vi.CAMERA_MEAN, vi.CAMERA_STD
+    frame = vi.make_camera_frame(27, 40, 5)
+    got = model.preprocess_u8(frame, 14, 28, mean, std)
+    # library: torch's bilinear resize (align_corners=False, no antialias) of the 0..1 planes, then normalisation
+    planes = T64(frame.transpose(2, 0, 1)) / 255.0
+    ref = F.interpolate(planes[None], size=(14, 28), mode="bilinear", align_corners=False, antialias=False)[0]
+    ref = (ref - T64(np.array(mean)).view(3, 1, 1)) / T64(np.array(std)).view(3, 1, 1)
+    assert relerr(got, ref.numpy()) < 1e-12
+    # hand loops on a few outputs, normalising BEFORE the resize (the two orders agree because the
+    # four blending weights sum to one)
+    Hs, Ws = frame.shape[:2]
+    for (c, y, x) in [(0, 0, 0), (1, 13, 27), (2, 7, 11), (0, 5, 26)]:
+        sy = min(max((y + 0.5) * Hs / 14 - 0.5, 0.0), Hs - 1.0)
+        sx = min(max((x + 0.5) * Ws / 28 - 0.5, 0.0), Ws - 1.0)
+        y0, x0 = int(math.floor(sy)), int(math.floor(sx))
+        y1, x1 = min(y0 + 1, Hs - 1), min(x0 + 1, Ws - 1)
+        a, b = sy - y0, sx - x0
+        nv = lambda yy, xx: (frame[yy, xx, c] / 255.0 - mean[c]) / std[c]
+        want = (1 - a) * ((1 - b) * nv(y0, x0) + b * nv(y0, x1)) + a * ((1 - b) * nv(y1, x0) + b * nv(y1, x1))
+        assert abs(got[c, y, x] - want) < 1e-12
+
+
+def test_preprocess_special_cases():
+    mean, std = (0.5, 0.25, 0.125), (0.5, 2.0, 0.25)
+    frame = vi.make_camera_frame(9, 13, 6)
+    # same size: pure type conversion and normalisation, per channel
+    same = model.preprocess_u8(frame, 9, 13, mean, std)
+    for c in range(3):
+        assert np.array_equal(same[c], (frame[:, :, c].astype(np.float64) / 255.0 - mean[c]) / std[c])
+    # a constant frame stays constant at any size; 0 and 255 map to the ends of the range
+    const = np.full((5, 7, 3), 255, dtype=np.uint8)
+    out = model.preprocess_u8(const, 11, 3, mean, std)
+    for c in range(3):
+        assert np.allclose(out[c], (1.0 - mean[c]) / std[c], rtol=0, atol=1e-15)
+    # channels do not mix and the layout is interleaved RGB: a frame that is red only
+    red = np.zeros((4, 4, 3), dtype=np.uint8)
+    red[:, :, 0] = 200
+    out = model.preprocess_u8(red, 8, 8, (0, 0, 0), (1, 1, 1))
+    assert np.allclose(out[0], 200 / 255.0) and np.all(out[1] == 0) and np.all(out[2] == 0)
+    # a 1 x 1 source fills the output
+    one = np.array([[[10, 20, 30]]], dtype=np.uint8)
+    out = model.preprocess_u8(one, 3, 2, (0, 0, 0), (1, 1, 1))
+    assert np.allclose(out[:, 0, 0], np.array([10, 20, 30]) / 255.0) and np.allclose(out, out[:, :1, :1])
+    # downscaling by an integer factor 2 samples exactly midway between two pixels: the 2 x 2 mean
+    f = vi.make_camera_frame(8, 12, 7)
+    out = model.preprocess_u8(f, 4, 6, (0, 0, 0), (1, 1, 1))
+    want = f.astype(np.float64).reshape(4, 2, 6, 2, 3).mean(axis=(1, 3)).transpose(2, 0, 1) / 255.0
+    assert np.allclose(out, want, rtol=0, atol=1e-15)

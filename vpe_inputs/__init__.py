@@ -302,6 +302,21 @@ def make_image(h: int, w: int, seed: int) -> np.ndarray:
     return _finish(make_field(h, w, rng).evaluate(), rng)
 
 
+# the usual ImageNet statistics, as used in front of DINOv2-style backbones (data, not arithmetic)
+CAMERA_MEAN = (0.485, 0.456, 0.406)
+CAMERA_STD = (0.229, 0.224, 0.225)
+
+
+def make_camera_frame(h: int, w: int, seed: int) -> np.ndarray:
+    """One raw camera frame [h, w, 3] uint8 (interleaved RGB): the same smooth field + sensor noise as
+    make_image, mapped to 0..255 with some clipping at both ends, as real frames have."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    clean = make_field(h, w, rng).evaluate()
+    img = clean + rng.normal(0.0, 0.05, clean.shape)
+    img = 128.0 + 48.0 * img                       # field amplitude is a few units: reaches past 0 and 255
+    return np.ascontiguousarray(np.clip(np.rint(img), 0, 255).astype(np.uint8).transpose(1, 2, 0))
+
+
 def make_batch(spec: ModelSpec, seed: int) -> np.ndarray:
     """[B, 3, H, W] fp32; batch element b (a camera view) uses seed + b."""
     return np.stack([make_image(spec.img_h, spec.img_w, seed + b) for b in range(spec.batch)])
