@@ -13,6 +13,8 @@
 //
 // Same operands, A modes and epilogues as gemm_kernel (see gemm.h); bf16 only.
 #pragma once
+#include <type_traits>
+
 #include "gemm.h"
 
 namespace vpe {
@@ -29,11 +31,12 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // OCC workgroups per CU (the launch bound is given in waves per SIMD: OCC * waves / 4).
 // WGM x 2 waves: WGM = 2 gives 128-row wave tiles (256 accumulator registers, one wave per SIMD),
 // WGM = 4 gives 64-row wave tiles and two waves per SIMD, i.e. twice as many waves issuing loads.
-template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE>
+template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE, int BM_ = 256>
 __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_kernel(const GemmArgs args) {
     const GemmArgs p = select_problem(args);
     typedef bf16 T;
-    constexpr int BM = 256, CE = 8, NW = WGN * WGM;
+    constexpr int BM = BM_, CE = 8, NW = WGN * WGM;
+    static_assert((BM * BK * 2) % (1024 * NW) == 0 && (BN * BK * 2) % (1024 * NW) == 0 && BM % (32 * WGM) == 0, "loader / wave tiling");
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     constexpr int ROWB = BK * 2, CPR = BK / 8, RPI = 64 / CPR;   // row bytes, chunks per row, rows per DMA instruction
     constexpr int KS = BK / 16;
@@ -131,43 +134,66 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
     // same for all of them: one lane offset per k-step, rows by immediates.
     const int arow0 = wm * WM + li, brow0 = wn * WN + li;
     const int asw = (arow0 >> SW_SHIFT) & SW_MASK, bsw = (brow0 >> SW_SHIFT) & SW_MASK;
+    // Wave tiles of up to 6 fragments per k-step keep two fragment sets (the reads of step ks + 1 are in
+    // flight during the MFMAs of step ks); larger wave tiles have no registers for the second set and read
+    // each step's fragments just before its MFMAs (two waves per SIMD cover for each other).
+    constexpr bool FRAG_DB = MI + NI <= 6;
     auto compute = [&](int stage) {
         const char* sA = smem + stage * STAGE + arow0 * ROWB;
         const char* sB = smem + stage * STAGE + A_BYTES + brow0 * ROWB;
-        bf16x8 fa[2][MI], fb[2][NI];
+        if constexpr (FRAG_DB) {
+            bf16x8 fa[2][MI], fb[2][NI];
 #pragma unroll
-        for (int i = 0; i < MI; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ((g ^ asw) * 16));
+            for (int i = 0; i < MI; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ((g ^ asw) * 16));
 #pragma unroll
-        for (int j = 0; j < NI; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + ((g ^ bsw) * 16));
+            for (int j = 0; j < NI; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + ((g ^ bsw) * 16));
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) {
-                const int ca = ((2 * (ks + 1) + g) ^ asw) * 16, cb = ((2 * (ks + 1) + g) ^ bsw) * 16;
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) {
+                    const int ca = ((2 * (ks + 1) + g) ^ asw) * 16, cb = ((2 * (ks + 1) + g) ^ bsw) * 16;
 #pragma unroll
-                for (int i = 0; i < MI; ++i) fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ca);
+                    for (int i = 0; i < MI; ++i) fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ca);
 #pragma unroll
-                for (int j = 0; j < NI; ++j) fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + cb);
-            }
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-            // Issue order for the scheduler: the LDS reads of step ks + 1 are spread between the MFMAs
-            // of step ks (one read per two MFMAs), so the only wave on this SIMD never waits on LDS
-            // with an empty matrix pipe.  0x100 = DS read, 0x008 = MFMA.
-            if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
-            if (ks + 1 < KS) {
-                constexpr int PER = (MI * NI) / (MI + NI) > 0 ? (MI * NI) / (MI + NI) : 1;
-                constexpr int GROUPS = (MI * NI) / PER < MI + NI ? (MI * NI) / PER : MI + NI;
-#pragma unroll
-                for (int n = 0; n < GROUPS; ++n) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int j = 0; j < NI; ++j) fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + cb);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x100, MI + NI - GROUPS, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - GROUPS * PER, 0);
-            } else {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                // Issue order for the scheduler: the LDS reads of step ks + 1 are spread between the MFMAs
+                // of step ks (one read per two MFMAs), so the only wave on this SIMD never waits on LDS
+                // with an empty matrix pipe.  0x100 = DS read, 0x008 = MFMA.
+                if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
+                if (ks + 1 < KS) {
+                    constexpr int PER = (MI * NI) / (MI + NI) > 0 ? (MI * NI) / (MI + NI) : 1;
+                    constexpr int GROUPS = (MI * NI) / PER < MI + NI ? (MI * NI) / PER : MI + NI;
+#pragma unroll
+                    for (int n = 0; n < GROUPS; ++n) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x100, MI + NI - GROUPS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - GROUPS * PER, 0);
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int ca = ((2 * ks + g) ^ asw) * 16, cb = ((2 * ks + g) ^ bsw) * 16;
+                bf16x8 fa[MI], fb[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * ROWB + ca);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * ROWB + cb);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
             }
         }
@@ -198,8 +224,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
     // block of LDS (the stage buffers are free now) and leaves with 8-column chunks per lane.
     float* sC = reinterpret_cast<float*>(smem) + wave * (32 * WN);
     const int wrow0 = m0 + wm * WM, wcol0 = n0 + wn * WN;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    // one pass per 32-row block of the wave tile; the block index is a compile-time constant of each pass (a
+    // loop that the optimizer declines to unroll would turn the accumulators into an indexed array in scratch)
+    auto pass = [&](auto I) {
+        constexpr int i = decltype(I)::value;
         if (p.ln_stats) {
             // (column sums are loaded here, not before the k loop: this kernel has no registers to spare)
             float lncs[NI];
@@ -263,11 +291,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                 }
             }
         } else if ((p.epi == EPI_RESID || p.epi == EPI_PATCH) && (p.st_out || p.xb_out)) {
-            // a wave's 64 columns are one statistics group: 8 consecutive lanes hold a row's 8 chunks
-            if constexpr (WN == 64) {
+            // 8 consecutive lanes hold the 8 chunks of one 64-column statistics group of a row
+            if constexpr (WN % 64 == 0) {
+                constexpr int CG = WN / 8;
 #pragma unroll
-                for (int it = lane; it < 32 * 8; it += 64) {
-                    const int rr = it >> 3, cg = it & 7;
+                for (int it = lane; it < 32 * CG; it += 64) {
+                    const int rr = it / CG, cg = it % CG;
                     const int r = rblk + rr, c = wcol0 + cg * 8;
                     const bool active = r < p.M && c < p.N;
                     float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -277,16 +306,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                         v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
                         v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
                     }
-                    resid_stats_chunk<T>(p, r, c, v, active, cg);
+                    resid_stats_chunk<T>(p, r, c, v, active, cg & 7);
                 }
             }
         } else if (p.epi == EPI_ROWDOT) {
-            // a wave's 64 columns are one projection group: 8 consecutive lanes hold a row's 8 chunks
-            if constexpr (WN == 64) {
+            // 8 consecutive lanes hold the 8 chunks of one 64-column projection group of a row
+            if constexpr (WN % 64 == 0) {
+                constexpr int CG = WN / 8;
                 float* out = reinterpret_cast<float*>(p.out);
 #pragma unroll
-                for (int it = lane; it < 32 * 8; it += 64) {
-                    const int rr = it >> 3, cg = it & 7;
+                for (int it = lane; it < 32 * CG; it += 64) {
+                    const int rr = it / CG, cg = it % CG;
                     const int r = rblk + rr, c = wcol0 + cg * 8;
                     float sum = 0.0f;
                     if (r < p.M && c < p.N) {
@@ -298,7 +328,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                     sum += __shfl_xor(sum, 1);
                     sum += __shfl_xor(sum, 2);
                     sum += __shfl_xor(sum, 4);
-                    if (cg == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
+                    if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
                 }
             }
         } else {
@@ -314,28 +344,33 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                 }
             }
         }
-    }
+    };
+    pass(std::integral_constant<int, 0>{});
+    if constexpr (MI > 1) pass(std::integral_constant<int, 1>{});
+    if constexpr (MI > 2) pass(std::integral_constant<int, 2>{});
+    if constexpr (MI > 3) pass(std::integral_constant<int, 3>{});
+    static_assert(MI <= 4, "passes are written out up to four row blocks");
 }
 
-template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1>
+template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1, int BM = 256>
 static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
-    constexpr int stage_b = S * (256 + BN) * BK * 2, epi_b = WGM * WGN * 32 * (BN / WGN) * 4;
-    constexpr int lds = (stage_b > epi_b ? stage_b : epi_b) + 256 * 8;     // + (mean, rstd) of the tile's 256 rows
+    constexpr int stage_b = S * (BM + BN) * BK * 2, epi_b = WGM * WGN * 32 * (BN / WGN) * 4;
+    constexpr int lds = (stage_b > epi_b ? stage_b : epi_b) + BM * 8;     // + (mean, rstd) of the tile's rows
     static_assert(lds * OCC <= 160 * 1024, "LDS budget of one CU");
     static bool configured = false;
     if (!configured) {
-        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN>),
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc == hipSuccess)
-            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3>),
+            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc != hipSuccess) return rc;
         configured = true;
     }
     if (configure_only) return hipSuccess;
-    const int tiles = cdiv(a.M, 256) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
-    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
-    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
+    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
+    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
+    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
     return hipGetLastError();
 }
 

@@ -137,10 +137,11 @@ def test_cfg2_vits_bf16_476x630_three_heads():
     check_all(spec, *vi.SEEDS["cfg2"], flags=vpe.VPE_FLAG_GRAPHS)
 
 
-@pytest.mark.parametrize("tile", ["256", "128"])
+@pytest.mark.parametrize("tile", ["384", "256", "128"])
 def test_large_tile_direct_to_lds_gemm_variant(tile, monkeypatch):
-    # the opt-in 256-row GEMM (global -> LDS loads) through every epilogue: QKV + transposed values,
-    # LayerScale residual, GELU and SwiGLU, patch embedding, 1x1 and 3x3 convolutions
+    # each direct-to-LDS GEMM shape (384 x 256, 256 x 256, 256 x 128 tiles), forced for every GEMM of the model,
+    # through every epilogue: folded LayerNorm + QKV with transposed values, LayerScale residual with row
+    # statistics, GELU and SwiGLU, patch embedding, 1x1 and 3x3 convolutions, the fused 1-channel projection
     monkeypatch.setenv("VPE_GEMM_TILE", tile)
     check_all(vi.ModelSpec("medium_bf16_tile" + tile, dtype="bf16", **MEDIUM), 102, 202)
     spec = vi.ModelSpec("swiglu_tile" + tile, dtype="bf16", **{**MEDIUM, "mlp_kind": vi.MLP_SWIGLU, "registers": 4,
