@@ -19,7 +19,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
 # calibrated against a 1 GiB copy (profiles/conv3x3_cfg2_hbm_traffic.txt); only the workload measured has one.
-TRAFFIC_BYTES = {"vits14_bf16_476x630": 72.2e6}
+TRAFFIC_BYTES = {"vits14_bf16_476x630": 64.3e6}
 
 
 def backbone_flops(spec) -> float:
