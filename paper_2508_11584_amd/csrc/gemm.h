@@ -228,6 +228,39 @@ __device__ __forceinline__ float rowdot_chunk(const GemmArgs& p, int c, const fl
     return s;
 }
 
+// QKV epilogue, value columns: tokens r .. r + 7 (r a multiple of 8) of value column c2 go to the transposed
+// buffer vt[(image * dim + c2)][token in image].  With several images whose token count is not a multiple of
+// 8 the group starts at an odd offset inside its image: still one run of 8 when it does not cross into the
+// next image, written with the widest stores its alignment allows; only a group that straddles two images
+// (or the end of the matrix) goes element by element.
+template <typename T>
+__device__ __forceinline__ void store_tokens8(const GemmArgs& p, T* vt, int r, int c2, const float* v) {
+    const int b = r / p.ntok, n = r - b * p.ntok;
+    T* dst = vt + ((int64_t)b * p.dim + c2) * p.npad + n;
+    if (n + 8 <= p.ntok && r + 8 <= p.M) {
+        if ((n & 7) == 0) {
+            store8(dst, v);
+        } else if (sizeof(T) == 2 && (n & 1) == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; k += 2) {
+                const T lo = from_f32<T>(v[k]), hi = from_f32<T>(v[k + 1]);
+                uint32_t w;
+                w = (uint32_t)(*reinterpret_cast<const uint16_t*>(&lo)) | ((uint32_t)(*reinterpret_cast<const uint16_t*>(&hi)) << 16);
+                *reinterpret_cast<uint32_t*>(dst + k) = w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dst[k] = from_f32<T>(v[k]);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int rk = r + k;
+            if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
+        }
+    }
+}
+
 // (mean, rstd) of row r from its group statistics (sum, sum of squares of each 64-column group): all loads are
 // independent 16-byte loads of two groups each (ln_groups is even or 1 group is handled last).
 __device__ __forceinline__ void ln_row_stats(const GemmArgs& p, int r, float& mean, float& rstd) {
@@ -347,16 +380,7 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[
             float v[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * BN + cc] + bias;
-            const int b = r / p.ntok, n = r % p.ntok;
-            if (n + 8 <= p.ntok && (n & 7) == 0) {
-                store8(vt + ((int64_t)b * p.dim + c2) * p.npad + n, v);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int rk = r + k;
-                    if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
-                }
-            }
+            store_tokens8<T>(p, vt, r, c2, v);
         }
         return;
     }

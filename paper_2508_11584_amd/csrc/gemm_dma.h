@@ -278,16 +278,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                     float v[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * WN + cc] + bias;
-                    const int b = r / p.ntok, n = r % p.ntok;
-                    if (n + 8 <= p.ntok && (n & 7) == 0) {
-                        store8(vt + ((int64_t)b * p.dim + c2) * p.npad + n, v);
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < 8; ++k) {
-                            const int rk = r + k;
-                            if (rk < p.M) vt[((int64_t)(rk / p.ntok) * p.dim + c2) * p.npad + rk % p.ntok] = from_f32<T>(v[k]);
-                        }
-                    }
+                    store_tokens8<T>(p, vt, r, c2, v);
                 }
             }
         } else if ((p.epi == EPI_RESID || p.epi == EPI_PATCH) && (p.st_out || p.xb_out)) {
