@@ -183,6 +183,41 @@ __global__ __launch_bounds__(256) void seg_upsample_argmax_kernel(const float* _
     cls[idx] = (uint8_t)best;
 }
 
+// The same output for an enlargement by an even integer factor S (S * S <= 256), the case of the 14 x 14
+// patches: all output pixels y in [S k - S/2, S k + S/2) blend the same two source rows k - 1 and k (clamped;
+// likewise along x), so one workgroup takes one such S x S cell, puts the four source logit vectors in LDS once
+// and every thread (one output pixel) walks the classes reading them by broadcast -- 4 LDS reads per class
+// instead of 4 global loads.  Weights come from bilinear_tap as before (at the image border it returns weight 0
+// for the clamped side, so the duplicated row / column does not matter); arithmetic and tie rule are unchanged.
+__global__ __launch_bounds__(256) void seg_upsample_argmax_cell_kernel(const float* __restrict__ logits, int B,
+                                                                       int gh, int gw, int C, int S,
+                                                                       uint8_t* __restrict__ cls) {
+    extern __shared__ float sv[];                 // [4][C]: (r0, c0), (r0, c1), (r1, c0), (r1, c1)
+    const int H = gh * S, W = gw * S;
+    const int cj = blockIdx.x % (gw + 1), ci = (blockIdx.x / (gw + 1)) % (gh + 1), b = blockIdx.x / ((gw + 1) * (gh + 1));
+    const int r0 = ci > 0 ? ci - 1 : 0, r1 = ci < gh ? ci : gh - 1;
+    const int c0 = cj > 0 ? cj - 1 : 0, c1 = cj < gw ? cj : gw - 1;
+    const float* base = logits + (int64_t)b * gh * gw * C;
+    for (int i = threadIdx.x; i < 4 * C; i += 256) {
+        const int q = i / C, c = i - q * C;
+        sv[i] = base[((int64_t)(q < 2 ? r0 : r1) * gw + ((q & 1) ? c1 : c0)) * C + c];
+    }
+    __syncthreads();
+    const int ly = threadIdx.x / S, lx = threadIdx.x - ly * S;
+    const int y = ci * S - S / 2 + ly, x = cj * S - S / 2 + lx;
+    if (ly >= S || y < 0 || y >= H || x < 0 || x >= W) return;
+    const Tap ty = bilinear_tap(y, gh, H), tx = bilinear_tap(x, gw, W);
+    int best = 0;
+    float bv = -INFINITY;
+    for (int c = 0; c < C; ++c) {
+        const float top = (1.0f - tx.w1) * sv[c] + tx.w1 * sv[C + c];
+        const float bot = (1.0f - tx.w1) * sv[2 * C + c] + tx.w1 * sv[3 * C + c];
+        const float v = (1.0f - ty.w1) * top + ty.w1 * bot;
+        if (v > bv) { bv = v; best = c; }
+    }
+    cls[((int64_t)b * H + y) * W + x] = (uint8_t)best;
+}
+
 // Depth output: depth = ReLU(bilinear(bilinear_x2(d) -> H x W)) with d fp32 [B][h8][w8] given as
 // d = bias + the sum of the `nparts` partial values stored per pixel (the convolution before it leaves the
 // 1-channel projection as one partial sum per 64 channels; summed here in index order, so the result does

@@ -68,7 +68,13 @@ hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const 
 
 hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw, int C, int H, int W,
                                       uint8_t* cls, hipStream_t s) {
-    hipLaunchKernelGGL(seg_upsample_argmax_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, logits, B, gh, gw, C, H, W, cls);
+    const int S = H / gh;
+    if (H == S * gh && W == S * gw && S >= 2 && S % 2 == 0 && S * S <= 256 && C <= 2048) {
+        const unsigned cells = (unsigned)(B * (gh + 1) * (gw + 1));
+        hipLaunchKernelGGL(seg_upsample_argmax_cell_kernel, dim3(cells), dim3(256), 4 * C * sizeof(float), s, logits, B, gh, gw, C, S, cls);
+    } else {
+        hipLaunchKernelGGL(seg_upsample_argmax_kernel, dim3(blocks_for((int64_t)B * H * W, 256)), dim3(256), 0, s, logits, B, gh, gw, C, H, W, cls);
+    }
     return hipGetLastError();
 }
 
