@@ -101,7 +101,7 @@ struct vpe_engine {
     // kernels are too small to fill 256 CUs on their own); results per frame are unchanged.
     struct Lane {
         // x: fp32 residual stream; u: its copy in the engine dtype (the A operand of the LayerNorm-folded
-        // GEMMs; unused by fp32 engines, which read x); stats: per row and 64-column group (sum, sum of squares) of x
+        // GEMMs; unused by fp32 engines, which read x); stats: per row and 64-column group (mean, sum of squared deviations) of x
         void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
         float *x = nullptr, *stats = nullptr;
         hipStream_t stream = nullptr;

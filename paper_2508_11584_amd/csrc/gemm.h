@@ -41,8 +41,8 @@ struct GemmArgs {
     // LayerNorm folded into this GEMM (consumer side): A holds the UN-normalised rows (plain row map), W has
     // been scaled by the LayerNorm gain along k and bias holds b + beta W; the accumulator of (row r, column c)
     // becomes rstd_r * (acc - mean_r * ln_colsum[c]) before bias / activation, with ln_colsum[c] = sum_k W[c][k].
-    // ln_stats [M][ln_groups][2]: (sum, sum of squares) of every 64-column group of row r, as written by the
-    // producer below (fp32; the variance is E[x^2] - mean^2, adequate while |mean| is not >> the deviation).
+    // ln_stats [M][ln_groups][2]: (mean, sum of squared deviations from it) of every 64-column group of row r,
+    // as written by the producer below; both sides work with differences, never with raw squares.
     const float* ln_stats;     // null: no LayerNorm
     const float* ln_colsum;
     int ln_groups;             // = K / 64
@@ -261,23 +261,32 @@ __device__ __forceinline__ void store_tokens8(const GemmArgs& p, T* vt, int r, i
     }
 }
 
-// (mean, rstd) of row r from its group statistics (sum, sum of squares of each 64-column group): all loads are
-// independent 16-byte loads of two groups each (ln_groups is even or 1 group is handled last).
+// (mean, rstd) of row r from its group statistics (mean_g, M2_g = sum of squared deviations from mean_g, of
+// each 64-column group).  Groups are merged around the first group's mean, so a level common to the whole row
+// cancels before anything is squared:
+//   mean = m_0 + avg_g (m_g - m_0),   M2 = sum_g M2_g + 64 (sum_g (m_g - m_0)^2 - G (mean - m_0)^2).
+// All loads are independent 16-byte loads of two groups each.
 __device__ __forceinline__ void ln_row_stats(const GemmArgs& p, int r, float& mean, float& rstd) {
     const float* st = p.ln_stats + (int64_t)r * p.ln_groups * 2;
-    float s = 0.0f, q = 0.0f;
+    const float m0 = st[0];
+    float sd = 0.0f, sdd = 0.0f, sm2 = 0.0f;
     int g = 0;
 #pragma unroll 4
     for (; g + 2 <= p.ln_groups; g += 2) {
         const f32x4 v = *reinterpret_cast<const f32x4*>(st + 2 * g);
-        s += v[0] + v[2];
-        q += v[1] + v[3];
+        const float d0 = v[0] - m0, d1 = v[2] - m0;
+        sd += d0 + d1;
+        sdd += d0 * d0 + d1 * d1;
+        sm2 += v[1] + v[3];
     }
-    if (g < p.ln_groups) { s += st[2 * g]; q += st[2 * g + 1]; }
-    const float n = 64.0f * (float)p.ln_groups;
-    mean = s / n;
-    const float var = fmaxf(q / n - mean * mean, 0.0f);
-    rstd = 1.0f / sqrtf(var + p.ln_eps);
+    if (g < p.ln_groups) {
+        const float d = st[2 * g] - m0;
+        sd += d; sdd += d * d; sm2 += st[2 * g + 1];
+    }
+    const float G = (float)p.ln_groups, dm = sd / G;
+    mean = m0 + dm;
+    const float m2 = sm2 + 64.0f * fmaxf(sdd - G * dm * dm, 0.0f);
+    rstd = 1.0f / sqrtf(m2 / (64.0f * G) + p.ln_eps);
 }
 
 // RESID / PATCH chunk with the producer-side extras.  Called by all 8 lanes that hold the 8 chunks of one
@@ -294,16 +303,24 @@ __device__ __forceinline__ void resid_stats_chunk(const GemmArgs& p, int r, int 
         for (int i = 0; i < 8; ++i) v[i] = 0.0f;
     }
     if (!p.st_out) return;
-    float sum = 0.0f, sq = 0.0f;
+    // group statistics around the group's first element (broadcast from the group's first lane), so that the
+    // level of the data cancels before squaring: mean_g = v0 + s1 / 64, M2_g = s2 - s1^2 / 64
+    const float v0 = __shfl(v[0], (int)(__lane_id() & ~7u));
+    float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { sum += v[i]; sq += v[i] * v[i]; }
+    for (int i = 0; i < 8; ++i) {
+        const float d = v[i] - v0;
+        s1 += d;
+        s2 += d * d;
+    }
 #pragma unroll
     for (int o = 1; o < 8; o <<= 1) {
-        sum += __shfl_xor(sum, o);
-        sq += __shfl_xor(sq, o);
+        s1 += __shfl_xor(s1, o);
+        s2 += __shfl_xor(s2, o);
     }
     if (active && lane8 == 0)
-        *reinterpret_cast<f32x2*>(p.st_out + (orow * (p.N >> 6) + (c >> 6)) * 2) = f32x2{sum, sq};
+        *reinterpret_cast<f32x2*>(p.st_out + (orow * (p.N >> 6) + (c >> 6)) * 2) =
+            f32x2{v0 + s1 * (1.0f / 64.0f), fmaxf(s2 - s1 * s1 * (1.0f / 64.0f), 0.0f)};
 }
 
 // Block-level epilogue shared by the register-staged kernels.  The accumulators go through LDS

@@ -58,8 +58,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 // Patch gathering for the 14x14 stride-14 embedding: row (b, p) of `cols` receives the 588
 // pixels of patch p in (channel, row, column) order, zero-padded to kpad columns.  The same
 // launch also fills the non-patch rows of the residual stream (CLS + pos[0], then registers)
-// from the `special` table [1 + R][D], together with their copy in T (xb, may be null) and the (sum, sum
-// of squares) of each of their 64-column groups (stats [rows][D / 64][2], may be null) -- what
+// from the `special` table [1 + R][D], together with their copy in T (xb, may be null) and the (mean, sum
+// of squared deviations) of each of their 64-column groups (stats [rows][D / 64][2], may be null) -- what
 // the GEMM epilogues produce for the other rows.  blocks [0, B*P) gather; the rest write special rows.
 template <typename T>
 __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ img, int B, int H, int W,
@@ -90,10 +90,11 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ i
             const float v = special[(int64_t)r * D + d];
             x[row * D + d] = v;
             if (xb) xb[row * D + d] = from_f32<T>(v);
-            const float sum = wave_sum(v), sq = wave_sum(v * v);
+            const float mean = wave_sum(v) * (1.0f / 64.0f);
+            const float m2 = wave_sum((v - mean) * (v - mean));
             if (stats && lane == 0) {
-                stats[(row * (D / 64) + grp) * 2] = sum;
-                stats[(row * (D / 64) + grp) * 2 + 1] = sq;
+                stats[(row * (D / 64) + grp) * 2] = mean;
+                stats[(row * (D / 64) + grp) * 2 + 1] = m2;
             }
         }
     }

@@ -37,7 +37,11 @@ def regret(scores, ref_cls, got_cls):
     return float(np.max(a - b))
 
 
-def check_all(spec, seed, img_seed, kinds=("seg", "depth", "det"), flags=0, batch_check=None, lead_frames=0, **engine_kw):
+def check_all(spec, seed, img_seed, kinds=("seg", "depth", "det"), flags=0, batch_check=None, lead_frames=0,
+              weights_edit=None, **engine_kw):
+    if weights_edit is not None:               # same generator, then an in-place change both sides will see
+        engine_kw["weights"] = vi.make_backbone_weights(spec, seed)
+        weights_edit(engine_kw["weights"])
     eng, w, hw = make_engine(spec, seed, kinds=kinds, flags=flags, **engine_kw)
     images = vi.make_batch(spec, img_seed)
     # optional lead-in: other frames pushed through encode + heads with no host synchronisation, so that the
@@ -142,6 +146,20 @@ def test_cfg2_vits_bf16_476x630_three_heads():
     # benchmark configuration 2 (the headline one), whole, all three heads, as bench.py runs it
     spec = vi.CONFIGS["cfg2"]
     check_all(spec, *vi.SEEDS["cfg2"], flags=vpe.VPE_FLAG_GRAPHS)
+
+
+def test_residual_stream_with_a_large_common_offset():
+    # every token carries a level of +30 (patch bias and CLS) on top of deviations of order 1, and keeps it through
+    # all blocks: the in-GEMM LayerNorm statistics must come from differences, not from raw sums of squares
+    # (E[x^2] - mean^2 in fp32 would lose four digits here and miss the 1e-4 gate)
+    def lift(w, by):
+        w["patch_b"] += np.float32(by)
+        w["cls"] += np.float32(by)
+    check_all(vi.ModelSpec("offset30_f32", dtype="f32", **MEDIUM), 104, 204, weights_edit=lambda w: lift(w, 30.0))
+    # the bf16 engine multiplies the rounded stream itself, so a common level costs it precision in proportion
+    # (about 2^-9 |level| / deviation: with this model's deviations of ~0.35 a level of 2 lands right at the
+    # 2e-2 gate); half a unit, already larger than the deviations, still has to pass it
+    check_all(vi.ModelSpec("offset_bf16", dtype="bf16", **MEDIUM), 105, 205, weights_edit=lambda w: lift(w, 0.5))
 
 
 def test_cfg2_in_the_pipelined_configuration_the_benchmark_times():
