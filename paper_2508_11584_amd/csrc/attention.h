@@ -16,6 +16,9 @@
 
 namespace vpe {
 
+// The loader reads up to 2 * 4 * 64 key rows past the last token of qk and as many columns past the end of vt
+// (prefetch of tiles that do not exist); both buffers must be readable that far.  What is read there is never
+// used.
 struct AttnArgs {
     const void* qk;
     const void* vt;
@@ -149,21 +152,28 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
     const int NIT = (KT + KW - 1) / KW;
     const int lchunk = tid % CPR;
     u32x4 rg[CH];
-    // chunk i of this thread: linear index tid + i NT over (tile j, K|V, row, chunk)
-    auto gload = [&](int it) {
+    // chunk i of this thread: linear index tid + i NT over (tile j, K|V, row, chunk).  Its address advances by a
+    // fixed step per iteration (KW tiles), so the loader keeps one running pointer per chunk instead of
+    // recomputing tile, row and clamps each time.  Nothing is clamped: tiles past the last one and key rows past
+    // N are read from whatever follows (the next image's keys, the buffers' padding -- see AttnArgs) and never
+    // used: scores of keys >= N are overwritten with -inf, waves skip tiles >= KT.
+    // Thread part of the address (its row within a pass and its chunk) in two pointers; tile, K|V and pass of
+    // chunk i are compile-time constants, the advance per iteration is wave-uniform: scalar arithmetic only.
+    constexpr int RPP = NT / CPR;                      // rows per loader pass
+    static_assert(64 % RPP == 0, "a pass must not straddle tiles");
+    const T* kthr = kbase + (int64_t)(tid / CPR) * ld + lchunk * CE;
+    const T* vthr = vt + (int64_t)(tid / CPR) * p.npad + lchunk * CE;
+    int64_t kadv = 0, vadv = 0;
+    auto gload = [&]() {                               // loads the next iteration's tiles
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int idx = (tid + i * NT) / CPR;          // (j * 2 + which) * 64 + row
-            const int row = idx & 63, which = (idx >> 6) & 1, t = it * KW + (idx >> 7);
-            // always-valid addresses instead of branches: a key row past N re-reads row N - 1 (its
-            // scores are masked to -inf anyway) and a tile past the end re-reads the last tile (the
-            // wave that would use it skips its compute)
-            const int tc = t < KT ? t : KT - 1;
-            const int key = tc * 64 + row < p.N ? tc * 64 + row : p.N - 1;
-            const T* src = which ? vt + (int64_t)row * p.npad + tc * 64 + lchunk * CE
-                                 : kbase + (int64_t)key * ld + lchunk * CE;
+            const int r0 = (i * RPP) & 63, which = ((i * RPP) >> 6) & 1, j = (i * RPP) >> 7;
+            const T* src = which ? vthr + (int64_t)r0 * p.npad + j * 64 + vadv
+                                 : kthr + (int64_t)(j * 64 + r0) * ld + kadv;
             rg[i] = ld_global_16(src);
         }
+        kadv += (int64_t)KW * 64 * ld;
+        vadv += KW * 64;
     };
     auto sstore = [&]() {
 #pragma unroll
@@ -175,12 +185,12 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
         }
     };
 
-    gload(0);
+    gload();
     for (int it = 0; it < NIT; ++it) {
         __syncthreads();           // everyone is done reading the previous tiles
         sstore();
         __syncthreads();
-        gload(it + 1);         // unconditional (indices are clamped): keeps the in-flight load count static
+        gload();               // unconditional (reads past the end land in padding): keeps the in-flight load count static
         const int t = it * KW + kw;
         if (t >= KT) continue;     // (barriers above are reached by every wave in every iteration)
         const char* sK = smem + (kw * 2) * TILE;

@@ -263,8 +263,9 @@ void layout(vpe_engine& e, Bump& b) {
         L.x = f32(T * D);
         L.stats = f32(T * (D / 64) * 2);
         L.u = b.take(T * D * esz);
-        L.qk = b.take(T * 2 * D * esz);
-        L.vt = b.take(B * D * e.npad * esz);
+        // + 512 rows / columns that the attention loader may prefetch past the end (never used)
+        L.qk = b.take((T + 512) * 2 * D * esz);
+        L.vt = b.take((B * D * e.npad + 512) * esz);
         L.att = b.take(T * D * esz);
         L.hid = b.take(T * e.Mh * esz);
     }
