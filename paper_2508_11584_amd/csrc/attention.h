@@ -62,6 +62,20 @@ template <> struct AttnMma<bf16> {
             o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o, 0, 0, 0);
         }
     }
+    // Row sums of the probabilities on the matrix pipe: ones[32 x 16] P^T adds the 16 keys of a k-step for
+    // every query, in every row of the accumulator (lane halves included), using the same rounded
+    // probabilities as the numerator.  Four of these per tile replace 32 VALU additions per lane.
+    static constexpr bool MFMA_ROWSUM = true;
+    static __device__ __forceinline__ void rowsum(f32x16& l, const f32x16& p) {
+        const bf16x8 ones = {(bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f};
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            bf16x8 b;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) b[kk] = (bf16)p[8 * s + kk];
+            l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, b, l, 0, 0, 0);
+        }
+    }
 };
 
 template <> struct AttnMma<float> {
@@ -87,6 +101,8 @@ template <> struct AttnMma<float> {
         }
     }
     // one MFMA per score element index v: k slot g is key 8 (v / 4) + 4 g + v % 4 of the block
+    static constexpr bool MFMA_ROWSUM = false;
+    static __device__ __forceinline__ void rowsum(f32x16&, const f32x16&) {}
     static __device__ __forceinline__ void pv(f32x16& o, const char* sV, int drow, int kb, const f32x16& p, int g) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -136,12 +152,20 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
             q[qb][ks] = qi < p.N ? AttnMma<T>::load_q(qk + (int64_t)qi * ld, ks, g) : AttnMma<T>::zero_q();
     }
 
+    // denominators: on the matrix pipe where the type and the register budget allow it (complete sums, every
+    // accumulator row the same), else per lane half in l_run
+    constexpr bool LMFMA = AttnMma<T>::MFMA_ROWSUM && QB == 1;
+    f32x16 lacc[LMFMA ? QB : 1];
     f32x16 o[QB][2];
     float m_run[QB], l_run[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         m_run[qb] = -INFINITY;
         l_run[qb] = 0.0f;
+        if (LMFMA) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) lacc[qb][v] = 0.0f;
+        }
 #pragma unroll
         for (int d = 0; d < 2; ++d)
 #pragma unroll
@@ -220,9 +244,28 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
 #pragma unroll
                 for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[qb], mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * p.scale_log2e);
-            const float mc = m_new * p.scale_log2e;
+            // Lazy rescaling: m_run is the reference the exponentials are taken against (in log2 units), not
+            // necessarily the running maximum.  It only moves when a query's maximum has grown by more than 8
+            // (probabilities stay <= 2^8, exact in fp32 and harmless in bf16), which after the first tile is
+            // rare -- and then the whole wave skips the 32 multiplications of the accumulator.  On the first
+            // tile the reference is -inf, alpha = 0 and the (zero) accumulators are overwritten.
+            const float mxs = mx * p.scale_log2e;
+            const bool grow = mxs > m_run[qb] + 8.0f;
+            if (__any(grow)) {
+                const float m_new = grow ? mxs : m_run[qb];
+                const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+                l_run[qb] *= alpha;
+                m_run[qb] = m_new;
+                if (LMFMA) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) lacc[qb][v] *= alpha;
+                }
+#pragma unroll
+                for (int d = 0; d < 2; ++d)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[qb][d][v] *= alpha;
+            }
+            const float mc = m_run[qb];
             float psum = 0.0f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -230,19 +273,25 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
                 for (int v = 0; v < 16; ++v) {
                     const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][v], p.scale_log2e, -mc));
                     s[kb][v] = e;
-                    psum += e;
+                    if (!LMFMA) psum += e;
                 }
-            l_run[qb] = l_run[qb] * alpha + psum;
-            m_run[qb] = m_new;
-#pragma unroll
-            for (int d = 0; d < 2; ++d)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[qb][d][v] *= alpha;
+            if (LMFMA) {
+                AttnMma<T>::rowsum(lacc[qb], s[0]);
+                AttnMma<T>::rowsum(lacc[qb], s[1]);
+            } else {
+                l_run[qb] += psum;
+            }
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int d = 0; d < 2; ++d) AttnMma<T>::pv(o[qb][d], sV, d * 32 + li, kb, s[kb], g);
         }
+    }
+
+    if (LMFMA) {
+        // the matrix-pipe sums are complete in both lane halves; the code below adds the halves, so each takes half
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] = 0.5f * lacc[qb][0];
     }
 
     if constexpr (KW > 1) {
@@ -270,8 +319,8 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
             for (int qb = 0; qb < QB; ++qb) {
                 const float mk = src[(qb * 34 + 32) * 64], lk = src[(qb * 34 + 33) * 64];
                 const float m_new = fmaxf(m_run[qb], mk);
-                const float a = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * p.scale_log2e);
-                const float bsc = __builtin_amdgcn_exp2f((mk - m_new) * p.scale_log2e);
+                const float a = __builtin_amdgcn_exp2f(m_run[qb] - m_new);      // references are in log2 units
+                const float bsc = __builtin_amdgcn_exp2f(mk - m_new);
 #pragma unroll
                 for (int d = 0; d < 2; ++d)
 #pragma unroll
