@@ -136,6 +136,14 @@ def test_one_row_of_patches():
     check_all(vi.ModelSpec("strip", dtype="bf16", **{**MEDIUM, "img_h": 14, "img_w": 14 * 67}), 106, 206)
 
 
+def test_widest_supported_model():
+    # the limits the library accepts: width 2048 (32 heads: 32 statistics groups per row, LayerNorm rows of 16
+    # float2 per lane), 64 register tokens, 255 segmentation classes, 1024 head channels; four blocks, a 2 x 3 grid
+    spec = vi.ModelSpec("widest", dtype="bf16", dim=2048, depth=4, heads=32, mlp_hidden=2048, registers=64, img_h=28,
+                        img_w=42, taps=(1, 2, 3, 4), seg_classes=255, head_ch=1024)
+    check_all(spec, 107, 207)
+
+
 def test_cfg1_vits_fp32_224_seg():
     # benchmark configuration 1: ViT-S/14 fp32, 224 x 224, linear seg head; gate 1e-4
     spec = vi.CONFIGS["cfg1"]
