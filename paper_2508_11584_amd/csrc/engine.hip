@@ -96,6 +96,7 @@ struct vpe_engine {
     std::vector<BlockW> blk;
     // encoder scratch
     void* zeros = nullptr;               // 256 bytes that stay zero (padding taps of the 3x3 convolutions)
+    float* lev0 = nullptr;               // [T] level of a fresh frame's rows: mean over the width of bias + positional row
     // Encoder lanes: `lanes` complete scratch sets, each with its own stream.  Frame f is encoded on lane
     // f % lanes, so with two lanes the encoder passes of consecutive frames overlap on the GPU (the ViT-S
     // kernels are too small to fill 256 CUs on their own); results per frame are unchanged.
@@ -104,6 +105,7 @@ struct vpe_engine {
         // GEMMs; unused by fp32 engines, which read x); stats: per row and 64-column group (mean, sum of squared deviations) of x
         void *apatch = nullptr, *u = nullptr, *qk = nullptr, *vt = nullptr, *att = nullptr, *hid = nullptr;
         float *x = nullptr, *stats = nullptr;
+        float* lev[2] = {nullptr, nullptr};   // [T] row levels the copy u is stored against, alternating (see ln_gemm)
         hipStream_t stream = nullptr;
         hipEvent_t done = nullptr;      // completion of the lane's most recent encode
         bool used = false;
@@ -257,11 +259,13 @@ void layout(vpe_engine& e, Bump& b) {
     }
     e.norm_g = f32(D); e.norm_b = f32(D);
     e.zeros = b.take(256);
+    e.lev0 = f32(T);
     for (int l = 0; l < e.lanes; ++l) {
         vpe_engine::Lane& L = e.lane[l];
         L.apatch = b.take(B * P * KPATCH_PAD * esz);
         L.x = f32(T * D);
         L.stats = f32(T * (D / 64) * 2);
+        L.lev[0] = f32(T); L.lev[1] = f32(T);
         L.u = b.take(T * D * esz);
         // + 512 rows / columns that the attention loader may prefetch past the end (never used)
         L.qk = b.take((T + 512) * 2 * D * esz);
@@ -336,7 +340,8 @@ int upload_backbone(vpe_engine& e, const float* blob, float* staging) {
     const int D = e.D;
     // patch kernel [D][588] -> [D][640] (zero padded columns)
     TRY(up.relayout((int64_t)D * KPATCH, e.patch_w, D, KPATCH, KPATCH, 1, 0, 0, 0, KPATCH_PAD, 0, 0));
-    TRY(up.f32(e.patch_b, D));
+    const float* patch_b = up.take(D);
+    HIPCHK(&e, hipMemcpy(e.patch_b, patch_b, 4 * (size_t)D, hipMemcpyHostToDevice));
     // special rows: CLS + pos[0], then the registers; remaining pos rows belong to the patches
     const float* cls = up.take(D);
     const float* reg = up.take((int64_t)e.R * D);
@@ -346,6 +351,16 @@ int upload_backbone(vpe_engine& e, const float* blob, float* staging) {
     if (e.R) memcpy(sp.data() + D, reg, sizeof(float) * (size_t)e.R * D);
     HIPCHK(&e, hipMemcpy(e.special, sp.data(), sp.size() * 4, hipMemcpyHostToDevice));
     HIPCHK(&e, hipMemcpy(e.pos, pos + D, (size_t)e.P * D * 4, hipMemcpyHostToDevice));
+    {   // level of a fresh frame's rows: what is known of a row before its image arrives, averaged over the width
+        std::vector<float> lev((size_t)e.T);
+        for (int n = 0; n < e.N; ++n) {
+            double acc = 0.0;
+            if (n < 1 + e.R) for (int d = 0; d < D; ++d) acc += sp[(size_t)n * D + d];
+            else for (int d = 0; d < D; ++d) acc += (double)patch_b[d] + pos[(size_t)(n - e.R) * D + d];
+            for (int b = 0; b < e.B; ++b) lev[(size_t)b * e.N + n] = (float)(acc / D);
+        }
+        HIPCHK(&e, hipMemcpy(e.lev0, lev.data(), lev.size() * 4, hipMemcpyHostToDevice));
+    }
     const bool sw = e.cfg.mlp_kind == VPE_MLP_SWIGLU;
     for (auto& w : e.blk) {
         TRY(up.f32(w.ln1_g, D)); TRY(up.f32(w.ln1_b, D));
@@ -418,17 +433,23 @@ GemmArgs plain_gemm(const void* A, int64_t lda, const void* W, const float* bias
 // ------------------------------------------------------------------ launch sequences
 // A GEMM that consumes LayerNorm(x) of the lane's residual stream with the LayerNorm folded in: A is the copy
 // of x in the engine dtype (x itself for fp32 engines), statistics come from the producers' epilogues.
-GemmArgs ln_gemm(const vpe_engine& e, const vpe_engine::Lane& L, const void* W, const float* bias, const float* colsum, int N) {
+// The 16-bit copy is stored relative to a per-row level: `level` is the one the current copy was written
+// against, `next_level` receives the rows' means for the next copy (fp32 engines read x itself: no levels).
+GemmArgs ln_gemm(const vpe_engine& e, const vpe_engine::Lane& L, const void* W, const float* bias, const float* colsum, int N,
+                 const float* level, float* next_level) {
     GemmArgs a = plain_gemm(e.bf ? (const void*)L.u : (const void*)L.x, e.D, W, bias, e.T, N, e.D);
     a.ln_stats = L.stats; a.ln_colsum = colsum; a.ln_groups = e.D / 64; a.ln_eps = e.cfg.ln_eps;
+    if (e.bf) { a.ln_level = level; a.ln_level_out = next_level; }
     return a;
 }
 
-// A GEMM whose epilogue updates the residual stream: also refreshes its copy and its row statistics.
-void produce_stats(const vpe_engine& e, const vpe_engine::Lane& L, GemmArgs& a) {
+// A GEMM whose epilogue updates the residual stream: also refreshes its copy (against `level`) and its row
+// statistics.
+void produce_stats(const vpe_engine& e, const vpe_engine::Lane& L, GemmArgs& a, const float* level) {
     a.out = L.x; a.ldo = e.D;
     a.st_out = L.stats;
     a.xb_out = e.bf ? L.u : nullptr;
+    a.xb_level = e.bf ? level : nullptr;
 }
 
 int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
@@ -438,14 +459,19 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
         GemmArgs a = plain_gemm(L.apatch, KPATCH_PAD, e.patch_w, e.patch_b, e.B * e.P, D, KPATCH_PAD);
         a.epi = EPI_PATCH; a.pos = e.pos;
         a.o_rpi = e.P; a.o_istride = e.N; a.o_off = 1 + e.R;
-        produce_stats(e, L, a);
+        produce_stats(e, L, a, e.lev0);
         HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
     }
+    // levels alternate between the lane's two buffers: each LayerNorm-consuming GEMM reads the level its input
+    // was stored against and writes the rows' means into the other buffer, for the producer that follows it
+    const float* level = e.lev0;
+    int nxt = 0;
     int tap = 0;
     for (int l = 0; l < e.L; ++l) {
         const BlockW& w = e.blk[l];
         {
-            GemmArgs a = ln_gemm(e, L, w.qkv_w, w.qkv_b, w.qkv_s, 3 * D);
+            GemmArgs a = ln_gemm(e, L, w.qkv_w, w.qkv_b, w.qkv_s, 3 * D, level, L.lev[nxt]);
+            level = L.lev[nxt]; nxt ^= 1;
             a.epi = EPI_QKV; a.out = L.qk; a.ldo = 2 * D; a.out2 = L.vt; a.ntok = e.N; a.npad = e.npad; a.dim = D;
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
@@ -456,11 +482,12 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
         {
             GemmArgs a = plain_gemm(L.att, D, w.proj_w, w.proj_b, T, D, D);
             a.epi = EPI_RESID; a.gamma = w.ls1;
-            produce_stats(e, L, a);
+            produce_stats(e, L, a, level);
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         {
-            GemmArgs a = ln_gemm(e, L, w.fc1_w, w.fc1_b, w.fc1_s, e.F);
+            GemmArgs a = ln_gemm(e, L, w.fc1_w, w.fc1_b, w.fc1_s, e.F, level, L.lev[nxt]);
+            level = L.lev[nxt]; nxt ^= 1;
             a.out = L.hid; a.ldo = e.Mh;
             if (e.cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
             else a.act = ACT_GELU;
@@ -469,7 +496,7 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
         {
             GemmArgs a = plain_gemm(L.hid, e.Mh, w.fc2_w, w.fc2_b, T, D, e.Mh);
             a.epi = EPI_RESID; a.gamma = w.ls2;
-            produce_stats(e, L, a);
+            produce_stats(e, L, a, level);
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         if (tap < 4 && l + 1 == e.cfg.taps[tap]) {
@@ -747,7 +774,7 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
         // a lane's scratch is single-instance: order after the lane's previous encode
         if (L.used) HIPCHK(e, hipStreamWaitEvent(s, L.done, 0));
         HIPCHK(e, launch_im2col(e->bf, images, e->B, e->H, e->W, KPATCH_PAD, L.apatch, e->special, 1 + e->R,
-                                e->N, e->D, L.x, e->bf ? L.u : nullptr, L.stats, s));
+                                e->N, e->D, L.x, e->bf ? L.u : nullptr, L.stats, e->bf ? e->lev0 : nullptr, s));
         if (e->graphs) {
             hipGraphExec_t& ge = e->enc_graphs[(size_t)slot * e->lanes + ln];
             if (!ge) TRY(capture(*e, &ge, [&](hipStream_t cs) { return enqueue_encoder_body(*e, slot, ln, cs); }));
@@ -884,7 +911,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
         if (timed) HIPCHK(e, hipEventRecord(t0, s));
         for (int i = 0; i < (timed ? reps : 1); ++i) {
             if (which == 0) {
-                GemmArgs a = ln_gemm(*e, L0, e->blk[0].qkv_w, e->blk[0].qkv_b, e->blk[0].qkv_s, 3 * D);
+                GemmArgs a = ln_gemm(*e, L0, e->blk[0].qkv_w, e->blk[0].qkv_b, e->blk[0].qkv_s, 3 * D, L0.lev[1], nullptr);
                 a.epi = EPI_QKV; a.out = L0.qk; a.ldo = 2 * D; a.out2 = L0.vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
             } else if (which == 1) {

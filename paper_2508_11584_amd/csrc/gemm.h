@@ -47,10 +47,18 @@ struct GemmArgs {
     const float* ln_colsum;
     int ln_groups;             // = K / 64
     float ln_eps;
+    // A may hold the rows minus a per-row level (LayerNorm does not see a level common to a row, and a 16-bit
+    // copy of x - level keeps its precision when the row sits far from zero): ln_level[r] is that level (null:
+    // 0).  ln_level_out (may be null) receives the rows' means, written by the tiles of the first column
+    // block: the level for the NEXT copy of these rows -- a different buffer from ln_level, which the other
+    // column tiles are still reading.
+    const float* ln_level;
+    float* ln_level_out;
     // Producer side (RESID / PATCH, N a multiple of 64): besides the fp32 rows, write their copy in T
     // (xb_out, [rows][N], may be null) and the group statistics of the updated rows (st_out, may be null)
     void* xb_out;
     float* st_out;
+    const float* xb_level;     // xb_out holds x - xb_level[row] (null: 0); statistics are of x itself
     // batch of nz independent problems of the same shape in one launch (blockIdx.y = z): problem z uses
     // A + z * z_a, W + z * z_w, out + z * z_out (byte strides, may be negative) and bias + z * z_bias (elements)
     int nz;
@@ -289,6 +297,18 @@ __device__ __forceinline__ void ln_row_stats(const GemmArgs& p, int r, float& me
     rstd = 1.0f / sqrtf(m2 / (64.0f * G) + p.ln_eps);
 }
 
+// Consumer prologue, one thread per tile row: (mean relative to the level A was stored against, rstd) into
+// lnrow, and the row's mean handed on as the next level by the first column block's tiles.
+__device__ __forceinline__ void ln_tile_row(const GemmArgs& p, int m0, int n0, int t, float* lnrow) {
+    const bool real = m0 + t < p.M;
+    const int r = real ? m0 + t : p.M - 1;
+    float mean, rstd;
+    ln_row_stats(p, r, mean, rstd);
+    lnrow[2 * t] = mean - (p.ln_level ? p.ln_level[r] : 0.0f);
+    lnrow[2 * t + 1] = rstd;
+    if (p.ln_level_out && n0 == 0 && real) p.ln_level_out[r] = mean;
+}
+
 // RESID / PATCH chunk with the producer-side extras.  Called by all 8 lanes that hold the 8 chunks of one
 // 64-column group of a row (consecutive lanes, chunk index = lane % 8); `active` is the same for all of them.
 template <typename T>
@@ -297,7 +317,13 @@ __device__ __forceinline__ void resid_stats_chunk(const GemmArgs& p, int r, int 
     if (active) {
         epilogue_chunk<T>(p, r, c, v);         // leaves the updated residual values in v
         if (p.epi == EPI_PATCH) orow = (int64_t)(r / p.o_rpi) * p.o_istride + p.o_off + r % p.o_rpi;
-        if (p.xb_out) store8(reinterpret_cast<T*>(p.xb_out) + orow * p.ldo + c, v);
+        if (p.xb_out) {
+            const float lev = p.xb_level ? p.xb_level[orow] : 0.0f;
+            float rel[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rel[i] = v[i] - lev;
+            store8(reinterpret_cast<T*>(p.xb_out) + orow * p.ldo + c, rel);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = 0.0f;
@@ -601,10 +627,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
             const int c = n0 + wn * WN + j * 32 + li;
             if (c < p.N) lncs[j] = p.ln_colsum[c];
         }
-        if (tid < BM) {
-            const int r = m0 + tid < p.M ? m0 + tid : p.M - 1;
-            ln_row_stats(p, r, lnrow[2 * tid], lnrow[2 * tid + 1]);
-        }
+        if (tid < BM) ln_tile_row(p, m0, n0, tid, lnrow);
     }
     sstore(0, 0);
     __syncthreads();

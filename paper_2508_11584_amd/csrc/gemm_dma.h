@@ -206,10 +206,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
     const int KT = p.K / BK;
 #pragma unroll
     for (int s = 0; s < PD; ++s) dma(s, s < KT ? s : KT - 1);
-    if (p.ln_stats && tid < BM) {      // behind the first tile loads, ordered before the epilogue by the loop's barriers
-        const int r = m0 + tid < p.M ? m0 + tid : p.M - 1;
-        ln_row_stats(p, r, lnrow[2 * tid], lnrow[2 * tid + 1]);
-    }
+    // behind the first tile loads, ordered before the epilogue by the loop's barriers
+    if (p.ln_stats && tid < BM) ln_tile_row(p, m0, n0, tid, lnrow);
     for (int kt = 0; kt < KT; ++kt) {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * (A_SLOTS + B_SLOTS)));
         __syncthreads();

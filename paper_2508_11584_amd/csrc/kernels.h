@@ -18,7 +18,7 @@ hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const fl
                             float eps, void* y, hipStream_t s);
 hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
                          const float* special, int nspecial, int ntok, int D, float* x, void* xb, float* stats,
-                         hipStream_t s);
+                         const float* level, hipStream_t s);
 hipError_t launch_relayout(int dtype, const float* src, void* dst, int n_rows, int n_cols, int64_t rs,
                            int64_t cs, int mode, int cin, int swiglu_half, int64_t dst_ld, int row_off,
                            int col_off, const float* kscale, hipStream_t s);

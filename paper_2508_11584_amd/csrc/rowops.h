@@ -58,7 +58,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 // Patch gathering for the 14x14 stride-14 embedding: row (b, p) of `cols` receives the 588
 // pixels of patch p in (channel, row, column) order, zero-padded to kpad columns.  The same
 // launch also fills the non-patch rows of the residual stream (CLS + pos[0], then registers)
-// from the `special` table [1 + R][D], together with their copy in T (xb, may be null) and the (mean, sum
+// from the `special` table [1 + R][D], together with their copy in T minus the row's level (xb, level; may be
+// null) and the (mean, sum
 // of squared deviations) of each of their 64-column groups (stats [rows][D / 64][2], may be null) -- what
 // the GEMM epilogues produce for the other rows.  blocks [0, B*P) gather; the rest write special rows.
 template <typename T>
@@ -66,7 +67,8 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ i
                                                      int kpad, T* __restrict__ cols,
                                                      const float* __restrict__ special, int nspecial,
                                                      int ntok, int D, float* __restrict__ x,
-                                                     T* __restrict__ xb, float* __restrict__ stats) {
+                                                     T* __restrict__ xb, float* __restrict__ stats,
+                                                     const float* __restrict__ level) {
     const int gw = W / 14, P = (H / 14) * gw;
     int blk = blockIdx.x;
     if (blk < B * P) {
@@ -89,7 +91,7 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ i
             const int d = grp * 64 + lane;
             const float v = special[(int64_t)r * D + d];
             x[row * D + d] = v;
-            if (xb) xb[row * D + d] = from_f32<T>(v);
+            if (xb) xb[row * D + d] = from_f32<T>(v - (level ? level[row] : 0.0f));
             const float mean = wave_sum(v) * (1.0f / 64.0f);
             const float m2 = wave_sum((v - mean) * (v - mean));
             if (stats && lane == 0) {

@@ -17,11 +17,11 @@ hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const fl
 
 hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
                          const float* special, int nspecial, int ntok, int D, float* x, void* xb, float* stats,
-                         hipStream_t s) {
+                         const float* level, hipStream_t s) {
     const int P = (H / 14) * (W / 14);
     const unsigned nb = (unsigned)(B * P + B * nspecial);
-    if (dtype) hipLaunchKernelGGL(im2col_kernel<bf16>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (bf16*)cols, special, nspecial, ntok, D, x, (bf16*)xb, stats);
-    else hipLaunchKernelGGL(im2col_kernel<float>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (float*)cols, special, nspecial, ntok, D, x, (float*)xb, stats);
+    if (dtype) hipLaunchKernelGGL(im2col_kernel<bf16>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (bf16*)cols, special, nspecial, ntok, D, x, (bf16*)xb, stats, level);
+    else hipLaunchKernelGGL(im2col_kernel<float>, dim3(nb), dim3(256), 0, s, img, B, H, W, kpad, (float*)cols, special, nspecial, ntok, D, x, (float*)xb, stats, level);
     return hipGetLastError();
 }
 
