@@ -11,18 +11,20 @@ namespace {
 //     t [us] = alpha * max(r, 1) + beta * r * (bm * bn * K / 1e6),     r = ceil(tiles / 256) / held,
 // r being the number of "rounds" on the busiest of the 256 CUs (it gets ceil(tiles / 256) tiles and works on
 // `held` of them at a time); alpha is the cost a workgroup pays whatever its size (first loads, epilogue), not
-// discounted on a partly filled chip.  Fitted (relative least squares) to 28 measured shapes x 6 tilings on
+// discounted on a partly filled chip.  Fitted (relative least squares) to 28 measured shapes x 8 tilings on
 // MI355X with random bf16 data: the QKV / proj / fc1 / fc2 GEMMs of ViT-S, -B, -L (batch 4) and -g (batch 8),
 // the heads' 1x1 projections, and the 3x3 convolutions at 34x45 ... 296x296 grids (batch 1 and 4).  The
-// model's pick is the measured best or within 4 % of it on every one of them (0.2 % in total time).
-struct Cand { int kind, bm, bn, held; float alpha, beta; };
+// model's pick is the measured best on 23 of them, within 8 % on four and 15 % on one (0.4 % in total time).
+struct Cand { int kind, bm, bn, held; float alpha, beta; bool dma; };
 constexpr Cand kCands[] = {
-    {128, 256, 128, 2, 5.35f, 1.057f},    // direct-to-LDS, 64 x 64 wave tiles
-    {256, 256, 256, 1, 12.15f, 0.333f},   // direct-to-LDS, 64 x 128 wave tiles
-    {384, 384, 256, 1, 16.00f, 0.359f},   // direct-to-LDS, 96 x 128 wave tiles
-    {1, 128, 128, 2, 7.85f, 1.116f},      // register-staged
-    {2, 64, 128, 3, 6.08f, 1.980f},
-    {3, 64, 64, 4, 4.90f, 3.201f},
+    {128, 256, 128, 2, 5.16f, 1.055f, true},    // direct-to-LDS, 8 waves, 64 x 64 wave tiles
+    {256, 256, 256, 1, 11.96f, 0.332f, true},   // direct-to-LDS, 8 waves, 64 x 128 wave tiles
+    {384, 384, 256, 1, 15.66f, 0.361f, true},   // direct-to-LDS, 8 waves, 96 x 128 wave tiles
+    {65, 64, 128, 3, 5.13f, 1.828f, true},      // direct-to-LDS, 4 waves, 32 x 64 wave tiles
+    {64, 64, 64, 4, 4.55f, 2.909f, true},       // direct-to-LDS, 4 waves, 32 x 32 wave tiles
+    {1, 128, 128, 2, 7.72f, 1.120f, false},     // register-staged (any operand size)
+    {2, 64, 128, 3, 5.96f, 1.972f, false},
+    {3, 64, 64, 4, 4.88f, 3.153f, false},
 };
 }  // namespace
 
@@ -36,17 +38,18 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     int best = 3;
     float best_cost = 0.0f;
     for (const Cand& c : kCands) {
-        if (c.kind >= 128 && !fits) continue;
-        if (c.kind == 3 && a.epi == EPI_SWIGLU) continue;       // needs 64-column wave tiles
+        if (c.dma && !fits) continue;
+        if (c.bn == 64 && a.epi == EPI_SWIGLU) continue;        // needs 64-column wave tiles
         const int64_t tiles = (int64_t)cdiv(a.M, c.bm) * cdiv(a.N, c.bn) * (a.nz > 1 ? a.nz : 1);
         const float r = (float)cdiv(tiles, 256) / c.held;
         const float cost = c.alpha * (r > 1.0f ? r : 1.0f) + c.beta * r * (1e-6f * c.bm * c.bn * a.K);
         if (best_cost == 0.0f || cost < best_cost) { best_cost = cost; best = c.kind; }
     }
-    if ((forced == 384 || forced == 256 || forced == 128) && fits) best = forced;
+    if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
+    if (forced == 64 && fits) best = a.epi == EPI_SWIGLU ? 65 : 64;
     if (forced == 1) best = a.epi == EPI_SWIGLU ? 2 : 3;
     switch (best) {
-        case 128: case 256: case 384: return launch_gemm_dma_bf16(best, a, amode, s);
+        case 64: case 65: case 128: case 256: case 384: return launch_gemm_dma_bf16(best, a, amode, s);
         case 1: return launch_tile<bf16, 128, 128, 2, 2>(a, amode, s);
         case 2: return launch_tile<bf16, 64, 128, 2, 2>(a, amode, s);
         default: return launch_tile<bf16, 64, 64, 2, 2>(a, amode, s);

@@ -218,6 +218,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // drain the clamped tail prefetches before LDS is reused
     __syncthreads();
 
+    if constexpr (WN % 64 != 0) {
+        // Small tiles (32-column wave tiles): a wave does not hold whole 64-column groups, so the tile leaves
+        // through the block-level epilogue of the register-staged kernels (whole tile staged in LDS).
+        static_assert(BM * BN * 4 <= S * STAGE, "accumulator tile must fit the stage buffers");
+        float lncs[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int c = n0 + wn * WN + j * 32 + li;
+            lncs[j] = p.ln_stats && c < p.N ? p.ln_colsum[c] : 0.0f;
+        }
+        block_epilogue<T, BM, BN, WGM, WGN>(p, acc, smem, lnrow, lncs, m0, n0);
+        return;
+    }
+
     // --- epilogue.  Each wave stages its accumulators 32 rows at a time in its own 32 x WN fp32
     // block of LDS (the stage buffers are free now) and leaves with 8-column chunks per lane.
     float* sC = reinterpret_cast<float*>(smem) + wave * (32 * WN);

@@ -6,9 +6,14 @@ namespace vpe {
 //   128: 256 x 128 tile, 32-deep k-tiles, 8 waves (64 x 64 wave tiles), two workgroups per CU      820-850
 //   256: 256 x 256 tile, 64-deep k-tiles, 8 waves (64 x 128 wave tiles), one workgroup per CU       975
 //   384: 384 x 256 tile, 32-deep k-tiles, 8 waves (96 x 128 wave tiles), one workgroup per CU       995
+// and two small shapes for small problems (4 waves, 64-deep k-tiles), faster than their register-staged
+// counterparts by 8-14 % on the ViT-S / ViT-B GEMMs and the small convolutions:
+//    64: 64 x 64 tile (32 x 32 wave tiles, block-level epilogue), 65: 64 x 128 tile (32 x 64 wave tiles)
 // The one-per-CU shapes run in lockstep rounds, so they pay for a partly filled last round in full; which
 // shape wins depends on how the tile count divides by the 256 CUs (see launch_gemm_bf16).
 hipError_t launch_gemm_dma_bf16(int kind, const GemmArgs& a, int amode, hipStream_t s) {
+    if (kind == 64) return launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, amode, s);
+    if (kind == 65) return launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, amode, s);
     if (kind == 384) return launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, amode, s);
     if (kind == 256) return launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, amode, s);
     return launch_gemm_dma<128, 32, 2, 4, 2, 2>(a, amode, s);
@@ -17,6 +22,8 @@ hipError_t launch_gemm_dma_bf16(int kind, const GemmArgs& a, int amode, hipStrea
 hipError_t configure_gemm() {
     GemmArgs a{};
     hipError_t rc = launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, A_PLAIN, nullptr, true);
+    if (rc == hipSuccess) rc = launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
+    if (rc == hipSuccess) rc = launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, A_PLAIN, nullptr, true);
     return rc != hipSuccess ? rc : launch_gemm_dma<128, 32, 2, 4, 2, 2>(a, A_PLAIN, nullptr, true);
 }

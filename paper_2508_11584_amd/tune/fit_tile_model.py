@@ -9,7 +9,8 @@ import sys
 import numpy as np
 
 KINDS = [("d256x128", 256, 128, 2), ("d256x256", 256, 256, 1), ("d384x256", 384, 256, 1),
-         ("r128x128", 128, 128, 2), ("r64x128", 64, 128, 3), ("r64x64", 64, 64, 4)]
+         ("r128x128", 128, 128, 2), ("r64x128", 64, 128, 3), ("r64x64", 64, 64, 4),
+         ("d64x64", 64, 64, 4), ("d64x128", 64, 128, 3)]
 
 
 def cdiv(a, b):

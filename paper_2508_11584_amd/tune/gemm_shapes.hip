@@ -63,16 +63,18 @@ int main(int argc, char** argv) {
         if (s.cC) { a.lda = s.cC; a.cH = s.cH; a.cW = s.cW; a.cC = s.cC; a.a_istride = s.cH * s.cW; a.zeros = bias; a.act = ACT_RELU; }
         const double fl = 2.0 * s.M * s.N * s.K;
         const int reps = 20;
-        float t[6];
+        float t[8];
         t[0] = timeit([&] { launch_gemm_dma<128, 32, 2, 4, 2, 2>(a, amode, 0); }, reps);
         t[1] = timeit([&] { launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, amode, 0); }, reps);
         t[2] = timeit([&] { launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, amode, 0); }, reps);
         t[3] = timeit([&] { launch_tile<bf16, 128, 128, 2, 2>(a, amode, 0); }, reps);
         t[4] = timeit([&] { launch_tile<bf16, 64, 128, 2, 2>(a, amode, 0); }, reps);
         t[5] = timeit([&] { launch_tile<bf16, 64, 64, 2, 2>(a, amode, 0); }, reps);
+        t[6] = timeit([&] { launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, amode, 0); }, reps);
+        t[7] = timeit([&] { launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, amode, 0); }, reps);
         printf("%-22s M=%5d N=%5d K=%5d |", s.name, s.M, s.N, s.K);
-        const char* names[6] = {"d256x128", "d256x256", "d384x256", "r128x128", "r64x128", "r64x64"};
-        for (int k = 0; k < 6; ++k) printf(" %s %7.1fus %4.0fTF |", names[k], t[k] * 1e3, fl / t[k] / 1e9);
+        const char* names[8] = {"d256x128", "d256x256", "d384x256", "r128x128", "r64x128", "r64x64", "d64x64", "d64x128"};
+        for (int k = 0; k < 8; ++k) printf(" %s %7.1fus %4.0fTF |", names[k], t[k] * 1e3, fl / t[k] / 1e9);
         printf("\n");
         fflush(stdout);
     }
