@@ -106,6 +106,86 @@ def multihead_experiment(args, vpe, vi, make_engine, np, torch) -> None:
                       "latency": "median ms, one frame at a time, inputs resident in HBM", "rows": rows}))
 
 
+def freshness_experiment(args, vpe, vi, make_engine, np, torch) -> None:
+    """The lossy, decentralised way of running the engine (paper, Sec. "Decentralization", "Data Flow", "Dynamic
+    Frequency Control", Appendix "Rate-Limiting Experiment"), on the host's real clock.
+
+    rate_limit: 300 frames published at a fixed rate, every head limited to the same rate in Hz, engine
+      stamping frames with its own steady clock; delivered counts against rate x duration (the appendix's table;
+      its 30 Hz / 10 s stream is run ten times faster here, 300 Hz / 1 s, limits 50 .. 300 Hz).
+    saturated: frames pushed as fast as the encoder takes them (the producer stays one encode per lane ahead of
+      the device) while every head keeps asking for the newest complete frame and is turned away while its previous
+      run is still going: nothing waits for anything else, slow heads lose frames."""
+    spec = vi.CONFIGS[args.config]
+    wseed, iseed = vi.SEEDS[args.config]
+    kinds = ("seg", "depth", "det")
+    images_np = vi.make_batch(spec, iseed)
+    frames = [torch.from_numpy(images_np).cuda(), torch.from_numpy(np.ascontiguousarray(images_np[..., ::-1])).cuda()]
+    flags = (0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS) | vpe.VPE_FLAG_WALL_CLOCK
+    lanes = args.encoder_lanes
+    publish_hz, n = 300.0, 300
+    table = []
+    for limit in (50.0, 100.0, 150.0, 200.0, 250.0, 300.0):
+        eng, _, _ = make_engine(spec, wseed, kinds=kinds, ring_slots=lanes + 1, encoder_lanes=lanes, flags=flags)
+        for i in range(6):                                    # graph capture, not limited
+            fh = eng.encode(frames[i & 1])
+            for h in range(3):
+                eng.run_head(h, fh)
+        eng.sync()
+        before = [eng.head_counters(h)["runs"] for h in range(3)]
+        for h in range(3):
+            eng.set_head_rate_hz(h, limit)
+        t0 = time.perf_counter()
+        for i in range(n):
+            while time.perf_counter() - t0 < i / publish_hz:
+                pass
+            fh = eng.encode(frames[i & 1])
+            for h in range(3):
+                eng.run_head(h, fh)
+        eng.sync()
+        span = time.perf_counter() - t0
+        got = [eng.head_counters(h)["runs"] - before[h] for h in range(3)]
+        ideal = n * limit / publish_hz
+        table.append({"limit_hz": limit, "ideal": ideal, "delivered": dict(zip(kinds, got)),
+                      "error": dict(zip(kinds, [g - ideal for g in got])), "span_s": round(span, 4)})
+        eng.close()
+        print(json.dumps(table[-1]), file=sys.stderr, flush=True)
+    eng, _, _ = make_engine(spec, wseed, kinds=kinds, ring_slots=lanes + 1, encoder_lanes=lanes, flags=flags)
+    for i in range(6):
+        fh = eng.encode(frames[i & 1])
+        for h in range(3):
+            eng.run_head(h, fh)
+    eng.sync()
+    c0 = [eng.head_counters(h) for h in range(3)]
+    n_sat = max(args.steps, 300) * 4
+    pending = []
+
+    def poll():
+        for h in range(3):
+            eng.run_head_latest(h)
+
+    t0 = time.perf_counter()
+    for i in range(n_sat):
+        while len(pending) >= lanes and eng.frame_ready(pending[0]) == vpe.VPE_BUSY:     # stay `lanes` encodes ahead at most
+            poll()
+        if len(pending) >= lanes:
+            pending.pop(0)
+        pending.append(eng.encode(frames[i & 1]))
+        poll()
+    eng.sync()
+    span = time.perf_counter() - t0
+    heads = {}
+    for h, kind in enumerate(kinds):
+        c = eng.head_counters(h)
+        runs = c["runs"] - c0[h]["runs"]
+        heads[kind] = {"runs": runs, "runs_per_s": round(runs / span, 1), "missed": c["missed"] - c0[h]["missed"],
+                       "busy_returns": c["busy"] - c0[h]["busy"], "overflow": c["overflow"] - c0[h]["overflow"]}
+    eng.close()
+    print(json.dumps({"experiment": "freshness", "workload": spec.name, "encoder_lanes": lanes, "hw_queues": args.hw_queues,
+                      "rate_limit": {"published_hz": publish_hz, "frames": n, "rows": table},
+                      "saturated": {"frames": n_sat, "encoder_frames_per_s": round(n_sat * spec.batch / span, 1), "heads": heads}}))
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,10 +205,12 @@ def main() -> None:
     ap.add_argument("--roofline-only", action="store_true",
                     help="one frame, a 1 GiB device copy (counter calibration) and the dominant-kernel timing leg only; "
                          "the mode the rocprofv3 --pmc passes are taken in")
-    ap.add_argument("--experiment", choices=["multihead"], default=None,
+    ap.add_argument("--experiment", choices=["multihead", "freshness"], default=None,
                     help="multihead: frame latency against the number of identical heads (1, 2, 4, 8), for depth heads "
                          "(the paper's single-backbone-vs-independent-models experiment) and detection heads (its "
-                         "parallel-vs-sequential-heads experiment); prints its own JSON line instead of the benchmark's")
+                         "parallel-vs-sequential-heads experiment); freshness: the appendix's rate-limiting table on the real "
+                         "clock, and the lossy newest-frame policy under a saturating producer; each prints its own JSON "
+                         "line instead of the benchmark's")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from the --pmc passes (FETCH_SIZE + WRITE_SIZE, "
                          "calibrated); reported as roofline.traffic")
@@ -151,6 +233,9 @@ def main() -> None:
 
     if args.experiment == "multihead":
         multihead_experiment(args, vpe, vi, make_engine, np, torch)
+        return
+    if args.experiment == "freshness":
+        freshness_experiment(args, vpe, vi, make_engine, np, torch)
         return
 
     spec = vi.CONFIGS[args.config]

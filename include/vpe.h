@@ -14,6 +14,7 @@
  *
  * Conventions
  *   - return value: 0 = VPE_OK, 1 = VPE_SKIPPED (head not due on that frame; not an
+ *     error), 2 = VPE_BUSY (vpe_run_head_latest only: the head's previous run has not finished; not an
  *     error), negative = error (see vpe_status).  vpe_last_error() gives a message.
  *   - "device" pointers are HIP device addresses on the current device; "host" pointers
  *     are ordinary process memory.
@@ -37,7 +38,7 @@ typedef struct vpe_engine vpe_engine;                 /* opaque, owned by the li
  * index (0 for the first vpe_encode of the engine, then 1, 2, ...).  A plain value. */
 typedef struct { int32_t slot; int32_t reserved; int64_t frame; } vpe_feat;
 
-typedef enum { VPE_OK = 0, VPE_SKIPPED = 1, VPE_EINVAL = -1, VPE_ENOMEM = -2, VPE_ESTALE = -3,
+typedef enum { VPE_OK = 0, VPE_SKIPPED = 1, VPE_BUSY = 2, VPE_EINVAL = -1, VPE_ENOMEM = -2, VPE_ESTALE = -3,
                VPE_EHIP = -4 } vpe_status;
 typedef enum { VPE_F32 = 0, VPE_BF16 = 1 } vpe_dtype;
 typedef enum { VPE_MLP_GELU = 0, VPE_MLP_SWIGLU = 1 } vpe_mlp;
@@ -45,8 +46,10 @@ typedef enum { VPE_HEAD_SEG = 0, VPE_HEAD_DEPTH = 1, VPE_HEAD_DET = 2 } vpe_head
 
 enum {
     VPE_FLAG_GRAPHS = 1,     /* replay the encoder and the heads as captured HIP graphs */
-    VPE_FLAG_HOST_ONLY = 2   /* no device at all: calls do the scheduling bookkeeping only (slot ring, rates,
+    VPE_FLAG_HOST_ONLY = 2,  /* no device at all: calls do the scheduling bookkeeping only (slot ring, rates,
                                 staleness, counters); for exercising the host logic on a machine without a GPU */
+    VPE_FLAG_WALL_CLOCK = 4  /* vpe_encode stamps each frame with the host's steady clock (seconds since
+                                vpe_create), so limits in Hz act on real time without the caller keeping one */
 };
 
 /*
@@ -159,12 +162,41 @@ int vpe_next_encode_stream(vpe_engine* e, void** stream);
 /* As vpe_encode, for a frame captured at time t_seconds (any monotonic clock of the caller's: a camera
  * timestamp, or frame index / frame rate).  The time is kept with the frame and is what per-head limits in
  * Hz (vpe_set_head_rate_hz) are measured against; frames encoded with vpe_encode carry no time and are
- * not limited in Hz.  t_seconds must not decrease from one frame to the next (VPE_EINVAL). */
+ * not limited in Hz, unless the engine was created with VPE_FLAG_WALL_CLOCK.  t_seconds must not decrease from one frame to the next (VPE_EINVAL). */
 int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_seconds, vpe_feat* out);
 
 /* Run head `head` on a frame's features.  Returns VPE_SKIPPED when fh.frame % every_n != 0,
  * VPE_ESTALE when the slot has been reused by a later frame. */
 int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream);
+
+/* Has the encoder finished writing this frame's features?  VPE_OK = yes, VPE_BUSY = still executing,
+ * VPE_ESTALE = the slot has been taken by a later frame (no error message is set for these three).  A producer
+ * that must not run further ahead of the device than the ring is long polls the handle it got `ring_slots - 1`
+ * frames ago.  Never blocks. */
+int vpe_frame_ready(vpe_engine* e, vpe_feat fh);
+
+/* Run head `head` on the NEWEST frame whose features are complete, the way the paper's decentralised modules do (Sec.
+ * "Decentralization", "Data Flow": modules never wait for each other, a circular buffer overwrites its oldest
+ * entry, so a slow head works on the freshest features and loses the frames in between).  In order:
+ *   VPE_SKIPPED  no frame has been encoded since this head last asked (through this call or vpe_run_head);
+ *   VPE_BUSY     the head's previous run is still executing on the device: nothing is queued behind it, call
+ *                again later (never returned by host-only engines);
+ *   VPE_SKIPPED  none of the frames encoded since then, and still in the ring, has finished on the device;
+ *   VPE_SKIPPED  the newest frame is fewer than every_n frames after the head's last run, or the limit in Hz
+ *                does not allow it yet;
+ *   VPE_OK       the run was enqueued; *ran_on (may be NULL) receives the frame's handle.
+ * Frames between the last one the head asked about and the one it takes now are counted as missed (see
+ * vpe_head_counters).  Never blocks the host.  While the head reads a slot, an encode into that slot waits on the
+ * device (not on the host): size the ring so that ring_slots frame periods exceed the slowest head's run time. */
+int vpe_run_head_latest(vpe_engine* e, int head, void* stream, vpe_feat* ran_on);
+
+/* Per-head counters, all since vpe_create:
+ *   out[0] runs, out[1] skips (not due), out[2] missed: frames passed over by vpe_run_head_latest taking a newer
+ *   one, out[3] overflow: frames overwritten in the ring before this head had asked about them or a later frame
+ *   (the signal that the consumer does not keep pace with the producer; paper, Sec. "Data Flow"),
+ *   out[4] busy returns, out[5] frame of the last run (-1 = none), out[6] newest frame asked about (-1 = none),
+ *   out[7] reserved (0). */
+int vpe_head_counters(vpe_engine* e, int head, int64_t out[8]);
 
 /* Change a head's rate; takes effect from the next vpe_run_head.  every_n_frames < 1 -> VPE_EINVAL. */
 int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames);

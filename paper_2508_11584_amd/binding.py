@@ -12,11 +12,11 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-VPE_OK, VPE_SKIPPED, VPE_EINVAL, VPE_ENOMEM, VPE_ESTALE, VPE_EHIP = 0, 1, -1, -2, -3, -4
+VPE_OK, VPE_SKIPPED, VPE_BUSY, VPE_EINVAL, VPE_ENOMEM, VPE_ESTALE, VPE_EHIP = 0, 1, 2, -1, -2, -3, -4
 VPE_F32, VPE_BF16 = 0, 1
 VPE_MLP_GELU, VPE_MLP_SWIGLU = 0, 1
 VPE_HEAD_SEG, VPE_HEAD_DEPTH, VPE_HEAD_DET = 0, 1, 2
-VPE_FLAG_GRAPHS, VPE_FLAG_HOST_ONLY = 1, 2
+VPE_FLAG_GRAPHS, VPE_FLAG_HOST_ONLY, VPE_FLAG_WALL_CLOCK = 1, 2, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libvpe.so")
@@ -62,6 +62,9 @@ def load_library(path: Optional[str] = None):
     L.vpe_create.argtypes = [C.POINTER(vpe_backbone_cfg), C.POINTER(vpe_head_cfg), i32, vp, C.c_uint64, C.POINTER(vp)]
     L.vpe_encode.argtypes = [vp, vp, vp, C.POINTER(vpe_feat)]
     L.vpe_run_head.argtypes = [vp, i32, vpe_feat, vp]
+    L.vpe_run_head_latest.argtypes = [vp, i32, vp, C.POINTER(vpe_feat)]
+    L.vpe_head_counters.argtypes = [vp, i32, i64p]
+    L.vpe_frame_ready.argtypes = [vp, vpe_feat]
     L.vpe_set_head_rate.argtypes = [vp, i32, i32]
     L.vpe_next_encode_stream.argtypes = [vp, C.POINTER(C.c_void_p)]
     L.vpe_preprocess_u8.argtypes = [vp, i32, i32, i32, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
@@ -78,7 +81,7 @@ def load_library(path: Optional[str] = None):
     L.vpe_destroy.restype = None
     for n in ("vpe_workspace_bytes", "vpe_create", "vpe_encode", "vpe_encode_at", "vpe_run_head", "vpe_set_head_rate",
               "vpe_set_head_rate_hz", "vpe_preprocess_u8", "vpe_next_encode_stream", "vpe_feat_view",
-              "vpe_head_output", "vpe_sync", "vpe_stats", "vpe_time_kernel"):
+              "vpe_head_output", "vpe_sync", "vpe_stats", "vpe_time_kernel", "vpe_run_head_latest", "vpe_head_counters", "vpe_frame_ready"):
         getattr(L, n).restype = C.c_int
     if path is None:
         _lib = L
@@ -159,6 +162,34 @@ def vpe_run_head(engine, head: int, fh: vpe_feat, stream_ptr: Optional[int] = No
     if rc < 0:
         raise VpeError(rc, vpe_last_error(engine))
     return rc
+
+
+def vpe_run_head_latest(engine, head: int, stream_ptr: Optional[int] = None):
+    """Returns (status, handle): handle is the frame the head was started on, None unless status == VPE_OK."""
+    fh = vpe_feat()
+    rc = lib().vpe_run_head_latest(engine, head, stream_ptr, C.byref(fh))
+    if rc < 0:
+        raise VpeError(rc, vpe_last_error(engine))
+    return rc, (fh if rc == VPE_OK else None)
+
+
+def vpe_frame_ready(engine, fh: vpe_feat) -> int:
+    """VPE_OK, VPE_BUSY or VPE_ESTALE."""
+    rc = lib().vpe_frame_ready(engine, fh)
+    if rc < 0 and rc != VPE_ESTALE:
+        raise VpeError(rc, vpe_last_error(engine))
+    return rc
+
+
+HEAD_COUNTERS = ("runs", "skips", "missed", "overflow", "busy", "last_run_frame", "seen")
+
+
+def vpe_head_counters(engine, head: int) -> dict:
+    out = (C.c_int64 * 8)()
+    rc = lib().vpe_head_counters(engine, head, out)
+    if rc:
+        raise VpeError(rc, vpe_last_error(engine))
+    return {k: int(out[i]) for i, k in enumerate(HEAD_COUNTERS)}
 
 
 def vpe_set_head_rate(engine, head: int, every_n_frames: int) -> None:
@@ -278,6 +309,15 @@ class Engine:
 
     def run_head(self, head: int, fh: vpe_feat, stream=None) -> int:
         return vpe_run_head(self.handle, head, fh, None if stream is None else stream.cuda_stream)
+
+    def run_head_latest(self, head: int, stream=None):
+        return vpe_run_head_latest(self.handle, head, None if stream is None else stream.cuda_stream)
+
+    def frame_ready(self, fh: vpe_feat) -> int:
+        return vpe_frame_ready(self.handle, fh)
+
+    def head_counters(self, head: int) -> dict:
+        return vpe_head_counters(self.handle, head)
 
     def next_encode_stream(self) -> Optional[int]:
         """Raw handle of the engine stream the next encode() without a stream argument will run on."""

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -78,6 +79,12 @@ struct Head {
     double period = 0.0;              // 1 / max_hz, 0 = no limit in Hz
     double due = 0.0;                 // frame time from which the next run is allowed
     bool due_set = false;
+    // lossy-freshness bookkeeping
+    int64_t seen = -1;                // newest frame this head has been asked about
+    int64_t last_run_frame = -1;
+    int64_t missed = 0;               // frames passed over because a newer one was taken
+    int64_t overflow = 0;             // frames overwritten in the ring before the head was asked about them
+    int64_t busy = 0;                 // vpe_run_head_latest calls turned away because the previous run was still going
     std::vector<hipGraphExec_t> graphs;   // per slot
 };
 
@@ -118,6 +125,8 @@ struct vpe_engine {
     std::vector<double> slot_time;       // its capture time, NaN = none given
     double last_time = 0.0;
     bool have_time = false;
+    bool wall_clock = false;             // frames without a time are stamped with the host's steady clock
+    std::chrono::steady_clock::time_point t0;
     std::vector<hipEvent_t> ready;       // [S]
     std::vector<hipEvent_t> done;        // [S][n_heads]
     std::vector<char> done_set;          // [S][n_heads]
@@ -640,7 +649,9 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     if (!v.empty() || !out) { g_create_error = v.empty() ? "out is null" : v; return VPE_EINVAL; }
     vpe_engine* e = new vpe_engine();
     derive(*e, *cfg, heads, n_heads);
-    e->host_only = (cfg->flags & 2) != 0;
+    e->host_only = (cfg->flags & VPE_FLAG_HOST_ONLY) != 0;
+    e->wall_clock = (cfg->flags & VPE_FLAG_WALL_CLOCK) != 0;
+    e->t0 = std::chrono::steady_clock::now();
     Bump measure;
     layout(*e, measure);
     const uint64_t need = (uint64_t)rup((int64_t)measure.off, 256);
@@ -755,6 +766,8 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
     if (!out) return e->fail(VPE_EINVAL, "out is null");
     if (!images && !e->host_only) return e->fail(VPE_EINVAL, "images is null");
     if (std::isinf(t_seconds)) return e->fail(VPE_EINVAL, "frame time is not finite");
+    if (std::isnan(t_seconds) && e->wall_clock)
+        t_seconds = std::max(e->last_time, std::chrono::duration<double>(std::chrono::steady_clock::now() - e->t0).count());
     if (!std::isnan(t_seconds)) {
         if (e->have_time && t_seconds < e->last_time) return e->fail(VPE_EINVAL, "frame time went backwards");
         e->last_time = t_seconds;
@@ -787,6 +800,10 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
         HIPCHK(e, hipEventRecord(e->ready[slot], s));
     }
     for (int h = 0; h < nh; ++h) e->done_set[(size_t)slot * nh + h] = 0;
+    // the ring overwrites its oldest frame; heads that never asked about it (or a later one) are told
+    if (e->slot_frame[slot] >= 0)
+        for (Head& h : e->heads)
+            if (h.seen < e->slot_frame[slot]) ++h.overflow;
     e->slot_frame[slot] = frame;
     e->slot_time[slot] = t_seconds;
     e->frames = frame + 1;
@@ -796,41 +813,109 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
     return VPE_OK;
 }
 
+namespace {
+// The limit in Hz: may a frame stamped t run, and if so move the due time on.
+bool hz_allows(Head& h, double t) {
+    if (!(h.period > 0.0) || std::isnan(t)) return true;
+    if (h.due_set && t < h.due - 1e-6 * h.period) return false;
+    // accumulate while the head keeps up; after a gap of more than a period start again from this frame
+    h.due = h.due_set && t - h.due < h.period ? h.due + h.period : t + h.period;
+    h.due_set = true;
+    return true;
+}
+
+// Enqueue one run of a head on the frame in `slot` (already checked to be current and due).
+int start_head(vpe_engine* e, int head, int slot, int64_t frame, void* stream) {
+    Head& h = e->heads[head];
+    const int nh = (int)e->heads.size();
+    if (!e->host_only) {
+        hipStream_t s = stream ? (hipStream_t)stream : h.stream;
+        HIPCHK(e, hipStreamWaitEvent(s, e->ready[slot], 0));
+        // the head's scratch and outputs are single-instance: order after its previous run
+        if (h.ran) HIPCHK(e, hipStreamWaitEvent(s, h.last_done, 0));
+        if (e->graphs) {
+            if (!h.graphs[slot])
+                TRY(capture(*e, &h.graphs[slot], [&](hipStream_t cs) { return enqueue_head_body(*e, h, slot, cs); }));
+            HIPCHK(e, hipGraphLaunch(h.graphs[slot], s));
+        } else {
+            TRY(enqueue_head_body(*e, h, slot, s));
+        }
+        hipEvent_t ev = e->done[(size_t)slot * nh + head];
+        HIPCHK(e, hipEventRecord(ev, s));
+        h.last_done = ev;
+    }
+    e->done_set[(size_t)slot * nh + head] = 1;
+    h.ran = true;
+    h.last_run_frame = frame;
+    ++h.runs;
+    return VPE_OK;
+}
+}  // namespace
+
 int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream) {
     if (!e) return VPE_EINVAL;
     if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
     if (fh.slot < 0 || fh.slot >= e->S || fh.frame < 0 || fh.frame >= e->frames || fh.frame % e->S != fh.slot)
         return e->fail(VPE_EINVAL, "feature handle was not produced by this engine");
     Head& h = e->heads[head];
+    h.seen = std::max(h.seen, fh.frame);
     if (fh.frame % h.every_n != 0) { ++h.skips; return VPE_SKIPPED; }
     if (e->slot_frame[fh.slot] != fh.frame) return e->fail(VPE_ESTALE, "slot has been reused by a later frame");
-    const double t = e->slot_time[fh.slot];
-    if (h.period > 0.0 && !std::isnan(t)) {
-        if (h.due_set && t < h.due - 1e-6 * h.period) { ++h.skips; return VPE_SKIPPED; }
-        // accumulate while the head keeps up; after a gap of more than a period start again from this frame
-        h.due = h.due_set && t - h.due < h.period ? h.due + h.period : t + h.period;
-        h.due_set = true;
+    if (!hz_allows(h, e->slot_time[fh.slot])) { ++h.skips; return VPE_SKIPPED; }
+    return start_head(e, head, fh.slot, fh.frame, stream);
+}
+
+int vpe_run_head_latest(vpe_engine* e, int head, void* stream, vpe_feat* ran_on) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    Head& h = e->heads[head];
+    if (e->frames - 1 <= h.seen) return VPE_SKIPPED;                 // nothing new since the head last asked
+    if (!e->host_only && h.ran) {
+        const hipError_t q = hipEventQuery(h.last_done);
+        if (q == hipErrorNotReady) { ++h.busy; return VPE_BUSY; }
+        HIPCHK(e, q);
     }
-    const int nh = (int)e->heads.size();
-    if (!e->host_only) {
-        hipStream_t s = stream ? (hipStream_t)stream : h.stream;
-        HIPCHK(e, hipStreamWaitEvent(s, e->ready[fh.slot], 0));
-        // the head's scratch and outputs are single-instance: order after its previous run
-        if (h.ran) HIPCHK(e, hipStreamWaitEvent(s, h.last_done, 0));
-        if (e->graphs) {
-            if (!h.graphs[fh.slot])
-                TRY(capture(*e, &h.graphs[fh.slot], [&](hipStream_t cs) { return enqueue_head_body(*e, h, fh.slot, cs); }));
-            HIPCHK(e, hipGraphLaunch(h.graphs[fh.slot], s));
-        } else {
-            TRY(enqueue_head_body(*e, h, fh.slot, s));
+    // newest frame that is still in the ring and whose features are complete on the device
+    int64_t newest = -1;
+    for (int64_t f = e->frames - 1; f > h.seen && f >= e->frames - e->S; --f) {
+        if (!e->host_only) {
+            const hipError_t q = hipEventQuery(e->ready[f % e->S]);
+            if (q == hipErrorNotReady) continue;
+            HIPCHK(e, q);
         }
-        hipEvent_t ev = e->done[(size_t)fh.slot * nh + head];
-        HIPCHK(e, hipEventRecord(ev, s));
-        h.last_done = ev;
+        newest = f;
+        break;
     }
-    e->done_set[(size_t)fh.slot * nh + head] = 1;
-    h.ran = true;
-    ++h.runs;
+    if (newest < 0) return VPE_SKIPPED;                              // the new frames are still being encoded
+    const int64_t skipped_over = newest - 1 - h.seen;                // frames between the last one asked about and this one
+    h.seen = newest;
+    h.missed += skipped_over;
+    const int slot = (int)(newest % e->S);
+    if (h.last_run_frame >= 0 && newest - h.last_run_frame < h.every_n) { ++h.skips; return VPE_SKIPPED; }
+    if (!hz_allows(h, e->slot_time[slot])) { ++h.skips; return VPE_SKIPPED; }
+    const int rc = start_head(e, head, slot, newest, stream);
+    if (rc == VPE_OK && ran_on) { ran_on->slot = slot; ran_on->reserved = 0; ran_on->frame = newest; }
+    return rc;
+}
+
+int vpe_frame_ready(vpe_engine* e, vpe_feat fh) {
+    if (!e) return VPE_EINVAL;
+    if (fh.slot < 0 || fh.slot >= e->S || fh.frame < 0 || fh.frame >= e->frames || fh.frame % e->S != fh.slot)
+        return e->fail(VPE_EINVAL, "feature handle was not produced by this engine");
+    if (e->slot_frame[fh.slot] != fh.frame) return VPE_ESTALE;
+    if (e->host_only) return VPE_OK;
+    const hipError_t q = hipEventQuery(e->ready[fh.slot]);
+    if (q == hipErrorNotReady) return VPE_BUSY;
+    HIPCHK(e, q);
+    return VPE_OK;
+}
+
+int vpe_head_counters(vpe_engine* e, int head, int64_t out[8]) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size() || !out) return e->fail(VPE_EINVAL, "unknown head or null output");
+    const Head& h = e->heads[head];
+    out[0] = h.runs; out[1] = h.skips; out[2] = h.missed; out[3] = h.overflow;
+    out[4] = h.busy; out[5] = h.last_run_frame; out[6] = h.seen; out[7] = 0;
     return VPE_OK;
 }
 

@@ -209,6 +209,91 @@ def test_rate_can_change_at_run_time():
         eng.set_head_rate(3, 1)
 
 
+def test_latest_frame_policy_takes_the_newest_and_counts_what_it_passed_over():
+    # the paper's decentralised modules (Sec. "Decentralization", "Data Flow"): a head that asks less often than
+    # frames arrive works on the newest one; the frames in between are lost to it and counted; the ring, which
+    # overwrites its oldest entry, reports the frames that left it without the head having asked
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg", "seg"), ring_slots=2, flags=vpe.VPE_FLAG_HOST_ONLY)
+    assert eng.run_head_latest(0) == (vpe.VPE_SKIPPED, None)          # nothing encoded yet
+    taken = []
+    for f in range(20):
+        fh = eng.encode(None)
+        assert eng.run_head(1, fh) == 0                               # head 1 keeps pace, frame by frame
+        if f % 5 == 4:                                                # head 0 asks after every 5th frame
+            rc, got = eng.run_head_latest(0)
+            assert rc == 0 and got.frame == f and got.slot == f % 2
+            taken.append(got.frame)
+            assert eng.run_head_latest(0) == (vpe.VPE_SKIPPED, None)  # same frame: nothing new
+    assert taken == [4, 9, 14, 19]
+    c0, c1 = eng.head_counters(0), eng.head_counters(1)
+    assert c0["runs"] == 4 and c0["missed"] == 16 and c0["last_run_frame"] == 19 and c0["seen"] == 19
+    # frames 0..17 were overwritten (2 slots): frame g leaves when frame g + 2 arrives, and counts for head 0
+    # unless the head had by then asked about g or a later frame
+    left_unasked = [g for g in range(18) if max([t for t in taken if t < g + 2], default=-1) < g]
+    assert c0["overflow"] == len(left_unasked) == 12
+    assert c1 == {"runs": 20, "skips": 0, "missed": 0, "overflow": 0, "busy": 0, "last_run_frame": 19, "seen": 19}
+    frames, runs, skips = eng.stats()
+    assert frames == 20 and runs == [4, 20] and skips == [0, 0]      # "nothing new" is not a rate skip
+
+
+def test_latest_frame_policy_respects_the_divider_and_the_limit_in_hz():
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg", "seg"), every_n=(3, 1), ring_slots=3,
+                            flags=vpe.VPE_FLAG_HOST_ONLY)
+    eng.set_head_rate_hz(1, 10.0)
+    ran = [[], []]
+    for f in range(90):                                               # 30 Hz for 3 s, both heads ask every frame
+        eng.encode(None, t=f / 30.0)
+        for h in range(2):
+            rc, got = eng.run_head_latest(h)
+            if rc == 0:
+                ran[h].append(got.frame)
+    assert ran[0] == list(range(0, 90, 3))                            # at least 3 frames apart
+    assert ran[1] == list(range(0, 90, 3))                            # 10 Hz out of 30 Hz
+    for h in range(2):
+        c = eng.head_counters(h)
+        assert c["missed"] == 0 and c["overflow"] == 0 and c["runs"] == 30 and c["skips"] == 60
+    # a head that asks only now and then still obeys its minimum distance, measured from its last run
+    eng.set_head_rate(0, 4)
+    got = []
+    for f in range(90, 110):
+        eng.encode(None, t=f / 30.0)
+        if f % 3 == 0:
+            rc, fh = eng.run_head_latest(0)
+            if rc == 0:
+                got.append(fh.frame)
+    assert got == [93, 99, 105]                                       # asks at 90, 93, ...: 93 - 87 >= 4, then every 6
+    f_new = eng.encode(None, t=4.0)
+    assert eng.frame_ready(f_new) == vpe.VPE_OK                       # no device: complete at once
+    assert eng.frame_ready(vpe.binding.vpe_feat(slot=(f_new.frame - 3) % 3, reserved=0, frame=f_new.frame - 3)) == vpe.VPE_ESTALE
+    with pytest.raises(vpe.VpeError, match="not produced"):
+        eng.frame_ready(vpe.binding.vpe_feat(slot=0, reserved=0, frame=1000))
+    with pytest.raises(vpe.VpeError, match="unknown head"):
+        eng.run_head_latest(2)
+    with pytest.raises(vpe.VpeError, match="unknown head"):
+        eng.head_counters(-1)
+
+
+def test_wall_clock_engine_limits_in_real_time():
+    import time
+    eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg", "seg"), flags=vpe.VPE_FLAG_HOST_ONLY | vpe.VPE_FLAG_WALL_CLOCK)
+    eng.set_head_rate_hz(0, 20.0)
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < 1.0:                             # about 1 s of frames every ~4 ms
+        fh = eng.encode(None)
+        eng.run_head(0, fh)
+        eng.run_head(1, fh)
+        n += 1
+        time.sleep(0.004)
+    span = time.perf_counter() - t0
+    c0, c1 = eng.head_counters(0), eng.head_counters(1)
+    assert c1["runs"] == n and n > 60
+    assert abs(c0["runs"] - 20.0 * span) <= 2.5, (c0, span)           # one run of slack each for start and end
+    # explicit times still work on such an engine, and must not run backwards against the clock
+    with pytest.raises(vpe.VpeError, match="backwards"):
+        eng.encode(None, t=0.0)
+
+
 def test_ring_overwrites_oldest_and_stale_handles_are_refused():
     eng, _, _ = make_engine(vi.small_spec(), 1, kinds=("seg",), ring_slots=2, flags=vpe.VPE_FLAG_HOST_ONLY)
     f0, f1 = eng.encode(None), eng.encode(None)

@@ -253,3 +253,48 @@ def test_rate_limit_in_hz_on_the_device():
     for a, b in zip(got, [exp[0][0], exp[0][1], exp[1][2], exp[2][3], exp[2][4]]):
         assert torch.equal(a, b)
     eng.close()
+
+
+def test_newest_frame_policy_on_the_device_never_queues_behind_a_running_head():
+    # a producer that stays at most one ring ahead of the device, every head asking for the newest complete frame
+    # after each: a call starts the head, is turned away because the previous run is still going, or finds no
+    # complete new frame; what a head holds at the end is the result of the last frame it reported, computed alone
+    fs = frames(4, seed=1000)
+    eng, _, _ = make_engine(SPEC, 22, flags=vpe.VPE_FLAG_GRAPHS, ring_slots=3, encoder_lanes=2)
+    n = 60
+    handles = []
+    ran = {0: [], 1: [], 2: []}
+
+    def poll():
+        for h in range(3):
+            rc, fh = eng.run_head_latest(h)
+            assert rc in (vpe.VPE_OK, vpe.VPE_BUSY, vpe.VPE_SKIPPED)
+            if rc == vpe.VPE_OK:
+                assert eng.frame_ready(fh) == vpe.VPE_OK
+                ran[h].append(fh.frame)
+
+    for i in range(n):
+        while i >= 2 and eng.frame_ready(handles[i - 2]) == vpe.VPE_BUSY:
+            poll()
+        handles.append(eng.encode(fs[i % 4]))
+        poll()
+    eng.sync()
+    assert eng.frame_ready(handles[-1]) == vpe.VPE_OK and eng.frame_ready(handles[0]) == vpe.VPE_ESTALE
+    poll()                                                             # idle now: every head takes frame n - 1 unless it has it
+    eng.sync()
+    got = outputs(eng)
+    for h in range(3):
+        c = eng.head_counters(h)
+        assert ran[h] == sorted(set(ran[h])) and ran[h][-1] == n - 1 and len(ran[h]) >= 2
+        assert c["runs"] == len(ran[h]) and c["skips"] == 0
+        assert c["last_run_frame"] == c["seen"] == n - 1
+        assert c["missed"] == n - c["runs"]                        # every frame either ran or was passed over
+    eng.close()
+    eng, _, _ = make_engine(SPEC, 22)
+    fh = eng.encode(fs[(n - 1) % 4])
+    for h in range(3):
+        eng.run_head(h, fh)
+    eng.sync()
+    for a, b in zip(got, outputs(eng)):
+        assert torch.equal(a, b)
+    eng.close()
