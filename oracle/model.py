@@ -159,3 +159,58 @@ def depth_head(spec, hw, feats, return_stages: bool = False) -> Dict[str, np.nda
         out["stages"] = stages
         out["d16"] = d
     return out
+
+
+def _rcu(x: np.ndarray, hw, name: str) -> np.ndarray:
+    """Residual convolution unit: x + conv3x3(ReLU(conv3x3(ReLU(x)))), both convolutions with bias."""
+    t = ops.conv3x3(np.maximum(x, 0.0), hw[name + "_c1_w"], hw[name + "_c1_b"], relu=True)
+    return x + ops.conv3x3(t, hw[name + "_c2_w"], hw[name + "_c2_b"])
+
+
+def dpt_head(spec, hw, feats, return_stages: bool = False) -> Dict[str, np.ndarray]:
+    """Dense-prediction-transformer depth head (the structure of the DepthAnythingV2 head that the paper's
+    example implementation runs, Sec. "Example implementation"), on one image's four feature maps.
+
+    Width F = head_ch; reassembled widths oc_i = (3 F / 4) 2^i.  Taps shallow -> deep, i = 0..3:
+      reassemble   p_i = 1x1 conv D -> oc_i of the patch grid of F_i; then
+                   r_0 = transposed conv (kernel = stride = 4) of p_0        -> 4 gh x 4 gw
+                   r_1 = transposed conv (kernel = stride = 2) of p_1        -> 2 gh x 2 gw
+                   r_2 = p_2                                                 ->   gh x   gw
+                   r_3 = 3x3 conv, stride 2, padding 1 of p_3                -> ceil(gh/2) x ceil(gw/2)
+      l_i = 3x3 conv oc_i -> F of r_i, no bias.
+    Fusion, deep -> shallow, k = 3..0, with s_3 = l_3 and s_k = path_{k+1} + RCU_a(l_k) for k < 3:
+      path_k = 1x1 conv F -> F of bilinear_aligned(RCU_b(s_k) -> size of l_{k-1}; for k = 0: twice its size).
+    Output: o = 3x3 conv F -> F/2 of path_0; u = bilinear_aligned(o -> H x W);
+      depth = ReLU(1x1 conv 32 -> 1 of ReLU(3x3 conv F/2 -> 32 of u)).
+    """
+    gh, gw = spec.gh, spec.gw
+    ls = []
+    for i in range(4):
+        p = ops.conv1x1(_grid(spec, feats[i]), hw[f"proj{i}_w"], hw[f"proj{i}_b"])
+        if i == 0:
+            r = ops.conv_transpose(p, hw["up0_w"], hw["up0_b"], 4)
+        elif i == 1:
+            r = ops.conv_transpose(p, hw["up1_w"], hw["up1_b"], 2)
+        elif i == 2:
+            r = p
+        else:
+            r = ops.conv3x3_s2(p, hw["down3_w"], hw["down3_b"])
+        ls.append(ops.conv3x3(r, hw[f"rn{i}_w"], None))
+    path = None
+    paths = []
+    for k in (3, 2, 1, 0):
+        s = ls[k] if path is None else path + _rcu(ls[k], hw, f"fuse{k}_a")
+        y = _rcu(s, hw, f"fuse{k}_b")
+        size = (ls[k - 1].shape[1], ls[k - 1].shape[2]) if k > 0 else (2 * y.shape[1], 2 * y.shape[2])
+        path = ops.conv1x1(ops.bilinear_ac(y, *size), hw[f"fuse{k}_out_w"], hw[f"fuse{k}_out_b"])
+        paths.append(path)
+    o = ops.conv3x3(path, hw["head1_w"], hw["head1_b"])
+    u = ops.bilinear_ac(o, spec.img_h, spec.img_w)
+    v = ops.conv3x3(u, hw["head2_w"], hw["head2_b"], relu=True)
+    pre = ops.conv1x1(v, hw["head3_w"], hw["head3_b"])[0]
+    out = {"depth": np.maximum(pre, 0.0), "pre_relu": pre}
+    if return_stages:
+        out["l"] = ls
+        out["paths"] = paths
+        out["o"] = o
+    return out

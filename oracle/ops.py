@@ -137,6 +137,36 @@ def bilinear(inp, H: int, W: int):
     return out
 
 
+def conv3x3_s2(inp, w, b):
+    inp, w = _d(inp), _d(w)
+    b = None if b is None else _d(b)
+    Cin, H, W = inp.shape
+    Cout = w.shape[0]
+    assert w.shape == (Cout, Cin, 3, 3)
+    out = np.empty((Cout, (H - 1) // 2 + 1, (W - 1) // 2 + 1))
+    lib().vo_conv3x3_s2(_p(inp), Cin, H, W, _p(w), _p(b), Cout, _p(out))
+    return out
+
+
+def conv_transpose(inp, w, b, stride: int):
+    inp, w = _d(inp), _d(w)
+    b = None if b is None else _d(b)
+    Cin, H, W = inp.shape
+    Cout = w.shape[1]
+    assert w.shape == (Cin, Cout, stride, stride)
+    out = np.empty((Cout, stride * H, stride * W))
+    lib().vo_conv_transpose(_p(inp), Cin, H, W, _p(w), _p(b), Cout, stride, _p(out))
+    return out
+
+
+def bilinear_ac(inp, H: int, W: int):
+    inp = _d(inp)
+    Cc, h, w = inp.shape
+    out = np.empty((Cc, H, W))
+    lib().vo_bilinear_ac(_p(inp), Cc, h, w, H, W, _p(out))
+    return out
+
+
 def argmax_channels(inp):
     inp = _d(inp)
     Cc = inp.shape[0]

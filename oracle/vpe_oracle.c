@@ -225,6 +225,72 @@ void vo_bilinear(const double* in, int C, int h, int w, int H, int W, double* ou
         }
 }
 
+/* 3x3 convolution, stride 2, zero padding 1: out[co][y][x] = b[co] + sum_{ci,ky,kx} w[co][ci][ky][kx] *
+ * in[ci][2y + ky - 1][2x + kx - 1] (terms outside the image are zero).  in [Cin][H][W] ->
+ * out [Cout][Ho][Wo] with Ho = floor((H - 1) / 2) + 1, Wo likewise. */
+void vo_conv3x3_s2(const double* in, int Cin, int H, int W, const double* w, const double* b, int Cout, double* out) {
+    const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int co = 0; co < Cout; ++co)
+        for (int y = 0; y < Ho; ++y)
+            for (int x = 0; x < Wo; ++x) {
+                double acc = b ? b[co] : 0.0;
+                for (int ci = 0; ci < Cin; ++ci)
+                    for (int ky = 0; ky < 3; ++ky)
+                        for (int kx = 0; kx < 3; ++kx) {
+                            const int sy = 2 * y + ky - 1, sx = 2 * x + kx - 1;
+                            if (sy < 0 || sy >= H || sx < 0 || sx >= W) continue;
+                            acc += w[((size_t)(co * Cin + ci) * 3 + ky) * 3 + kx] * in[((size_t)ci * H + sy) * W + sx];
+                        }
+                out[((size_t)co * Ho + y) * Wo + x] = acc;
+            }
+}
+
+/* Transposed convolution whose kernel size equals its stride s (no overlap, no padding): every input pixel
+ * paints its own s x s block,  out[co][s y + dy][s x + dx] = b[co] + sum_ci in[ci][y][x] * w[ci][co][dy][dx].
+ * in [Cin][H][W], w [Cin][Cout][s][s] (input channel first, as transposed convolutions are stored),
+ * out [Cout][s H][s W]. */
+void vo_conv_transpose(const double* in, int Cin, int H, int W, const double* w, const double* b, int Cout, int s,
+                       double* out) {
+#pragma omp parallel for schedule(static)
+    for (int co = 0; co < Cout; ++co)
+        for (int y = 0; y < H; ++y)
+            for (int x = 0; x < W; ++x)
+                for (int dy = 0; dy < s; ++dy)
+                    for (int dx = 0; dx < s; ++dx) {
+                        double acc = b ? b[co] : 0.0;
+                        for (int ci = 0; ci < Cin; ++ci)
+                            acc += in[((size_t)ci * H + y) * W + x] * w[(((size_t)ci * Cout + co) * s + dy) * s + dx];
+                        out[((size_t)co * s * H + (size_t)s * y + dy) * s * W + (size_t)s * x + dx] = acc;
+                    }
+}
+
+/* Bilinear resize with aligned corners: output sample y sits at source coordinate sy = y (h - 1) / (H - 1)
+ * (0 when H == 1), so the four corner samples are copied and the rest interpolate linearly between the two
+ * nearest source rows / columns.  in [C][h][w] -> out [C][H][W]. */
+void vo_bilinear_ac(const double* in, int C, int h, int w, int H, int W, double* out) {
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < C; ++c)
+        for (int y = 0; y < H; ++y) {
+            const double sy = H > 1 ? (double)y * (double)(h - 1) / (double)(H - 1) : 0.0;
+            int y0 = (int)floor(sy);
+            if (y0 > h - 1) y0 = h - 1;
+            const int y1 = y0 + 1 < h ? y0 + 1 : h - 1;
+            const double a = sy - y0;
+            for (int x = 0; x < W; ++x) {
+                const double sx = W > 1 ? (double)x * (double)(w - 1) / (double)(W - 1) : 0.0;
+                int x0 = (int)floor(sx);
+                if (x0 > w - 1) x0 = w - 1;
+                const int x1 = x0 + 1 < w ? x0 + 1 : w - 1;
+                const double bx = sx - x0;
+                const double* p = in + (size_t)c * h * w;
+                const double top = (1.0 - bx) * p[(size_t)y0 * w + x0] + bx * p[(size_t)y0 * w + x1];
+                const double bot = (1.0 - bx) * p[(size_t)y1 * w + x0] + bx * p[(size_t)y1 * w + x1];
+                out[((size_t)c * H + y) * W + x] = (1.0 - a) * top + a * bot;
+            }
+        }
+}
+
 /* Channel argmax, ties to the lowest index.  in [C][HW] -> out [HW] (int32). */
 void vo_argmax_channels(const double* in, int C, int64_t HW, int32_t* out) {
 #pragma omp parallel for schedule(static)

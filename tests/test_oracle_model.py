@@ -266,6 +266,78 @@ def test_depth_head_stage_structure():
     assert relerr(out2["stages"][3]["p"], out["stages"][3]["p"]) > 1e-3
 
 
+def _torch_dpt(spec, hw, feats):
+    """The DPT head written a second time with library layers (torch fp64)."""
+    c = lambda name, x, **kw: F.conv2d(x, T64(hw[name + "_w"]), T64(hw[name + "_b"]) if name + "_b" in hw else None, **kw)
+    one = lambda name, x: F.conv2d(x, T64(hw[name + "_w"])[:, :, None, None], T64(hw[name + "_b"]))
+    rcu = lambda name, x: x + c(name + "_c2", F.relu(c(name + "_c1", F.relu(x), padding=1)), padding=1)
+    p = [one(f"proj{i}", _torch_grid(spec, feats[i])) for i in range(4)]
+    r = [F.conv_transpose2d(p[0], T64(hw["up0_w"]), T64(hw["up0_b"]), stride=4),
+         F.conv_transpose2d(p[1], T64(hw["up1_w"]), T64(hw["up1_b"]), stride=2),
+         p[2], c("down3", p[3], stride=2, padding=1)]
+    l = [c(f"rn{i}", r[i], padding=1) for i in range(4)]
+    path = None
+    for k in (3, 2, 1, 0):
+        s_ = l[k] if path is None else path + rcu(f"fuse{k}_a", l[k])
+        y = rcu(f"fuse{k}_b", s_)
+        y = F.interpolate(y, size=l[k - 1].shape[2:], mode="bilinear", align_corners=True) if k else \
+            F.interpolate(y, scale_factor=2, mode="bilinear", align_corners=True)
+        path = one(f"fuse{k}_out", y)
+    u = F.interpolate(c("head1", path, padding=1), size=(spec.img_h, spec.img_w), mode="bilinear", align_corners=True)
+    return F.relu(one("head3", F.relu(c("head2", u, padding=1))))[0, 0], l, path
+
+
+@pytest.mark.parametrize("hw_px", [(28, 42), (42, 70)])
+def test_dpt_head_equals_library_composition(hw_px):
+    spec = vi.ModelSpec("dpt", dim=32, depth=4, heads=2, mlp_hidden=48, img_h=hw_px[0], img_w=hw_px[1], dtype="f32",
+                        taps=(1, 2, 3, 4), head_ch=16, head_dim=16)
+    w = boost(vi.make_backbone_weights(spec, 71))
+    hp = boost(vi.make_head_weights(spec, vi.HEAD_DPT, 71))
+    feats = model.encode_image(spec, w, vi.make_image(*hw_px, 72))
+    out = model.dpt_head(spec, hp, feats, return_stages=True)
+    tdepth, tl, tpath = _torch_dpt(spec, hp, [T64(f) for f in feats])
+    gh, gw = spec.gh, spec.gw
+    want = [(4 * gh, 4 * gw), (2 * gh, 2 * gw), (gh, gw), ((gh + 1) // 2, (gw + 1) // 2)]
+    for i in range(4):
+        assert out["l"][i].shape == (16,) + want[i]
+        assert relerr(out["l"][i], tl[i][0].numpy()) < 1e-12
+    assert out["paths"][-1].shape == (16, 8 * gh, 8 * gw) and relerr(out["paths"][-1], tpath[0].numpy()) < 1e-12
+    assert out["depth"].shape == hw_px and relerr(out["depth"], tdepth.numpy()) < 1e-12
+    assert out["depth"].min() >= 0.0 and out["depth"].max() > 0.0
+
+
+def test_dpt_head_structure():
+    spec = _spec(registers=2, head_ch=16)
+    w = boost(vi.make_backbone_weights(spec, 81))
+    hp = dict(boost(vi.make_head_weights(spec, vi.HEAD_DPT, 81)))
+    feats = model.encode_image(spec, w, vi.make_image(28, 42, 82))
+    base = model.dpt_head(spec, hp, feats, return_stages=True)
+    # CLS and register rows are not read
+    feats2 = [f.copy() for f in feats]
+    for f in feats2:
+        f[:3] += 5.0
+    assert relerr(model.dpt_head(spec, hp, feats2)["depth"], base["depth"]) == 0.0
+    # tap i feeds level i only: the deepest tap alone decides l_3
+    feats3 = [f.copy() for f in feats]
+    feats3[0][3:] += 1.0
+    moved = model.dpt_head(spec, hp, feats3, return_stages=True)
+    assert relerr(moved["l"][3], base["l"][3]) == 0.0 and relerr(moved["l"][0], base["l"][0]) > 1e-3
+    # with the second convolution of every residual unit switched off the units are identities, and the
+    # deepest path is the 1x1 convolution of the aligned resize of l_3 (the two commute: both are linear maps
+    # with weights summing to one along space)
+    for k, v in hp.items():
+        if "_c2_" in k:
+            hp[k] = np.zeros_like(v)
+    ident = model.dpt_head(spec, hp, feats, return_stages=True)
+    l3 = ident["l"][3]
+    a = ops.conv1x1(ops.bilinear_ac(l3, spec.gh, spec.gw), hp["fuse3_out_w"], hp["fuse3_out_b"])
+    b = ops.bilinear_ac(ops.conv1x1(l3, hp["fuse3_out_w"], hp["fuse3_out_b"]), spec.gh, spec.gw)
+    assert relerr(ident["paths"][0], a) == 0.0 and relerr(a, b) < 1e-12
+    # and the next path is the same map of (path_3 + l_2)
+    c = ops.conv1x1(ops.bilinear_ac(ident["paths"][0] + ident["l"][2], 2 * spec.gh, 2 * spec.gw), hp["fuse2_out_w"], hp["fuse2_out_b"])
+    assert relerr(ident["paths"][1], c) < 1e-13
+
+
 def test_heads_ignore_cls_and_register_rows():
     spec = _spec(registers=2)
     w = boost(vi.make_backbone_weights(spec, 61))

@@ -221,6 +221,67 @@ def test_bilinear_properties():
     close(line, np.array([0.0, 1.0, 3.0, 4.0]), 1e-15)
 
 
+# ---------------------------------------------------------------- operators of the full DPT head
+@pytest.mark.parametrize("H,W", [(7, 9), (8, 6), (1, 5), (34, 45)])
+def test_conv3x3_stride2_matches_library(H, W):
+    x, w, b = RNG.normal(size=(5, H, W)), RNG.normal(size=(4, 5, 3, 3)), RNG.normal(size=4)
+    ref = F.conv2d(T64(x)[None], T64(w), T64(b), stride=2, padding=1)[0].numpy()
+    close(ops.conv3x3_s2(x, w, b), ref, 1e-13)
+    assert ops.conv3x3_s2(x, w, b).shape == (4, (H + 1) // 2, (W + 1) // 2)
+
+
+def test_conv3x3_stride2_hand_cases():
+    x = np.arange(30.0).reshape(1, 5, 6)
+    delta = np.zeros((1, 1, 3, 3)); delta[0, 0, 1, 1] = 1.0
+    close(ops.conv3x3_s2(x, delta, None), x[:, ::2, ::2], 0.0)                 # centre tap: every second pixel
+    right = np.zeros((1, 1, 3, 3)); right[0, 0, 1, 2] = 1.0                     # tap (0, +1): in[2y][2x + 1]
+    close(ops.conv3x3_s2(x, right, None), x[:, ::2, 1::2], 0.0)
+    up = np.zeros((1, 1, 3, 3)); up[0, 0, 0, 1] = 1.0                           # tap (-1, 0): zero above the image
+    exp = np.zeros((1, 3, 3)); exp[0, 1:] = x[0, 1:4:2, ::2]
+    close(ops.conv3x3_s2(x, up, None), exp, 0.0)
+    ones = ops.conv3x3_s2(np.ones((2, 4, 4)), np.ones((1, 2, 3, 3)), np.array([0.5]))
+    close(ones, np.array([[[8.5, 12.5], [12.5, 18.5]]]), 0.0)                   # neighbours inside the image, x 2 channels
+
+
+@pytest.mark.parametrize("s", [2, 4])
+def test_conv_transpose_matches_library(s):
+    x, w, b = RNG.normal(size=(5, 3, 4)), RNG.normal(size=(5, 6, s, s)), RNG.normal(size=6)
+    ref = F.conv_transpose2d(T64(x)[None], T64(w), T64(b), stride=s)[0].numpy()
+    close(ops.conv_transpose(x, w, b, s), ref, 1e-13)
+
+
+def test_conv_transpose_paints_one_block_per_pixel():
+    x = np.zeros((2, 3, 3)); x[1, 2, 0] = 2.0
+    w = RNG.normal(size=(2, 3, 4, 4))
+    out = ops.conv_transpose(x, w, None, 4)
+    exp = np.zeros((3, 12, 12)); exp[:, 8:12, 0:4] = 2.0 * w[1]                 # input channel 1 -> all outputs
+    close(out, exp, 0.0)
+    close(ops.conv_transpose(np.zeros((2, 2, 2)), w, np.array([1.0, 2.0, 3.0]), 4)[:, 3, 5], np.array([1.0, 2.0, 3.0]), 0.0)
+
+
+@pytest.mark.parametrize("h,w,H,W", [(3, 4, 6, 8), (17, 23, 34, 45), (16, 24, 14, 21), (5, 7, 5, 7), (2, 2, 7, 5), (4, 4, 1, 1), (1, 1, 3, 3)])
+def test_bilinear_aligned_corners_matches_library(h, w, H, W):
+    x = RNG.normal(size=(3, h, w))
+    ref = F.interpolate(T64(x)[None], size=(H, W), mode="bilinear", align_corners=True)[0].numpy()
+    close(ops.bilinear_ac(x, H, W), ref, 1e-13)
+
+
+def test_bilinear_aligned_corners_properties():
+    x = RNG.normal(size=(2, 5, 6))
+    up = ops.bilinear_ac(x, 13, 16)
+    close(up[:, [0, 0, -1, -1], [0, -1, 0, -1]], x[:, [0, 0, -1, -1], [0, -1, 0, -1]], 0.0)     # corners are copied
+    close(ops.bilinear_ac(x, 5, 6), x, 1e-15)
+    close(ops.bilinear_ac(x, 9, 11)[:, ::2, ::2], x, 1e-15)                     # 2 n - 1 samples contain the source
+    # an affine ramp is reproduced exactly everywhere (no clamping region with aligned corners)
+    yy, xx = np.meshgrid(np.arange(5.0), np.arange(6.0), indexing="ij")
+    ramp = (2.0 * yy - 3.0 * xx + 1.0)[None]
+    sy, sx = np.arange(13) * 4.0 / 12.0, np.arange(16) * 5.0 / 15.0
+    close(ops.bilinear_ac(ramp, 13, 16)[0], 2.0 * sy[:, None] - 3.0 * sx[None, :] + 1.0, 1e-14)
+    close(ops.bilinear_ac(np.array([[[0.0, 3.0]]]), 1, 4)[0, 0], np.array([0.0, 1.0, 2.0, 3.0]), 1e-15)
+    # it differs from the half-pixel resize (which repeats the border)
+    assert np.max(np.abs(ops.bilinear_ac(x, 10, 12) - ops.bilinear(x, 10, 12))) > 1e-2
+
+
 def test_argmax_channels_ties_go_to_lowest_index():
     x = np.array([[[1.0, 5.0]], [[3.0, 5.0]], [[3.0, 2.0]]])        # [C=3][1][2]
     out = ops.argmax_channels(x)

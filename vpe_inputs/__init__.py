@@ -37,6 +37,7 @@ MLP_SWIGLU = 1
 HEAD_SEG = 0
 HEAD_DEPTH = 1
 HEAD_DET = 2
+HEAD_DPT = 3
 
 
 @dataclass(frozen=True)
@@ -185,6 +186,26 @@ def head_layout(spec: ModelSpec, kind: int) -> List[Tuple[str, Tuple[int, ...]]]
         for s in range(4):
             out += [(f"fuse{s}_w", (Ch, Ch, 3, 3)), (f"fuse{s}_b", (Ch,))]
         out += [("out_w", (1, Ch)), ("out_b", (1,))]
+        return out
+    if kind == HEAD_DPT:
+        F = Ch
+        oc = [3 * F // 4 << i for i in range(4)]
+        out = []
+        for i in range(4):   # i = 0 is the shallowest tap
+            out += [(f"proj{i}_w", (oc[i], D)), (f"proj{i}_b", (oc[i],))]
+        out += [("up0_w", (oc[0], oc[0], 4, 4)), ("up0_b", (oc[0],)),       # transposed convolutions: [Cin][Cout][k][k]
+                ("up1_w", (oc[1], oc[1], 2, 2)), ("up1_b", (oc[1],)),
+                ("down3_w", (oc[3], oc[3], 3, 3)), ("down3_b", (oc[3],))]
+        for i in range(4):
+            out += [(f"rn{i}_w", (F, oc[i], 3, 3))]
+        for k in (3, 2, 1, 0):
+            for unit in (("b",) if k == 3 else ("a", "b")):
+                for c in ("c1", "c2"):
+                    out += [(f"fuse{k}_{unit}_{c}_w", (F, F, 3, 3)), (f"fuse{k}_{unit}_{c}_b", (F,))]
+            out += [(f"fuse{k}_out_w", (F, F)), (f"fuse{k}_out_b", (F,))]
+        out += [("head1_w", (F // 2, F, 3, 3)), ("head1_b", (F // 2,)),
+                ("head2_w", (32, F // 2, 3, 3)), ("head2_b", (32,)),
+                ("head3_w", (1, 32)), ("head3_b", (1,))]
         return out
     raise ValueError(f"unknown head kind {kind}")
 
