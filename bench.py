@@ -200,6 +200,10 @@ def main() -> None:
     ap.add_argument("--hw-queues", type=int, default=5,
                     help="hardware queues the HIP runtime may use in this process (GPU_MAX_HW_QUEUES; the default "
                          "stream keeps one, the engine's lanes + head streams want four); 0 = leave the environment alone")
+    ap.add_argument("--heads", default=None,
+                    help="comma-separated head kinds in place of the workload's own (seg,depth,det): e.g. seg,dpt,det runs "
+                         "the full DPT depth head (--head-ch sets its width); not the headline workload")
+    ap.add_argument("--head-ch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--roofline-only", action="store_true",
@@ -241,6 +245,10 @@ def main() -> None:
     spec = vi.CONFIGS[args.config]
     wseed, iseed = vi.SEEDS[args.config]
     kinds = ("seg",) if args.config == "cfg1" else ("seg", "depth", "det")
+    if args.heads:
+        kinds = tuple(args.heads.split(","))
+    if args.head_ch:
+        spec = vi.with_(spec, head_ch=args.head_ch)
     flags = 0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS
     eng, w, hw = make_engine(spec, wseed, kinds=kinds, ring_slots=args.ring_slots, flags=flags, encoder_lanes=args.encoder_lanes)
     images_np = vi.make_batch(spec, iseed)
@@ -344,7 +352,7 @@ def main() -> None:
         t0 = time.perf_counter()
         feats = model.encode_image(spec, w, images_np[0])
         for k, hwd in zip(kinds, hw):
-            {"seg": model.seg_head, "depth": model.depth_head, "det": model.det_head}[k](spec, hwd, feats)
+            {"seg": model.seg_head, "depth": model.depth_head, "det": model.det_head, "dpt": model.dpt_head}[k](spec, hwd, feats)
         dt = time.perf_counter() - t0
         cpu_baseline = {"value": round(1.0 / dt, 5), "unit": "frames/s", "cores": ops.num_threads(), "kind": "oracle",
                         "sample": f"1 frame (batch element 0) of {spec.name}, encoder + {nh} head(s), {dt:.1f} s"}

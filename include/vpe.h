@@ -42,7 +42,7 @@ typedef enum { VPE_OK = 0, VPE_SKIPPED = 1, VPE_BUSY = 2, VPE_EINVAL = -1, VPE_E
                VPE_EHIP = -4 } vpe_status;
 typedef enum { VPE_F32 = 0, VPE_BF16 = 1 } vpe_dtype;
 typedef enum { VPE_MLP_GELU = 0, VPE_MLP_SWIGLU = 1 } vpe_mlp;
-typedef enum { VPE_HEAD_SEG = 0, VPE_HEAD_DEPTH = 1, VPE_HEAD_DET = 2 } vpe_head_kind;
+typedef enum { VPE_HEAD_SEG = 0, VPE_HEAD_DEPTH = 1, VPE_HEAD_DET = 2, VPE_HEAD_DPT = 3 } vpe_head_kind;
 
 enum {
     VPE_FLAG_GRAPHS = 1,     /* replay the encoder and the heads as captured HIP graphs */
@@ -114,12 +114,29 @@ typedef struct {
  *                  weights: proj{0..3}_w [ch][dim], proj{s}_b [ch] (pairs, s ascending), then
  *                  fuse{0..3}_w [ch][ch][3][3], fuse{s}_b [ch] (pairs), out_w [1][ch], out_b [1].
  *                  outputs: 0 = depth fp32 [B][img_h][img_w].
+ *   VPE_HEAD_DPT   the full dense-prediction-transformer depth head (the structure of the DepthAnythingV2 head
+ *                  of the paper's example implementation), width F = channels (64, 128, 192 or 256), reassembled
+ *                  widths oc_i = (3 F / 4) 2^i; feature map i = 0..3 (shallow to deep) is level i:
+ *                    reassemble: 1x1 conv dim->oc_i, then level 0: transposed conv kernel = stride = 4; level 1:
+ *                      transposed conv kernel = stride = 2; level 2: nothing; level 3: 3x3 conv stride 2 padding 1;
+ *                      then 3x3 conv oc_i->F without bias, giving l_i on the 4x, 2x, 1x, ceil(1/2)x patch grid;
+ *                    fusion, k = 3..0: s_3 = l_3, s_k = path_{k+1} + unit(l_k); path_k = 1x1 conv F->F of the
+ *                      bilinear resize with aligned corners of unit(s_k) to level k-1's grid (k = 0: to twice its
+ *                      own); unit(x) = x + conv3x3(ReLU(conv3x3(ReLU(x)))), both with bias;
+ *                    output: 3x3 conv F->F/2 of path_0, aligned-corner bilinear to img_h x img_w, 3x3 conv
+ *                      F/2->32 + ReLU, 1x1 conv 32->1, ReLU.
+ *                  weights: proj{0..3}_w [oc_i][dim], proj{i}_b (pairs); up0_w [oc_0][oc_0][4][4] (input channel
+ *                  first), up0_b; up1_w [oc_1][oc_1][2][2], up1_b; down3_w [oc_3][oc_3][3][3], down3_b;
+ *                  rn{0..3}_w [F][oc_i][3][3]; for k = 3, 2, 1, 0: (k < 3: unit a: c1_w [F][F][3][3], c1_b, c2_w,
+ *                  c2_b,) unit b: c1_w, c1_b, c2_w, c2_b, out_w [F][F], out_b; head1_w [F/2][F][3][3], head1_b;
+ *                  head2_w [32][F/2][3][3], head2_b; head3_w [1][32], head3_b [1].
+ *                  outputs: 0 = depth fp32 [B][img_h][img_w].
  *   every_n >= 1: the head runs on frame f iff f % every_n == 0 (paper, Sec. "Dynamic Frequency Control").
  */
 typedef struct {
     int32_t kind;         /* vpe_head_kind */
-    int32_t classes;      /* seg: C; det: number of object classes; depth: ignored */
-    int32_t channels;     /* det / depth hidden width (multiple of 64); seg: ignored */
+    int32_t classes;      /* seg: C; det: number of object classes; depth, dpt: ignored */
+    int32_t channels;     /* det / depth / dpt hidden width (multiple of 64; dpt: at most 256); seg: ignored */
     int32_t every_n;
     const void* weights;  /* host, fp32 */
     uint64_t weights_bytes;

@@ -15,7 +15,7 @@ import numpy as np
 VPE_OK, VPE_SKIPPED, VPE_BUSY, VPE_EINVAL, VPE_ENOMEM, VPE_ESTALE, VPE_EHIP = 0, 1, 2, -1, -2, -3, -4
 VPE_F32, VPE_BF16 = 0, 1
 VPE_MLP_GELU, VPE_MLP_SWIGLU = 0, 1
-VPE_HEAD_SEG, VPE_HEAD_DEPTH, VPE_HEAD_DET = 0, 1, 2
+VPE_HEAD_SEG, VPE_HEAD_DEPTH, VPE_HEAD_DET, VPE_HEAD_DPT = 0, 1, 2, 3
 VPE_FLAG_GRAPHS, VPE_FLAG_HOST_ONLY, VPE_FLAG_WALL_CLOCK = 1, 2, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -360,7 +360,7 @@ class Engine:
         kind = self.head_arr[head].kind
         is_map = which == 1 and kind in (VPE_HEAD_SEG, VPE_HEAD_DET)
         shape = [s for s in shape]
-        while len(shape) > 1 and shape[-1] == 1 and len(shape) > (3 if (is_map or kind == VPE_HEAD_DEPTH) else 4):
+        while len(shape) > 1 and shape[-1] == 1 and len(shape) > (3 if (is_map or kind in (VPE_HEAD_DEPTH, VPE_HEAD_DPT)) else 4):
             shape.pop()
         return self._as_tensor(ptr, shape, torch.uint8 if is_map else torch.float32)
 

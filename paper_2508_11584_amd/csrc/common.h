@@ -17,6 +17,10 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int WAVE = 64;
 
+// Source position of one output row (or column) of an aligned-corner bilinear resize, sy = y (in - 1) / (out - 1):
+// lower tap and the weight of the upper one (i0 + 1, clamped to the last sample).
+struct AcTap { int i0; float w1; };
+
 // One 16-byte chunk holds CE elements of T.
 template <typename T> struct Elem;
 template <> struct Elem<bf16>  { static constexpr int CE = 8; };

@@ -51,8 +51,38 @@ struct BlockW {
     void *qkv_w, *proj_w, *fc1_w, *fc2_w;
 };
 
+struct ConvW { void* w = nullptr; float* b = nullptr; };
+
+// State of a full DPT head (reassemble -> fusion with residual convolution units -> output convolutions).
+// Maps are pixel-major with the channel count rounded up to 64 (`ocp`, `hp`); the padding channels are zero
+// (the workspace is cleared at creation and nothing writes them) and meet zero weight columns.
+struct Dpt {
+    int F = 0, oc[4] = {}, ocp[4] = {}, hh[4] = {}, ww[4] = {}, hp = 0;   // level i: oc[i] channels on an hh[i] x ww[i] grid
+    // levels 0 and 1: tap projection and transposed convolution (kernel = stride s) composed into s*s matrices
+    // [oc][D], one per position (dy, dx) inside the s x s block, with their biases
+    void* up_w[2] = {};
+    float* up_b[2] = {};
+    ConvW proj[2];                 // taps 2 and 3
+    ConvW down3, rn[4];
+    ConvW fa1[4], fa2[4], fb1[4], fb2[4], fout[4];   // per level k: residual units a (k < 3) and b, output 1x1
+    ConvW head1, head2;
+    float* head3_w = nullptr;      // [64], 32 in use
+    float head3_b = 0.0f;
+    // activations
+    void* R[4] = {};               // reassembled maps [n_i][ocp_i]
+    void *P3 = nullptr, *G3 = nullptr;
+    float* L[4] = {};              // l_i in fp32 (residual operand)
+    void* Lr[4] = {};              // ReLU(l_i) in the engine dtype (convolution operand)
+    void *t = nullptr, *sr = nullptr, *y = nullptr, *c = nullptr, *path0 = nullptr, *o1 = nullptr, *u = nullptr;
+    float *s = nullptr, *path[2] = {}, *dpart = nullptr;
+    void* ty[5] = {};              // aligned-corner tap tables of the five resizes (rows, columns)
+    void* tx[5] = {};
+    int rh[5] = {}, rw[5] = {};    // their output sizes
+};
+
 struct Head {
     int kind = 0, classes = 0, ch = 0, every_n = 1;
+    Dpt dpt;
     // weights
     void* w0 = nullptr;            // seg: [C][D]; det: towers [2ch][9D]; depth: unused
     float* b0 = nullptr;
@@ -162,6 +192,15 @@ int64_t head_floats(const vpe_backbone_cfg& c, const vpe_head_cfg& h) {
         case VPE_HEAD_SEG: return (int64_t)h.classes * D + h.classes;
         case VPE_HEAD_DET: return 2 * (ch * D * 9 + ch) + (int64_t)h.classes * ch + h.classes + 4 * ch + 4;
         case VPE_HEAD_DEPTH: return 4 * (ch * D + ch) + 4 * (ch * ch * 9 + ch) + ch + 1;
+        case VPE_HEAD_DPT: {
+            const int64_t F = ch, oc0 = 3 * F / 4;
+            int64_t n = 0;
+            for (int i = 0; i < 4; ++i) n += (oc0 << i) * D + (oc0 << i);                   // tap projections
+            n += oc0 * oc0 * 16 + oc0 + 4 * oc0 * oc0 * 4 + 2 * oc0 + 64 * oc0 * oc0 * 9 + 8 * oc0;   // up0, up1, down3
+            for (int i = 0; i < 4; ++i) n += F * (oc0 << i) * 9;                            // l_i convolutions, no bias
+            n += 14 * (F * F * 9 + F) + 4 * (F * F + F);                                    // 7 residual units, 4 output 1x1
+            return n + (F / 2) * F * 9 + F / 2 + 32 * (F / 2) * 9 + 32 + 32 + 1;
+        }
     }
     return -1;
 }
@@ -197,9 +236,11 @@ std::string validate(const vpe_backbone_cfg* c, const vpe_head_cfg* heads, int n
     }
     for (int i = 0; i < n_heads; ++i) {
         const vpe_head_cfg& h = heads[i];
-        if (h.kind != VPE_HEAD_SEG && h.kind != VPE_HEAD_DEPTH && h.kind != VPE_HEAD_DET) return "unknown head kind";
+        if (h.kind != VPE_HEAD_SEG && h.kind != VPE_HEAD_DEPTH && h.kind != VPE_HEAD_DET && h.kind != VPE_HEAD_DPT)
+            return "unknown head kind";
+        if (h.kind == VPE_HEAD_DPT && h.channels > 256) return "a DPT head takes channels in 64..256";
         if (h.every_n < 1) return "every_n must be >= 1";
-        if (h.kind != VPE_HEAD_DEPTH && (h.classes < 1 || h.classes > 256)) return "classes must be in 1..256";
+        if ((h.kind == VPE_HEAD_SEG || h.kind == VPE_HEAD_DET) && (h.classes < 1 || h.classes > 256)) return "classes must be in 1..256";
         if (h.kind != VPE_HEAD_SEG && (h.channels < 64 || h.channels % 64 || h.channels > 1024))
             return "channels must be a multiple of 64 in 64..1024";
         if (!h.weights) return "head weights pointer is null";
@@ -233,6 +274,22 @@ void derive(vpe_engine& e, const vpe_backbone_cfg& c, const vpe_head_cfg* heads,
         e.heads[i].classes = heads[i].classes;
         e.heads[i].ch = heads[i].channels;
         e.heads[i].every_n = heads[i].every_n;
+        if (heads[i].kind == VPE_HEAD_DPT) {
+            Dpt& d = e.heads[i].dpt;
+            d.F = heads[i].channels;
+            d.hp = (int)rup(d.F / 2, 64);
+            for (int k = 0; k < 4; ++k) {
+                d.oc[k] = (3 * d.F / 4) << k;
+                d.ocp[k] = (int)rup(d.oc[k], 64);
+            }
+            const int gh = c.img_h / 14, gw = c.img_w / 14;
+            const int hh[4] = {4 * gh, 2 * gh, gh, (gh + 1) / 2}, ww[4] = {4 * gw, 2 * gw, gw, (gw + 1) / 2};
+            for (int k = 0; k < 4; ++k) { d.hh[k] = hh[k]; d.ww[k] = ww[k]; }
+            // resizes: after the fusion stage of level 3, 2, 1 to the next level's grid, after level 0 to twice
+            // its grid, and the output map to the image
+            const int rh[5] = {gh, 2 * gh, 4 * gh, 8 * gh, c.img_h}, rw[5] = {gw, 2 * gw, 4 * gw, 8 * gw, c.img_w};
+            for (int k = 0; k < 5; ++k) { d.rh[k] = rh[k]; d.rw[k] = rw[k]; }
+        }
     }
 }
 
@@ -242,6 +299,11 @@ double head_flops(const vpe_engine& e, const Head& h) {
     switch (h.kind) {
         case VPE_HEAD_SEG: return P * e.D * h.classes;
         case VPE_HEAD_DET: return P * (9.0 * e.D * 2 * h.ch + 2.0 * h.ch * (h.classes + 4));
+        case VPE_HEAD_DPT: {
+            const double F = h.ch;
+            // residual units on the 1/4, 1, 4, 16 grids, the output convolutions on the 64x and 196x grids
+            return P * (7.5 * e.D * F + 9.0 * F * F * (2 * 0.25 + 4 * 1 + 4 * 4 + 4 * 16) + 9.0 * F * F / 2 * 64 + 9.0 * 64 * 64 * 196);
+        }
         default: return P * (4.0 * e.D * h.ch + 85.0 * 9 * h.ch * h.ch);   // four 3x3 stages on 1 + 4 + 16 + 64 grids
     }
 }
@@ -296,6 +358,42 @@ void layout(vpe_engine& e, Bump& b) {
             h.tower = b.take(BP * 2 * ch * esz);
             h.logits = f32(BP * (h.classes + 4));
             h.classmap = (uint8_t*)b.take(BP);
+        } else if (h.kind == VPE_HEAD_DPT) {
+            Dpt& d = h.dpt;
+            const uint64_t F = d.F;
+            auto conv = [&](ConvW& c, int n_out, uint64_t k, bool bias = true) {
+                c.w = b.take(wrows(n_out) * k * esz);
+                c.b = bias ? f32(rup(n_out, 64)) : nullptr;
+            };
+            d.up_w[0] = b.take(16 * wrows(d.oc[0]) * D * esz); d.up_b[0] = f32(16 * d.oc[0]);
+            d.up_w[1] = b.take(4 * wrows(d.oc[1]) * D * esz); d.up_b[1] = f32(4 * d.oc[1]);
+            conv(d.proj[0], d.oc[2], D); conv(d.proj[1], d.oc[3], D);
+            conv(d.down3, d.oc[3], 9 * d.ocp[3]);
+            for (int i = 0; i < 4; ++i) conv(d.rn[i], d.F, 9 * d.ocp[i], false);
+            for (int k = 3; k >= 0; --k) {
+                if (k < 3) { conv(d.fa1[k], d.F, 9 * F); conv(d.fa2[k], d.F, 9 * F); }
+                conv(d.fb1[k], d.F, 9 * F); conv(d.fb2[k], d.F, 9 * F);
+                conv(d.fout[k], d.F, F);
+            }
+            conv(d.head1, d.F / 2, 9 * F);
+            conv(d.head2, 64, 9 * d.hp);
+            d.head3_w = f32(64);
+            uint64_t n[4];
+            for (int i = 0; i < 4; ++i) n[i] = B * d.hh[i] * d.ww[i];
+            const uint64_t n_out = B * d.rh[3] * d.rw[3], n_img = B * e.H * e.W;
+            for (int i = 0; i < 4; ++i) d.R[i] = b.take(n[i] * d.ocp[i] * esz);
+            d.P3 = b.take(BP * d.ocp[3] * esz);
+            d.G3 = b.take(n[3] * 9 * d.ocp[3] * esz);
+            for (int i = 0; i < 4; ++i) { d.L[i] = f32(n[i] * F); d.Lr[i] = b.take(n[i] * F * esz); }
+            d.t = b.take(n[0] * F * esz); d.sr = b.take(n[0] * F * esz);
+            d.y = b.take(n[0] * F * esz); d.c = b.take(n[0] * F * esz);
+            d.s = f32(n[0] * F); d.path[0] = f32(n[0] * F); d.path[1] = f32(n[0] * F);
+            d.path0 = b.take(n_out * F * esz);
+            d.o1 = b.take(n_out * d.hp * esz);
+            d.u = b.take(n_img * d.hp * esz);
+            d.dpart = f32(n_img);
+            h.depth = f32(n_img);
+            for (int r = 0; r < 5; ++r) { d.ty[r] = b.take(8 * (uint64_t)d.rh[r]); d.tx[r] = b.take(8 * (uint64_t)d.rw[r]); }
         } else {
             for (int s = 0; s < 4; ++s) { h.proj_w[s] = b.take(wrows(h.ch) * D * esz); h.proj_b[s] = f32(ch); }
             for (int s = 0; s < 4; ++s) { h.fuse_w[s] = b.take(wrows(h.ch) * 9 * ch * esz); h.fuse_b[s] = f32(ch); }
@@ -323,11 +421,27 @@ struct Uploader {
     // tensor of `count` floats -> dst rows/cols via relayout_kernel (see rowops.h)
     int relayout(int64_t count, void* dst, int n_rows, int n_cols, int64_t rs, int64_t cs, int mode, int cin,
                  int swiglu_half, int64_t dst_ld, int row_off, int col_off, const float* kscale = nullptr) {
-        HIPCHK(e, hipMemcpy(staging, take(count), 4 * count, hipMemcpyHostToDevice));
+        return relayout_host(take(count), count, dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld, row_off,
+                             col_off, kscale);
+    }
+    // the same from any host array (a tensor derived from the blob's)
+    int relayout_host(const float* src, int64_t count, void* dst, int n_rows, int n_cols, int64_t rs, int64_t cs, int mode,
+                      int cin, int swiglu_half, int64_t dst_ld, int row_off, int col_off, const float* kscale = nullptr) {
+        HIPCHK(e, hipMemcpy(staging, src, 4 * count, hipMemcpyHostToDevice));
         HIPCHK(e, launch_relayout(e->bf, staging, dst, n_rows, n_cols, rs, cs, mode, cin, swiglu_half, dst_ld,
                                   row_off, col_off, kscale, nullptr));
         HIPCHK(e, hipStreamSynchronize(nullptr));
         return 0;
+    }
+    // 3x3 kernel [n_out][cin][3][3] -> [n_out][9 cpad], column tap * cpad + ci; bias (may be absent) -> b
+    int conv3(const ConvW& c, int n_out, int cin, int cpad, bool bias = true) {
+        if (relayout((int64_t)n_out * cin * 9, c.w, n_out, 9 * cin, 0, cpad, 1, cin, 0, 9 * (int64_t)cpad, 0, 0)) return 1;
+        return bias ? f32(c.b, n_out) : 0;
+    }
+    // 1x1 kernel [n_out][cin] with bias
+    int conv1(const ConvW& c, int n_out, int cin) {
+        if (relayout((int64_t)n_out * cin, c.w, n_out, cin, cin, 1, 0, 0, 0, cin, 0, 0)) return 1;
+        return f32(c.b, n_out);
     }
     // y = x W + b weights stored [in][out]  ->  [out][in]
     int linear(void* dst, int in, int out, int swiglu_half = 0, const float* kscale = nullptr) {
@@ -415,6 +529,63 @@ int upload_head(vpe_engine& e, Head& h, const float* blob, int64_t n, float* sta
         TRY(up.f32(h.b1, h.classes));
         TRY(up.relayout((int64_t)4 * ch, h.w1, 4, ch, ch, 1, 0, 0, 0, 2 * ch, h.classes, ch));
         TRY(up.f32(h.b1 + h.classes, 4));
+    } else if (h.kind == VPE_HEAD_DPT) {
+        Dpt& d = h.dpt;
+        const int F = d.F;
+        const float *pw[2], *pb[2];
+        for (int i = 0; i < 2; ++i) { pw[i] = up.take((int64_t)d.oc[i] * D); pb[i] = up.take(d.oc[i]); }
+        TRY(up.conv1(d.proj[0], d.oc[2], D));
+        TRY(up.conv1(d.proj[1], d.oc[3], D));
+        // levels 0 and 1: out[(s y + dy, s x + dx)][co] = ub[co] + sum_ci uw[ci][co][dy][dx] (pb[ci] + sum_d pw[ci][d] x[d]):
+        // one [oc][D] matrix and one bias vector per (dy, dx), composed here in double
+        for (int i = 0; i < 2; ++i) {
+            const int st = i == 0 ? 4 : 2, oc = d.oc[i];
+            const float* uw = up.take((int64_t)oc * oc * st * st);
+            const float* ub = up.take(oc);
+            std::vector<double> acc((size_t)D);
+            std::vector<float> wz((size_t)oc * D), bz((size_t)oc);
+            const int64_t zstride = rup(oc, NPAD) * (int64_t)D * e.esz;
+            for (int z = 0; z < st * st; ++z) {
+                for (int co = 0; co < oc; ++co) {
+                    std::fill(acc.begin(), acc.end(), 0.0);
+                    double bb = ub[co];
+                    for (int ci = 0; ci < oc; ++ci) {
+                        const double u = uw[((int64_t)ci * oc + co) * st * st + z];
+                        bb += u * pb[i][ci];
+                        const float* row = pw[i] + (int64_t)ci * D;
+                        for (int k = 0; k < D; ++k) acc[k] += u * row[k];
+                    }
+                    for (int k = 0; k < D; ++k) wz[(size_t)co * D + k] = (float)acc[k];
+                    bz[co] = (float)bb;
+                }
+                TRY(up.relayout_host(wz.data(), (int64_t)oc * D, (char*)d.up_w[i] + z * zstride, oc, D, D, 1, 0, 0, 0, D, 0, 0));
+                HIPCHK(&e, hipMemcpy(d.up_b[i] + (int64_t)z * oc, bz.data(), 4 * (size_t)oc, hipMemcpyHostToDevice));
+            }
+        }
+        TRY(up.conv3(d.down3, d.oc[3], d.oc[3], d.ocp[3]));
+        for (int i = 0; i < 4; ++i) TRY(up.conv3(d.rn[i], F, d.oc[i], d.ocp[i], false));
+        for (int k = 3; k >= 0; --k) {
+            if (k < 3) { TRY(up.conv3(d.fa1[k], F, F, F)); TRY(up.conv3(d.fa2[k], F, F, F)); }
+            TRY(up.conv3(d.fb1[k], F, F, F)); TRY(up.conv3(d.fb2[k], F, F, F));
+            TRY(up.conv1(d.fout[k], F, F));
+        }
+        TRY(up.conv3(d.head1, F / 2, F, F));
+        TRY(up.conv3(d.head2, 32, F / 2, d.hp));
+        TRY(up.f32(d.head3_w, 32));
+        d.head3_b = *up.take(1);
+        // aligned-corner taps: output index y of `out` samples sits at y (in - 1) / (out - 1)
+        const int in_h[5] = {d.hh[3], d.hh[2], d.hh[1], d.hh[0], d.rh[3]}, in_w[5] = {d.ww[3], d.ww[2], d.ww[1], d.ww[0], d.rw[3]};
+        for (int r = 0; r < 5; ++r)
+            for (int axis = 0; axis < 2; ++axis) {
+                const int in = axis ? in_w[r] : in_h[r], out = axis ? d.rw[r] : d.rh[r];
+                std::vector<AcTap> tab((size_t)out);
+                for (int y = 0; y < out; ++y) {
+                    const int64_t num = (int64_t)y * (in - 1), den = out > 1 ? out - 1 : 1;
+                    tab[y].i0 = (int)std::min<int64_t>(num / den, in - 1);
+                    tab[y].w1 = (float)((double)(num % den) / (double)den);
+                }
+                HIPCHK(&e, hipMemcpy(axis ? d.tx[r] : d.ty[r], tab.data(), sizeof(AcTap) * tab.size(), hipMemcpyHostToDevice));
+            }
     } else {
         for (int s = 0; s < 4; ++s) {
             TRY(up.relayout((int64_t)ch * D, h.proj_w[s], ch, D, D, 1, 0, 0, 0, D, 0, 0));
@@ -532,9 +703,95 @@ GemmArgs conv3_gemm(vpe_engine& e, const void* in, int C, int B, int h, int w, i
     return a;
 }
 
+// Full DPT head (see Dpt).  The residual trunk (l_i, the sums s_k, the paths) is kept in fp32 and added in the
+// convolution epilogues; convolution operands are copies in the engine dtype, written through ReLU where the
+// next convolution wants that.  The 1x1 output convolution of a fusion stage runs before the resize (on the
+// smaller grid): both are linear and the resize weights sum to one, so the order only changes rounding.
+int enqueue_dpt(vpe_engine& e, Head& h, int slot, hipStream_t s) {
+    Dpt& d = h.dpt;
+    const int dt = e.bf, BP = e.B * e.P, F = d.F, B = e.B;
+    void* const* f = &e.feat[slot * 4];
+    auto conv = [&](const void* in, int cin_pad, int lvl_h, int lvl_w, const ConvW& w, int n_out, int act) {
+        GemmArgs a = conv3_gemm(e, in, cin_pad, B, lvl_h, lvl_w, lvl_h * lvl_w, 0, w.w, w.b, n_out);
+        a.act = act;
+        return a;
+    };
+    // reassemble, levels 0 and 1: one batched launch each, problem z = (dy, dx) writes pixel (s y + dy, s x + dx)
+    for (int i = 0; i < 2; ++i) {
+        const int st = i == 0 ? 4 : 2, oc = d.oc[i], cp = d.ocp[i];
+        GemmArgs a = tokens_gemm(e, f[i], d.up_w[i], d.up_b[i], oc);
+        a.out = d.R[i]; a.ldo = (int64_t)st * cp;                  // consecutive grid columns are st pixels apart
+        a.o_rpi = e.gw; a.o_istride = e.gw * st; a.o_off = 0;      // consecutive grid rows st pixel rows apart
+        a.nz = st * st; a.z_a = 0; a.z_w = rup(oc, NPAD) * (int64_t)e.D * e.esz; a.z_bias = oc;
+        a.z_inner = st; a.z_out = (int64_t)cp * e.esz; a.z_out2 = (int64_t)e.gw * st * cp * e.esz;
+        HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+    }
+    {   // level 2: the projection itself; level 3: projection, then 3x3 stride 2 as gather + GEMM
+        GemmArgs a = tokens_gemm(e, f[2], d.proj[0].w, d.proj[0].b, d.oc[2]);
+        a.out = d.R[2]; a.ldo = d.ocp[2];
+        HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
+        GemmArgs p3 = tokens_gemm(e, f[3], d.proj[1].w, d.proj[1].b, d.oc[3]);
+        p3.out = d.P3; p3.ldo = d.ocp[3];
+        HIPCHK(&e, launch_gemm(dt, p3, A_PLAIN, s));
+        HIPCHK(&e, launch_gather3x3s2(dt, d.P3, B, e.gh, e.gw, d.ocp[3], d.G3, s));
+        GemmArgs g = plain_gemm(d.G3, 9 * (int64_t)d.ocp[3], d.down3.w, d.down3.b, B * d.hh[3] * d.ww[3], d.oc[3], 9 * d.ocp[3]);
+        g.out = d.R[3]; g.ldo = d.ocp[3];
+        HIPCHK(&e, launch_gemm(dt, g, A_PLAIN, s));
+    }
+    for (int i = 0; i < 4; ++i) {   // l_i = 3x3 conv to F channels: fp32 trunk + ReLU copy
+        GemmArgs a = conv(d.R[i], d.ocp[i], d.hh[i], d.ww[i], d.rn[i], F, ACT_NONE);
+        a.out = d.L[i]; a.out_f32 = 1; a.ldo = F; a.twin = d.Lr[i]; a.twin_relu = 1;
+        HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
+    }
+    const float* path = nullptr;
+    for (int k = 3; k >= 0; --k) {
+        const int hk = d.hh[k], wk = d.ww[k], r = 3 - k;
+        const float* trunk = d.L[k];
+        const void* trunk_relu = d.Lr[k];
+        if (k < 3) {   // s_k = path + unit_a(l_k)
+            GemmArgs c1 = conv(d.Lr[k], F, hk, wk, d.fa1[k], F, ACT_RELU);
+            c1.out = d.t; c1.ldo = F;
+            HIPCHK(&e, launch_gemm(dt, c1, A_CONV3, s));
+            GemmArgs c2 = conv(d.t, F, hk, wk, d.fa2[k], F, ACT_NONE);
+            c2.out = d.s; c2.out_f32 = 1; c2.ldo = F; c2.add1 = d.L[k]; c2.add2 = path; c2.twin = d.sr; c2.twin_relu = 1;
+            HIPCHK(&e, launch_gemm(dt, c2, A_CONV3, s));
+            trunk = d.s;
+            trunk_relu = d.sr;
+        }
+        GemmArgs c1 = conv(trunk_relu, F, hk, wk, d.fb1[k], F, ACT_RELU);
+        c1.out = d.t; c1.ldo = F;
+        HIPCHK(&e, launch_gemm(dt, c1, A_CONV3, s));
+        GemmArgs c2 = conv(d.t, F, hk, wk, d.fb2[k], F, ACT_NONE);      // unit_b(s_k), only needed as an operand
+        c2.out = d.y; c2.ldo = F; c2.add1 = trunk;
+        HIPCHK(&e, launch_gemm(dt, c2, A_CONV3, s));
+        GemmArgs o = plain_gemm(d.y, F, d.fout[k].w, d.fout[k].b, B * hk * wk, F, F);
+        o.out = d.c; o.ldo = F;
+        HIPCHK(&e, launch_gemm(dt, o, A_PLAIN, s));
+        if (k > 0) {
+            float* next = d.path[k & 1];
+            HIPCHK(&e, launch_resize_ac(dt, 1, d.c, B, hk, wk, F, F, d.ty[r], d.tx[r], d.rh[r], d.rw[r], F, next, s));
+            path = next;
+        } else {
+            HIPCHK(&e, launch_resize_ac(dt, 0, d.c, B, hk, wk, F, F, d.ty[r], d.tx[r], d.rh[r], d.rw[r], F, d.path0, s));
+        }
+    }
+    GemmArgs h1 = conv(d.path0, F, d.rh[3], d.rw[3], d.head1, F / 2, ACT_NONE);
+    h1.out = d.o1; h1.ldo = d.hp;
+    HIPCHK(&e, launch_gemm(dt, h1, A_CONV3, s));
+    HIPCHK(&e, launch_resize_ac(dt, 0, d.o1, B, d.rh[3], d.rw[3], d.hp, F / 2, d.ty[4], d.tx[4], e.H, e.W, d.hp, d.u, s));
+    // last 3x3 (ReLU) with the 32 -> 1 projection taken in its epilogue; rows 32..63 of the weight are zero
+    GemmArgs h2 = conv(d.u, d.hp, e.H, e.W, d.head2, 64, ACT_RELU);
+    h2.epi = EPI_ROWDOT; h2.gamma = d.head3_w; h2.out = d.dpart; h2.ldo = 1;
+    HIPCHK(&e, launch_gemm(dt, h2, A_CONV3, s));
+    HIPCHK(&e, launch_rowsum_relu(d.dpart, 1, d.head3_b, (int64_t)B * e.H * e.W, h.depth, s));
+    (void)BP;
+    return 0;
+}
+
 int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
     const int dt = e.bf, BP = e.B * e.P;
     void* const* f = &e.feat[slot * 4];
+    if (h.kind == VPE_HEAD_DPT) return enqueue_dpt(e, h, slot, s);
     if (h.kind == VPE_HEAD_SEG) {
         GemmArgs a = tokens_gemm(e, f[3], h.w0, h.b0, h.classes);
         a.out = h.logits; a.ldo = h.classes; a.out_f32 = 1;
@@ -692,6 +949,9 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     int64_t big = (int64_t)e->D * std::max({3 * e->D, e->F, e->Mh, KPATCH});
     for (auto& h : e->heads) big = std::max<int64_t>(big, (int64_t)h.ch * 9 * std::max(e->D, h.ch));
     for (auto& h : e->heads) big = std::max<int64_t>(big, (int64_t)h.classes * e->D);
+    for (auto& h : e->heads)
+        if (h.kind == VPE_HEAD_DPT)
+            big = std::max<int64_t>({big, (int64_t)h.dpt.oc[3] * h.dpt.oc[3] * 9, (int64_t)h.dpt.oc[3] * e->D});
     float* staging = nullptr;
     if (hip(hipMalloc((void**)&staging, 4 * big), "hipMalloc(staging)")) return bail(VPE_ENOMEM);
     int rc = upload_backbone(*e, (const float*)cfg->weights, staging);
@@ -957,7 +1217,7 @@ int vpe_head_output(vpe_engine* e, int head, int which, const void** dev_ptr, in
     else if (h.kind == VPE_HEAD_SEG && which == 1) { *dev_ptr = h.classmap; shape[1] = e->H; shape[2] = e->W; }
     else if (h.kind == VPE_HEAD_DET && which == 0) { *dev_ptr = h.logits; shape[1] = e->gh; shape[2] = e->gw; shape[3] = h.classes + 4; }
     else if (h.kind == VPE_HEAD_DET && which == 1) { *dev_ptr = h.classmap; shape[1] = e->gh; shape[2] = e->gw; }
-    else if (h.kind == VPE_HEAD_DEPTH && which == 0) { *dev_ptr = h.depth; shape[1] = e->H; shape[2] = e->W; }
+    else if ((h.kind == VPE_HEAD_DEPTH || h.kind == VPE_HEAD_DPT) && which == 0) { *dev_ptr = h.depth; shape[1] = e->H; shape[2] = e->W; }
     else return e->fail(VPE_EINVAL, "this head has no such output");
     return VPE_OK;
 }

@@ -59,10 +59,20 @@ struct GemmArgs {
     void* xb_out;
     float* st_out;
     const float* xb_level;     // xb_out holds x - xb_level[row] (null: 0); statistics are of x itself
+    // STORE only (N and ldo multiples of 8): fp32 tensors added after the activation, read through the output
+    // row map with the output's row pitch (null: none); and a second copy of the result in T, optionally
+    // through ReLU (the operand of a following convolution), same map and pitch (null: none)
+    const float* add1;
+    const float* add2;
+    void* twin;
+    int twin_relu;
     // batch of nz independent problems of the same shape in one launch (blockIdx.y = z): problem z uses
-    // A + z * z_a, W + z * z_w, out + z * z_out (byte strides, may be negative) and bias + z * z_bias (elements)
+    // A + z * z_a, W + z * z_w, out + z * z_out (byte strides, may be negative) and bias + z * z_bias (elements);
+    // with z_inner > 0 the output alone is addressed in two levels, out + (z % z_inner) * z_out + (z / z_inner) * z_out2
     int nz;
     int64_t z_a, z_w, z_out, z_bias;
+    int z_inner;
+    int64_t z_out2;
 };
 
 // The arguments of problem blockIdx.y of a batched launch (a plain copy when the launch is not batched).
@@ -71,7 +81,8 @@ __device__ __forceinline__ GemmArgs select_problem(const GemmArgs& in) {
     const int64_t z = blockIdx.y;
     p.A = reinterpret_cast<const char*>(in.A) + z * in.z_a;
     p.W = reinterpret_cast<const char*>(in.W) + z * in.z_w;
-    p.out = reinterpret_cast<char*>(in.out) + z * in.z_out;
+    p.out = in.z_inner > 0 ? reinterpret_cast<char*>(in.out) + (z % in.z_inner) * in.z_out + (z / in.z_inner) * in.z_out2
+                           : reinterpret_cast<char*>(in.out) + z * in.z_out;
     if (in.bias) p.bias = in.bias + z * in.z_bias;
     return p;
 }
@@ -183,6 +194,24 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& p, int r, int c, 
             for (int i = 0; i < 8; ++i) v[i] = gelu_erf(v[i]);
         }
         const int64_t orow = (int64_t)(r / p.o_rpi) * p.o_istride + p.o_off + r % p.o_rpi;
+        if (p.add1) {
+            const float* a = p.add1 + orow * p.ldo + c;
+            const f32x4 a0 = *reinterpret_cast<const f32x4*>(a), a1 = *reinterpret_cast<const f32x4*>(a + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[i] += a0[i]; v[4 + i] += a1[i]; }
+        }
+        if (p.add2) {
+            const float* a = p.add2 + orow * p.ldo + c;
+            const f32x4 a0 = *reinterpret_cast<const f32x4*>(a), a1 = *reinterpret_cast<const f32x4*>(a + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[i] += a0[i]; v[4 + i] += a1[i]; }
+        }
+        if (p.twin) {
+            float t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t[i] = p.twin_relu ? fmaxf(v[i], 0.0f) : v[i];
+            store8(reinterpret_cast<T*>(p.twin) + orow * p.ldo + c, t);
+        }
         if (p.out_f32) {
             float* dst = reinterpret_cast<float*>(p.out) + orow * p.ldo + c;
             if (nv == 8 && (p.ldo & 3) == 0) store8(dst, v);

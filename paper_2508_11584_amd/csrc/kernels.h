@@ -32,6 +32,13 @@ hipError_t launch_seg_upsample_argmax(const float* logits, int B, int gh, int gw
 hipError_t launch_depth_output(const float* d, int nparts, float bias, int B, int h8, int w8,
                                int H, int W, float* depth, hipStream_t s);
 
+// Operators of the full DPT head; `tables` are AcTap arrays on the device (see resize.h).
+// out_f32 != 0: fp32 output from an input in the engine dtype.  C multiple of 8, pitches multiples of 8.
+hipError_t launch_resize_ac(int dtype, int out_f32, const void* src, int B, int h, int w, int ld_in, int C,
+                            const void* ty, const void* tx, int H, int W, int ld_out, void* dst, hipStream_t s);
+hipError_t launch_gather3x3s2(int dtype, const void* src, int B, int h, int w, int ld, void* dst, hipStream_t s);
+hipError_t launch_rowsum_relu(const float* d, int nparts, float bias, int64_t n, float* depth, hipStream_t s);
+
 hipError_t launch_preprocess_u8(const uint8_t* src, int B, int sh, int sw, int H, int W, const float* mean,
                                 const float* stdev, float* dst, hipStream_t s);
 

@@ -254,6 +254,69 @@ __global__ __launch_bounds__(256) void depth_output_kernel(const float* __restri
     depth[idx] = fmaxf((1.0f - ty.w1) * top + ty.w1 * bot, 0.0f);
 }
 
+// ---- operators of the full DPT head (maps are pixel-major: [B][h][w][ld] with C <= ld channels in use) ----
+
+// Bilinear resize with aligned corners, TI -> TO, 8 channels per thread.  The tap tables (AcTap per output
+// row and per output column) are filled on the host in exact integer arithmetic when the engine is created.
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void resize_ac_kernel(const TI* __restrict__ src, int B, int h, int w, int ld_in, int C,
+                                                        const AcTap* __restrict__ ty, const AcTap* __restrict__ tx,
+                                                        int H, int W, int ld_out, TO* __restrict__ dst) {
+    const int cgs = C >> 3;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)B * H * W * cgs) return;
+    const int cg = (int)(idx % cgs);
+    const int64_t pix = idx / cgs;
+    const int x = (int)(pix % W), y = (int)((pix / W) % H), b = (int)(pix / ((int64_t)W * H));
+    const AcTap a = ty[y], c = tx[x];
+    const int y1 = a.i0 + 1 < h ? a.i0 + 1 : h - 1, x1 = c.i0 + 1 < w ? c.i0 + 1 : w - 1;
+    const TI* base = src + (int64_t)b * h * w * ld_in + cg * 8;
+    float v00[8], v01[8], v10[8], v11[8], o[8];
+    auto load = [&](int yy, int xx, float* v) {
+        const TI* q = base + ((int64_t)yy * w + xx) * ld_in;
+#pragma unroll
+        for (int i = 0; i < 8; i += Elem<TI>::CE) Vec<TI, Elem<TI>::CE>::load(q + i, v + i);
+    };
+    load(a.i0, c.i0, v00); load(a.i0, x1, v01); load(y1, c.i0, v10); load(y1, x1, v11);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float top = (1.0f - c.w1) * v00[i] + c.w1 * v01[i], bot = (1.0f - c.w1) * v10[i] + c.w1 * v11[i];
+        o[i] = (1.0f - a.w1) * top + a.w1 * bot;
+    }
+    TO* out = dst + pix * ld_out + cg * 8;
+#pragma unroll
+    for (int i = 0; i < 8; i += Elem<TO>::CE) Vec<TO, Elem<TO>::CE>::store(out + i, o + i);
+}
+
+// Operand of a 3x3 convolution with stride 2 and padding 1, gathered: dst [B ho wo][9 ld] with column
+// tap * ld + c = src[b][2 y + tap / 3 - 1][2 x + tap % 3 - 1][c] (zero outside the image); 16-byte chunks.
+template <typename T>
+__global__ __launch_bounds__(256) void gather3x3s2_kernel(const T* __restrict__ src, int B, int h, int w, int ld,
+                                                          int ho, int wo, T* __restrict__ dst) {
+    constexpr int CE = Elem<T>::CE;
+    const int chunks = ld / CE;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)B * ho * wo * 9 * chunks) return;
+    const int ch = (int)(idx % chunks), tap = (int)((idx / chunks) % 9);
+    const int64_t pix = idx / (9 * chunks);
+    const int x = (int)(pix % wo), y = (int)((pix / wo) % ho), b = (int)(pix / ((int64_t)wo * ho));
+    const int sy = 2 * y + tap / 3 - 1, sx = 2 * x + tap % 3 - 1;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (sy >= 0 && sy < h && sx >= 0 && sx < w)
+        v = ld_global_16(src + (((int64_t)b * h + sy) * w + sx) * ld + ch * CE);
+    *reinterpret_cast<u32x4*>(dst + (pix * 9 + tap) * ld + ch * CE) = v;
+}
+
+// depth[i] = max(bias + sum of the nparts partial projections of pixel i, 0).
+__global__ __launch_bounds__(256) void rowsum_relu_kernel(const float* __restrict__ d, int nparts, float bias, int64_t n,
+                                                          float* __restrict__ depth) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n) return;
+    float v = bias;
+    for (int k = 0; k < nparts; ++k) v += d[idx * nparts + k];
+    depth[idx] = fmaxf(v, 0.0f);
+}
+
 // Camera-frame transform (paper, Sec. "Transforms": type conversion, resizing and normalisation in front of
 // the foundation model): src uint8 [B][sh][sw][3] interleaved RGB -> dst fp32 [B][3][H][W] with
 //   dst[c] = (bilinear(src[..., c] / 255 : sh x sw -> H x W) - mean[c]) / std[c],

@@ -104,7 +104,8 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float* __restrict__ i
 
 // Weight re-layout at engine creation: dst[(row_off + n)][col_off + k] = src element (n, k).
 //   mode 0: src index = n * rs + k * cs                       (any strided 2-D view)
-//   mode 1: src is a conv kernel [n][cin][3][3]; k = tap * cin + ci -> src[(n * cin + ci) * 9 + tap]
+//   mode 1: src is a conv kernel [n][cin][3][3]; k = tap * cin + ci -> src[(n * cin + ci) * 9 + tap], written to
+//           column tap * cs + ci when cs > 0 (channel pitch of a zero-padded operand), else to column k
 //   swiglu != 0: physical row n reads logical row  32 (n / 64) + n % 64          if n % 64 < 32
 //                                                  half + 32 (n / 64) + n % 64 - 32   otherwise
 //   kscale != null: element (n, k) is multiplied by kscale[k] before rounding (a LayerNorm gain folded in)
@@ -124,12 +125,14 @@ __global__ __launch_bounds__(256) void relayout_kernel(const float* __restrict__
     const int n = (int)(idx / n_cols), k = (int)(idx % n_cols);
     const int nl = swiglu_row(n, swiglu_half);
     int64_t si;
+    int kd = k;
     if (mode == 0) si = nl * rs + k * cs;
     else {
         const int tap = k / cin, ci = k % cin;
         si = ((int64_t)nl * cin + ci) * 9 + tap;
+        if (cs > 0) kd = tap * (int)cs + ci;
     }
-    dst[(int64_t)(row_off + n) * dst_ld + col_off + k] = from_f32<T>(kscale ? src[si] * kscale[k] : src[si]);
+    dst[(int64_t)(row_off + n) * dst_ld + col_off + kd] = from_f32<T>(kscale ? src[si] * kscale[k] : src[si]);
 }
 
 // Companion of a re-layout with a folded LayerNorm (y = LN(x) W + b with gain g and shift beta):

@@ -86,6 +86,31 @@ hipError_t launch_depth_output(const float* d, int nparts, float bias, int B, in
     return hipGetLastError();
 }
 
+hipError_t launch_resize_ac(int dtype, int out_f32, const void* src, int B, int h, int w, int ld_in, int C,
+                            const void* ty, const void* tx, int H, int W, int ld_out, void* dst, hipStream_t s) {
+    if (C % 8 || ld_in % 8 || ld_out % 8 || C > ld_in || C > ld_out) return hipErrorInvalidValue;
+    const dim3 grid(blocks_for((int64_t)B * H * W * (C / 8), 256)), block(256);
+    const AcTap *a = (const AcTap*)ty, *b = (const AcTap*)tx;
+    if (!dtype) hipLaunchKernelGGL((resize_ac_kernel<float, float>), grid, block, 0, s, (const float*)src, B, h, w, ld_in, C, a, b, H, W, ld_out, (float*)dst);
+    else if (out_f32) hipLaunchKernelGGL((resize_ac_kernel<bf16, float>), grid, block, 0, s, (const bf16*)src, B, h, w, ld_in, C, a, b, H, W, ld_out, (float*)dst);
+    else hipLaunchKernelGGL((resize_ac_kernel<bf16, bf16>), grid, block, 0, s, (const bf16*)src, B, h, w, ld_in, C, a, b, H, W, ld_out, (bf16*)dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather3x3s2(int dtype, const void* src, int B, int h, int w, int ld, void* dst, hipStream_t s) {
+    if (ld % 8) return hipErrorInvalidValue;
+    const int ho = (h - 1) / 2 + 1, wo = (w - 1) / 2 + 1;
+    const int64_t n = (int64_t)B * ho * wo * 9 * (ld / (dtype ? 8 : 4));
+    if (dtype) hipLaunchKernelGGL(gather3x3s2_kernel<bf16>, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const bf16*)src, B, h, w, ld, ho, wo, (bf16*)dst);
+    else hipLaunchKernelGGL(gather3x3s2_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const float*)src, B, h, w, ld, ho, wo, (float*)dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_rowsum_relu(const float* d, int nparts, float bias, int64_t n, float* depth, hipStream_t s) {
+    hipLaunchKernelGGL(rowsum_relu_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, d, nparts, bias, n, depth);
+    return hipGetLastError();
+}
+
 hipError_t launch_preprocess_u8(const uint8_t* src, int B, int sh, int sw, int H, int W, const float* mean,
                                 const float* stdev, float* dst, hipStream_t s) {
     Affine3 a;

@@ -6,7 +6,7 @@ import numpy as np
 import paper_2508_11584_amd as vpe
 import vpe_inputs as vi
 
-KIND = {"seg": vi.HEAD_SEG, "depth": vi.HEAD_DEPTH, "det": vi.HEAD_DET}
+KIND = {"seg": vi.HEAD_SEG, "depth": vi.HEAD_DEPTH, "det": vi.HEAD_DET, "dpt": vi.HEAD_DPT}
 
 
 def head_cfgs(spec, seed, kinds, every_n=None):

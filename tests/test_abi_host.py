@@ -316,6 +316,32 @@ def test_ring_overwrites_oldest_and_stale_handles_are_refused():
         eng.run_head(0, future)
 
 
+def test_dpt_head_blob_size_and_validation():
+    spec = vi.small_spec(head_ch=64)
+    eng, _, hd = make_engine(spec, 1, kinds=("dpt", "seg"), flags=vpe.VPE_FLAG_HOST_ONLY)   # blob size accepted
+    F = 64
+    oc = [48, 96, 192, 384]
+    assert hd[0]["up0_w"].shape == (48, 48, 4, 4) and hd[0]["down3_w"].shape == (384, 384, 3, 3)
+    assert hd[0]["rn3_w"].shape == (F, 384, 3, 3) and hd[0]["head2_w"].shape == (32, 32, 3, 3)
+    assert "fuse3_a_c1_w" not in hd[0] and "fuse2_a_c1_w" in hd[0]
+    shape = vpe.vpe_head_output(eng.handle, 0, 0)[1]
+    assert tuple(shape) == (1, spec.img_h, spec.img_w, 1)
+    blob = vi.pack_backbone(spec, vi.make_backbone_weights(spec, 1))
+    cfg = _cfg(spec, blob)
+    hw = vi.pack_head(spec, vi.HEAD_DPT, hd[0])
+    h = (vpe.binding.vpe_head_cfg * 1)()
+    h[0].kind, h[0].classes, h[0].every_n, h[0].weights, h[0].weights_bytes = vi.HEAD_DPT, 0, 1, hw.ctypes.data, hw.nbytes
+    for ch, needle in ((320, "64..256"), (96, "multiple of 64")):
+        h[0].channels = ch
+        with pytest.raises(vpe.VpeError, match=needle):
+            vpe.vpe_workspace_bytes(cfg, h, 1)
+    h[0].channels, h[0].weights_bytes = 64, hw.nbytes - 4
+    with pytest.raises(vpe.VpeError, match="weights_bytes"):
+        vpe.vpe_workspace_bytes(cfg, h, 1)
+    h[0].weights_bytes = hw.nbytes
+    assert vpe.vpe_workspace_bytes(cfg, h, 1) > hw.nbytes // 2
+
+
 def test_feature_and_output_shapes():
     spec = vi.small_spec(registers=2, batch=2)
     eng, _, _ = make_engine(spec, 1, flags=vpe.VPE_FLAG_HOST_ONLY)

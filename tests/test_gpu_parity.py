@@ -80,6 +80,11 @@ def check_all(spec, seed, img_seed, kinds=("seg", "depth", "det"), flags=0, batc
                 report[f"b{b}.det.agree"] = float(np.mean(cm == o["classmap"]))
                 err = np.max(np.abs(out[..., :K].transpose(2, 0, 1) - o["logits"]))
                 report[f"b{b}.det.regret_ok"] = bool(regret(o["logits"], o["classmap"], cm) <= 2 * err + 1e-6)
+            elif kind == "dpt":
+                o = model.dpt_head(spec, hw[hi], ofe)
+                d = eng.head_output(hi, 0).cpu().numpy()[b]
+                report[f"b{b}.dpt"] = depth_err(d, o)
+                assert d.min() >= 0.0 and d.shape == (spec.img_h, spec.img_w)
             else:
                 o = model.depth_head(spec, hw[hi], ofe)
                 d = eng.head_output(hi, 0).cpu().numpy()[b]
@@ -186,6 +191,28 @@ def test_direct_to_lds_gemm_variant(tile, monkeypatch):
     spec = vi.ModelSpec("swiglu_tile" + tile, dtype="bf16", **{**MEDIUM, "mlp_kind": vi.MLP_SWIGLU, "registers": 4,
                                                                 "batch": 3, "img_h": 70, "img_w": 98})
     check_all(spec, 103, 203)
+
+
+# ---------------------------------------------------------------- full DPT head
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dpt_head_small_grids_odd_and_even(dtype):
+    # 11 x 15 patches: the deepest level is 6 x 8 (odd grid halved with padding), resizes 6x8 -> 11x15 are not x2
+    check_all(vi.ModelSpec("dpt_odd_" + dtype, dtype=dtype, **MEDIUM), 131, 231, kinds=("dpt",))
+    # two images, registers, an even grid, together with the other heads (shared features)
+    spec = vi.ModelSpec("dpt_even_" + dtype, dtype=dtype, **{**MEDIUM, "registers": 4, "batch": 2, "img_h": 112, "img_w": 140})
+    check_all(spec, 132, 232, kinds=("seg", "dpt", "det"))
+
+
+def test_dpt_head_wider_and_under_graph_replay():
+    spec = vi.ModelSpec("dpt_wide", dtype="bf16", **{**MEDIUM, "head_ch": 128, "img_h": 98, "img_w": 126})
+    check_all(spec, 133, 233, kinds=("dpt", "depth"), flags=vpe.VPE_FLAG_GRAPHS, lead_frames=3, ring_slots=2)
+
+
+def test_dpt_head_at_the_benchmark_size():
+    # ViT-S/14 at 476 x 630 with the DepthAnythingV2-small head shape (width 64, reassembled widths 48 .. 384):
+    # levels 136x180, 68x90, 34x45, 17x23; output convolutions on 272x360 and 476x630
+    spec = vi.with_(vi.CONFIGS["cfg2"], head_ch=64, name="cfg2_dpt")
+    check_all(spec, *vi.SEEDS["cfg2"], kinds=("dpt",), flags=vpe.VPE_FLAG_GRAPHS, lead_frames=2, ring_slots=2)
 
 
 # ---------------------------------------------------------------- camera-frame transform

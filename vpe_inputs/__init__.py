@@ -9,7 +9,8 @@ The paper (Sec. "Example implementation") runs trained DINOv2 / DepthAnythingV2 
 linear-seg / detection weights on 1920x1080 camera streams; none of that data is
 available, so these generators stand in for it:
 
-* weights: every tensor ~ N(0, 0.02^2) truncated to +-2 std by rejection;
+* weights: every tensor ~ N(0, 0.02^2) truncated to +-2 std by rejection (the full DPT head: kernels
+  N(0, 2 / fan_in), biases N(0, 0.1^2), same truncation, see _dpt_std);
   LayerNorm gains are 1 + that, LayerScale vectors are the constant 0.1;
   for the bf16 configurations every value is rounded once to the nearest bf16
   (ties to even) so both sides start from the same stored parameters.
@@ -210,7 +211,18 @@ def head_layout(spec: ModelSpec, kind: int) -> List[Tuple[str, Tuple[int, ...]]]
     raise ValueError(f"unknown head kind {kind}")
 
 
-def _fill(layout, seed: int, quantize: bool) -> Dict[str, np.ndarray]:
+def _dpt_std(name: str, shape) -> float:
+    """Standard deviation of a DPT-head tensor: convolution kernels sqrt(2 / fan_in) (fan_in = inputs that feed
+    one output value: Cin k k, or Cin alone for the stride = kernel transposed convolutions, stored [Cin][Cout][k][k]),
+    so that the activations keep their size through the ~20 layers of the head and every layer's contribution is
+    visible in the output; biases 0.1."""
+    if name.endswith("_b"):
+        return 0.1
+    fan_in = shape[0] if name.startswith("up") else int(np.prod(shape[1:]))
+    return float(np.sqrt(2.0 / fan_in))
+
+
+def _fill(layout, seed: int, quantize: bool, std_of=None) -> Dict[str, np.ndarray]:
     """All tensors of a layout, generated straight into one flat blob (key "__blob__"); the named
     entries are views of it.  Tensor i draws from its own stream PCG64(SeedSequence([seed, i])), so
     tensors can be filled in parallel and do not depend on each other's sizes."""
@@ -225,7 +237,8 @@ def _fill(layout, seed: int, quantize: bool) -> Dict[str, np.ndarray]:
         if leaf in ("ls1", "ls2"):
             dst[:] = np.float32(0.1)
         else:
-            _trunc_normal_into(np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, i]))), dst)
+            _trunc_normal_into(np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, i]))), dst,
+                               0.02 if std_of is None else std_of(name, layout[i][1]))
             if leaf in ("ln1_g", "ln2_g", "norm_g"):
                 dst += np.float32(1.0)
         if quantize:
@@ -244,7 +257,8 @@ def make_backbone_weights(spec: ModelSpec, seed: int) -> Dict[str, np.ndarray]:
 
 
 def make_head_weights(spec: ModelSpec, kind: int, seed: int) -> Dict[str, np.ndarray]:
-    return _fill(head_layout(spec, kind), seed * 7919 + 17 * (kind + 1), spec.dtype == "bf16")
+    return _fill(head_layout(spec, kind), seed * 7919 + 17 * (kind + 1), spec.dtype == "bf16",
+                 _dpt_std if kind == HEAD_DPT else None)
 
 
 def pack(layout, w: Dict[str, np.ndarray]) -> np.ndarray:
