@@ -342,7 +342,7 @@ def main() -> None:
             peak = MFMA_PEAK_TFLOPS[spec.dtype]
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
-                        "frac": round(ach / peak, 4), "traffic": args.traffic_bytes if args.traffic_bytes is not None else TRAFFIC_BYTES.get(spec.name), "us_per_launch": round(ms * 1e3, 2),
+                        "frac": round(ach / peak, 4), "traffic": args.traffic_bytes if args.traffic_bytes is not None else (TRAFFIC_BYTES.get(spec.name) if name == "depth_conv3x3" and not args.head_ch else None), "us_per_launch": round(ms * 1e3, 2),
                         "algorithmic_bytes": by, "algorithmic_flops": fl}
 
     cpu_baseline = None
