@@ -208,6 +208,12 @@ def test_dpt_head_wider_and_under_graph_replay():
     check_all(spec, 133, 233, kinds=("dpt", "depth"), flags=vpe.VPE_FLAG_GRAPHS, lead_frames=3, ring_slots=2)
 
 
+def test_dpt_head_at_its_widest():
+    # width 256 (the DepthAnythingV2-large head shape): reassembled widths 192 .. 1536, no channel padding anywhere
+    spec = vi.ModelSpec("dpt_256", dtype="bf16", **{**MEDIUM, "head_ch": 256, "img_h": 70, "img_w": 98, "batch": 2})
+    check_all(spec, 134, 234, kinds=("dpt",))
+
+
 def test_dpt_head_at_the_benchmark_size():
     # ViT-S/14 at 476 x 630 with the DepthAnythingV2-small head shape (width 64, reassembled widths 48 .. 384):
     # levels 136x180, 68x90, 34x45, 17x23; output convolutions on 272x360 and 476x630
