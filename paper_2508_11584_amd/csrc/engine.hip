@@ -709,7 +709,7 @@ GemmArgs conv3_gemm(vpe_engine& e, const void* in, int C, int B, int h, int w, i
 // smaller grid): both are linear and the resize weights sum to one, so the order only changes rounding.
 int enqueue_dpt(vpe_engine& e, Head& h, int slot, hipStream_t s) {
     Dpt& d = h.dpt;
-    const int dt = e.bf, BP = e.B * e.P, F = d.F, B = e.B;
+    const int dt = e.bf, F = d.F, B = e.B;
     void* const* f = &e.feat[slot * 4];
     auto conv = [&](const void* in, int cin_pad, int lvl_h, int lvl_w, const ConvW& w, int n_out, int act) {
         GemmArgs a = conv3_gemm(e, in, cin_pad, B, lvl_h, lvl_w, lvl_h * lvl_w, 0, w.w, w.b, n_out);
@@ -784,7 +784,6 @@ int enqueue_dpt(vpe_engine& e, Head& h, int slot, hipStream_t s) {
     h2.epi = EPI_ROWDOT; h2.gamma = d.head3_w; h2.out = d.dpart; h2.ldo = 1;
     HIPCHK(&e, launch_gemm(dt, h2, A_CONV3, s));
     HIPCHK(&e, launch_rowsum_relu(d.dpart, 1, d.head3_b, (int64_t)B * e.H * e.W, h.depth, s));
-    (void)BP;
     return 0;
 }
 

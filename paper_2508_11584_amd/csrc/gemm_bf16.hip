@@ -15,6 +15,7 @@ namespace {
 // MI355X with random bf16 data: the QKV / proj / fc1 / fc2 GEMMs of ViT-S, -B, -L (batch 4) and -g (batch 8),
 // the heads' 1x1 projections, and the 3x3 convolutions at 34x45 ... 296x296 grids (batch 1 and 4).  The
 // model's pick is the measured best on 23 of them, within 8 % on four and 15 % on one (0.4 % in total time).
+// VPE_NO_SMALL_DMA in the environment leaves the two small direct-to-LDS shapes out (a tuning aid).
 struct Cand { int kind, bm, bn, held; float alpha, beta; bool dma; };
 constexpr Cand kCands[] = {
     {128, 256, 128, 2, 5.16f, 1.055f, true},    // direct-to-LDS, 8 waves, 64 x 64 wave tiles
@@ -37,10 +38,18 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     const bool fits = a_rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
     int best = 3;
     float best_cost = 0.0f;
+    static const bool no_small = getenv("VPE_NO_SMALL_DMA") != nullptr;
     for (const Cand& c : kCands) {
         if (c.dma && !fits) continue;
+        if (no_small && (c.kind == 64 || c.kind == 65)) continue;
         if (c.bn == 64 && a.epi == EPI_SWIGLU) continue;        // needs 64-column wave tiles
         const int64_t tiles = (int64_t)cdiv(a.M, c.bm) * cdiv(a.N, c.bn) * (a.nz > 1 ? a.nz : 1);
+        // Inside the engine (not in the calibration harness) the small direct-to-LDS shapes lose to their
+        // register-staged counterparts when there is less than one tile per CU (ViT-S proj / fc2 with 144 tiles:
+        // 12.7 against 11.7 us; 3x3 convolutions on the 34x45 and 68x90 grids: 24.0 against 20.7, 27.8 against
+        // 25.9 us) and win above that (QKV 8.3 against 9.1, fc1 11.3 against 12.0, the 136x180 convolution 43.8
+        // against 47.4 us)
+        if ((c.kind == 64 || c.kind == 65) && tiles < 256) continue;
         const float r = (float)cdiv(tiles, 256) / c.held;
         const float cost = c.alpha * (r > 1.0f ? r : 1.0f) + c.beta * r * (1e-6f * c.bm * c.bn * a.K);
         if (best_cost == 0.0f || cost < best_cost) { best_cost = cost; best = c.kind; }
