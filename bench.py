@@ -335,9 +335,11 @@ def main() -> None:
     kern = {}
     shared_step(0)
     eng.sync()
-    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm")) + (((3, "depth_conv3x3"),) if "depth" in kinds else ()):
+    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm")) + (((3, "depth_conv3x3"), (4, "depth_fuse_upsample")) if "depth" in kinds else ()):
         ms, fl, by = eng.time_kernel(which, args.kernel_reps)
         kern[name] = {"us": round(ms * 1e3, 2), "tflops": round(fl / ms / 1e9, 2), "gbps": round(by / ms / 1e6, 1)}
+        if name in ("layernorm", "depth_fuse_upsample"):            # bandwidth-bound kernels: fraction of the 8 TB/s HBM peak
+            kern[name]["hbm_frac"] = round(by / ms / 1e6 / 8000.0, 4)
         if name == "depth_conv3x3" or (name == "qkv_gemm" and "depth" not in kinds):
             peak = MFMA_PEAK_TFLOPS[spec.dtype]
             ach = fl / (ms * 1e-3) / 1e12

@@ -247,7 +247,7 @@ int vpe_stats(vpe_engine* e, int64_t* frames, int64_t* head_runs, int64_t* head_
  * encoder stream with HIP events around them and return the mean milliseconds per launch.
  * which: 0 = the fused-QKV GEMM of block 0 on the current activations, 1 = the attention
  * kernel of block 0, 2 = LayerNorm, 3 = the depth head's largest 3x3 convolution (last fusion stage; needs a
- * depth head).
+ * depth head), 4 = the resample-and-add kernel that writes that convolution's input (needs a depth head).
  * Also reports the algorithmic flops and bytes of one launch. */
 int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes);
 

@@ -1263,6 +1263,10 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 HIPCHK(e, launch_attention(dt, a, s));
             } else if (which == 2) {
                 HIPCHK(e, launch_layernorm(dt, L0.x, T, D, e->blk[0].ln1_g, e->blk[0].ln1_b, e->cfg.ln_eps, L0.u, s));
+            } else if (which == 4) {
+                // the stage input of that convolution: upsample of the tap projection + x2 upsample of the previous
+                // stage's output, 8x the patch grid (bandwidth-bound: reads 1/4 of what it writes)
+                HIPCHK(e, launch_fuse_upsample(dt, dh->p[3], e->gh, e->gw, dh->r, e->B, e->gh << 3, e->gw << 3, dh->ch, dh->z, s));
             } else {
                 // the largest 3x3 convolution of the depth head (last fusion stage, 8x the patch grid), same
                 // shape, weights and buffers as in a head run; its timing does not depend on the values in z
@@ -1275,7 +1279,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
         if (timed) HIPCHK(e, hipEventRecord(t1, s));
         return 0;
     };
-    if (which < 0 || which > 3 || (which == 3 && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
+    if (which < 0 || which > 4 || (which >= 3 && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
     if (!rc) rc = body(false);   // warm-up launch
     if (!rc) rc = body(true);
     if (!rc && hipEventSynchronize(t1) != hipSuccess) rc = e->fail(VPE_EHIP, "hipEventSynchronize failed");
@@ -1288,6 +1292,11 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
     if (which == 0) { fl = 2.0 * T * D * 3.0 * D; by = esz * ((double)T * D + 3.0 * D * D + 3.0 * T * D); }
     else if (which == 1) { fl = 4.0 * e->B * (double)e->N * e->N * D; by = esz * 4.0 * T * D; }
     else if (which == 2) { fl = 8.0 * T * D; by = (4.0 + esz) * T * D; }
+    else if (which == 4) {
+        const double ch = dh->ch, pix = (double)e->B * e->P;
+        fl = 14.0 * 64.0 * pix * ch;                                   // two bilinear blends and an add per output value
+        by = esz * ch * pix * (1.0 + 16.0 + 64.0);                     // tap projection + previous stage in, stage input out
+    }
     else {
         const double ch = dh->ch, pix = (double)e->B * e->P * 64.0;
         fl = 2.0 * 9.0 * ch * ch * pix;
