@@ -20,7 +20,7 @@ __device__ __forceinline__ Tap bilinear_tap(int y, int in, int out) {
     } else {
         // quotient by a float reciprocal, made exact by one correction step (|estimate - n / d| < 1 for the
         // image sizes that fit the 32-bit numerator)
-        const float rd = 1.0f / (float)d;
+        const float rd = __builtin_amdgcn_rcpf((float)d);      // 1 ulp; the correction step below absorbs it
         int q = (int)((float)n * rd);
         int rem = n - q * d;
         if (rem < 0) { --q; rem += d; }
@@ -91,17 +91,18 @@ __device__ __forceinline__ void add_block(const T* __restrict__ src, int b, int 
     BlockSrc<T, CE> ys, xs;
     ys.init(y0, h, Hs);
     xs.init(x0, w, Ws);
-    const T* base = src + (int64_t)b * h * w * C + cg * CE;
+    const T* base = src + (int64_t)b * h * w * C + cg * CE;     // offsets inside one image fit 32 bits (checked by the launcher)
     const int rows[3] = {ys.ra, ys.rb, ys.rc};
+    const int xa = xs.ra * C, xb = xs.rb * C, xc = xs.rc * C;
     // horizontal blends of each source row for the block's two output columns
     float hz[3][2][CE];
 #pragma unroll
     for (int i = 0; i < (SHARED ? 2 : 3); ++i) {
-        const T* rp = base + (int64_t)rows[i] * w * C;
+        const T* rp = base + rows[i] * w * C;
         float va[CE], vb[CE], vc[CE];
-        Vec<T, CE>::load(rp + (int64_t)xs.ra * C, va);
-        Vec<T, CE>::load(rp + (int64_t)xs.rb * C, vb);
-        if (!SHARED) Vec<T, CE>::load(rp + (int64_t)xs.rc * C, vc);
+        Vec<T, CE>::load(rp + xa, va);
+        Vec<T, CE>::load(rp + xb, vb);
+        if (!SHARED) Vec<T, CE>::load(rp + xc, vc);
 #pragma unroll
         for (int e = 0; e < CE; ++e) {
             hz[i][0][e] = (1.0f - xs.w0) * va[e] + xs.w0 * vb[e];

@@ -50,6 +50,7 @@ hipError_t launch_argmax_rows(const float* in, int64_t rows, int C, int ld, uint
 hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const void* r, int B, int Hs, int Ws,
                                 int C, void* z, hipStream_t s) {
     if (Hs % 2 || Ws % 2 || Hs < 2 * gh || Ws < 2 * gw) return hipErrorInvalidValue;   // 2 x 2 output blocks of an enlargement
+    if ((int64_t)Hs * Ws * C >= (int64_t(1) << 31)) return hipErrorInvalidValue;          // 32-bit offsets inside an image
     // both rows (columns) of an even-aligned block fall between the same two source samples when the factor f
     // is a multiple of 4: a sample boundary lies between outputs y and y + 1 only if f (2 j + 1) = 2 y + 2,
     // and for even y the right side is 2 mod 4
