@@ -203,6 +203,13 @@ def test_dpt_head_small_grids_odd_and_even(dtype):
     check_all(spec, 132, 232, kinds=("seg", "dpt", "det"))
 
 
+def test_dpt_head_degenerate_grids():
+    # one patch (every level at least 1 x 1, resizes from a single sample) and one row of patches
+    for dt in ("f32", "bf16"):
+        check_all(vi.ModelSpec("dpt_one_patch_" + dt, dtype=dt, **{**MEDIUM, "img_h": 14, "img_w": 14}), 135, 235, kinds=("dpt",))
+    check_all(vi.ModelSpec("dpt_strip", dtype="bf16", **{**MEDIUM, "img_h": 14, "img_w": 14 * 23}), 136, 236, kinds=("dpt",))
+
+
 def test_dpt_head_wider_and_under_graph_replay():
     spec = vi.ModelSpec("dpt_wide", dtype="bf16", **{**MEDIUM, "head_ch": 128, "img_h": 98, "img_w": 126})
     check_all(spec, 133, 233, kinds=("dpt", "depth"), flags=vpe.VPE_FLAG_GRAPHS, lead_frames=3, ring_slots=2)
