@@ -30,6 +30,7 @@ def sample():
     seg = model.seg_head(SPEC, vi.make_head_weights(SPEC, vi.HEAD_SEG, SEED), feats)
     det = model.det_head(SPEC, vi.make_head_weights(SPEC, vi.HEAD_DET, SEED), feats)
     dep = model.depth_head(SPEC, vi.make_head_weights(SPEC, vi.HEAD_DEPTH, SEED), feats)
+    dpt = model.dpt_head(SPEC, vi.make_head_weights(SPEC, vi.HEAD_DPT, SEED), feats, return_stages=True)
     out = {}
     for k, f in enumerate(feats):
         out[f"feat{k}"] = f.ravel()[::97][:8]
@@ -37,6 +38,9 @@ def sample():
     out["det_logits"] = det["logits"].ravel()[::5][:8]
     out["det_box"] = det["box"].ravel()[::3][:8]
     out["depth_pre_relu"] = dep["pre_relu"].ravel()[::131][:8]
+    out["dpt_l3"] = dpt["l"][3].ravel()[::11][:8]
+    out["dpt_path0"] = dpt["paths"][-1].ravel()[::1201][:8]
+    out["dpt_pre_relu"] = dpt["pre_relu"].ravel()[::131][:8]
     return out
 
 
