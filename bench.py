@@ -31,6 +31,46 @@ def backbone_flops(spec) -> float:
     return 2.0 * B * P * 588 * D + spec.depth * per_block
 
 
+class RawStream:
+    """A HIP stream by handle, in the shape the Engine wrapper expects of a stream argument."""
+    def __init__(self, handle: int):
+        self.cuda_stream = handle
+
+
+def make_masked_streams(vpe, k: int):
+    """k streams, stream i restricted to compute units [i * 256 / k, (i + 1) * 256 / k) by a CU mask; [] if the
+    runtime refuses.  The runtime call is taken from the HIP library that libvpe.so is linked against."""
+    import ctypes as C
+    try:
+        create = vpe.lib().hipExtStreamCreateWithCUMask
+    except AttributeError:
+        return []
+    create.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint32)]
+    create.restype = C.c_int
+    out, per = [], 256 // k
+    for i in range(k):
+        words = (C.c_uint32 * 8)()
+        for cu in range(i * per, (i + 1) * per):
+            words[cu // 32] |= 1 << (cu % 32)
+        h = C.c_void_p()
+        if create(C.byref(h), 8, words) != 0 or not h.value:
+            destroy_streams(vpe, out)
+            return []
+        out.append(RawStream(h.value))
+    return out
+
+
+def destroy_streams(vpe, streams) -> None:
+    import ctypes as C
+    if not streams:
+        return
+    destroy = vpe.lib().hipStreamDestroy
+    destroy.argtypes = [C.c_void_p]
+    destroy.restype = C.c_int
+    for st in streams:
+        destroy(st.cuda_stream)
+
+
 def multihead_experiment(args, vpe, vi, make_engine, np, torch) -> None:
     """Frame latency (submit one resident frame, wait for every head) against the number k of identical heads.
 
@@ -39,6 +79,7 @@ def multihead_experiment(args, vpe, vi, make_engine, np, torch) -> None:
       independent       k x (encoder pass + head) one after another on one stream: k separate full models
       sequential_heads  one encoder pass, then the k heads one after another on that stream
       concurrent        one encoder pass, the k heads spread over the engine's head streams
+      concurrent_cu_masked  one encoder pass, every head on a stream of its own that may use 256 / k compute units
     plus the pipelined rate of the concurrent arm (frames/s without waiting between frames, several encoder
     lanes) and the device memory each added head costs."""
     spec = vi.CONFIGS[args.config]
@@ -68,6 +109,15 @@ def multihead_experiment(args, vpe, vi, make_engine, np, torch) -> None:
                 for h in range(k):
                     eng.run_head(h, fh)
 
+            # the same with every head on its own stream restricted to 256 / k compute units (a CU mask; the
+            # analogue of the fixed GPU shares the paper gives its head processes through MPS)
+            masked = make_masked_streams(vpe, k)
+
+            def concurrent_masked(i):
+                fh = eng.encode(frames[i & 1])
+                for h in range(k):
+                    eng.run_head(h, fh, stream=masked[h])
+
             def latency(fn):
                 lat = []
                 for i in range(n + 5):
@@ -81,6 +131,9 @@ def multihead_experiment(args, vpe, vi, make_engine, np, torch) -> None:
             row = {"head": kind, "k": k, "independent_ms": round(latency(independent), 4),
                    "sequential_heads_ms": round(latency(sequential_heads), 4), "concurrent_ms": round(latency(concurrent), 4),
                    "workspace_mb": round(eng.workspace_bytes / 1e6, 1)}
+            row["concurrent_cu_masked_ms"] = round(latency(concurrent_masked), 4) if masked else None
+            eng.sync()
+            destroy_streams(vpe, masked)
             eng.close()
             # pipelined rate: frames are pushed without waiting, consecutive encoder passes overlap
             lanes = args.encoder_lanes or 3
