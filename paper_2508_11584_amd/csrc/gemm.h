@@ -383,36 +383,49 @@ __device__ __forceinline__ void resid_stats_chunk(const GemmArgs& p, int r, int 
 // each thread then owns 8 consecutive columns of a row: one row-index computation and 16-byte
 // coalesced global accesses per chunk instead of 64 scattered 2-byte stores per lane.
 // accumulator element v of lane (g, li) in block (i, j): row = 32 i + 8 (v / 4) + 4 g + v % 4, col = 32 j + li
-template <typename T, int BM, int BN, int WGM, int WGN>
+// KG > 1: the workgroup holds KG groups of WGM x WGN waves, each with the partial sums of its share of the k
+// range for the same tile; they are added in LDS in a fixed order (group 0, then 1, ...), and all KG groups'
+// threads share the chunk work below.
+template <typename T, int BM, int BN, int WGM, int WGN, int KG = 1>
 __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
                                                char* smem, const float* lnrow, const float* lncs, int m0, int n0) {
-    constexpr int NT = 64 * WGM * WGN;
+    constexpr int NTG = 64 * WGM * WGN, NT = NTG * KG;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid % NTG) >> 6;
+    const int kg = KG > 1 ? tid / NTG : 0;
     const int wm = wave / WGN, wn = wave % WGN;
     const int g = lane >> 5, li = lane & 31;
     float* sC = reinterpret_cast<float*>(smem);
     if (p.ln_stats) {
         // folded LayerNorm: lnrow[2 row] = mean, lnrow[2 row + 1] = rstd of the tile's rows
         // lncs[j]: column sum of this lane's column in block j, loaded before the k loop
+        // (the mean term belongs to the whole sum: only group 0 subtracts it)
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
                 const f32x2 st = *reinterpret_cast<const f32x2*>(lnrow + 2 * row);
+                const float mean = kg == 0 ? st[0] : 0.0f;
 #pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j][v] = st[1] * (acc[i][j][v] - st[0] * lncs[j]);
+                for (int j = 0; j < NI; ++j) acc[i][j][v] = st[1] * (acc[i][j][v] - mean * lncs[j]);
             }
     }
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int k = 0; k < KG; ++k) {
+        if (kg == k) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                sC[(wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * BN + wn * WN + j * 32 + li] = acc[i][j][v];
-    __syncthreads();
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float* dst = sC + (wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * BN + wn * WN + j * 32 + li;
+                        *dst = k == 0 ? acc[i][j][v] : *dst + acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+    }
 
     if (p.epi == EPI_SWIGLU) {
         // physical columns come in groups of 64: 32 gate columns, then their 32 linear partners;
@@ -674,6 +687,197 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
 
     static_assert(BM * BN * 4 <= 2 * STAGE, "accumulator tile must fit the stage buffers");
     block_epilogue<T, BM, BN, WGM, WGN>(p, acc, smem, lnrow, lncs, m0, n0);
+}
+
+// The same tile computed by two groups of WGM x WGN waves, each over half of the k range (group 0 the first
+// ceil(KT / 2) k-tiles, group 1 the rest), with its own pair of LDS buffers; the two partial sums are added in
+// LDS in a fixed order by the epilogue.  For problems with less than one tile per CU and a long k loop (the
+// ViT-S fc2 GEMM, the 3x3 convolutions on the patch grid): such a loop is a serial chain of load, barrier, LDS
+// read and MFMA in one wave per SIMD, and the second group's chain runs in the gaps of the first.
+// Dynamic LDS: 4 * STAGE + 8 * BM bytes.
+template <typename T, int BM, int BN, int WGM, int WGN, int AMODE>
+__global__ __launch_bounds__(128 * WGM * WGN, 2) void gemm_splitk_kernel(const GemmArgs args) {
+    const GemmArgs p = select_problem(args);
+    constexpr int KG = 2, NTG = 64 * WGM * WGN;
+    constexpr int CE = Elem<T>::CE;
+    constexpr int BK = 8 * CE;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    constexpr int RPP = NTG / 8;
+    constexpr int A_IT = BM / RPP, B_IT = BN / RPP;
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of the loader pass");
+    constexpr int STAGE = (BM + BN) * 128;
+    extern __shared__ __attribute__((aligned(16))) char smem_all[];
+    float* lnrow = reinterpret_cast<float*>(smem_all + KG * 2 * STAGE);
+
+    const int tid = threadIdx.x, kg = tid / NTG, gt = tid % NTG;
+    char* smem = smem_all + kg * 2 * STAGE;
+    const int lane = gt & 63, wave = gt >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int g = lane >> 5, li = lane & 31;
+    const int lrow = gt >> 3, lchunk = gt & 7;
+
+    int tm, tn;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const T* __restrict__ A = reinterpret_cast<const T*>(p.A);
+    const T* __restrict__ W = reinterpret_cast<const T*>(p.W);
+
+    // loader state as in gemm_kernel: no branches or selects on loaded values, rows past M re-read row M - 1,
+    // out-of-image taps read the page of zeros
+    const T* aptr[A_IT];
+    int ay[A_IT], ax[A_IT];
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+        int r = m0 + lrow + i * RPP;
+        r = r < p.M ? r : p.M - 1;
+        ay[i] = ax[i] = 0;
+        if (AMODE == A_PLAIN) {
+            const int64_t ar = (int64_t)(r / p.a_rpi) * p.a_istride + p.a_off + r % p.a_rpi;
+            aptr[i] = A + ar * p.lda + lchunk * CE;
+        } else {
+            const int hw = p.cH * p.cW;
+            const int b = r / hw, pix = r % hw;
+            ay[i] = pix / p.cW;
+            ax[i] = pix % p.cW;
+            aptr[i] = A + ((int64_t)b * p.a_istride + p.a_off + pix) * p.lda + lchunk * CE;
+        }
+    }
+    const T* wptr = W + (int64_t)(n0 + lrow) * p.K + lchunk * CE;
+    const T* zptr = reinterpret_cast<const T*>(p.zeros);
+
+    // this group's k-tiles: [kbeg, kbeg + kcnt) of the KT tiles; both groups run ceil(KT / 2) iterations (the
+    // barriers are common), a group with fewer tiles re-loads its last one and skips the multiply
+    const int KT = p.K / BK, KH = (KT + 1) / 2;
+    const int kbeg = kg * KH;
+    const int kcnt = KT - kbeg < KH ? (KT - kbeg > 0 ? KT - kbeg : 0) : KH;
+    auto tile_of = [&](int local) {
+        const int t = kbeg + (local < kcnt ? local : kcnt - 1);
+        return t < 0 ? 0 : (t < KT ? t : KT - 1);
+    };
+
+    u32x4 ra[2][A_IT], rb[2][B_IT];
+    auto gload = [&](int set, int local) {
+        const int kt = tile_of(local);
+        const int k0 = kt * BK;
+        if (AMODE == A_PLAIN) {
+#pragma unroll
+            for (int i = 0; i < A_IT; ++i) ra[set][i] = ld_global_16(aptr[i] + k0);
+        } else {
+            const int cc = kt / 9, tap = kt - cc * 9, c0 = cc * BK;
+            const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+            const int64_t shift = (int64_t)(dy * p.cW + dx) * p.lda + c0;
+#pragma unroll
+            for (int i = 0; i < A_IT; ++i) {
+                const int yy = ay[i] + dy, xx = ax[i] + dx;
+                const bool ok = yy >= 0 && yy < p.cH && xx >= 0 && xx < p.cW;
+                const uint64_t mask = ok ? ~uint64_t(0) : uint64_t(0);
+                const uint64_t addr = (reinterpret_cast<uint64_t>(aptr[i] + shift) & mask) |
+                                      (reinterpret_cast<uint64_t>(zptr) & ~mask);
+                ra[set][i] = ld_global_16(reinterpret_cast<const void*>(addr));
+            }
+        }
+        const int kw = AMODE == A_PLAIN ? k0 : (kt % 9) * p.cC + (kt / 9) * BK;
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) rb[set][i] = ld_global_16(wptr + (int64_t)i * RPP * p.K + kw);
+    };
+    auto sstore = [&](int set, int buf) {
+        char* sA = smem + buf * STAGE;
+        char* sB = sA + BM * 128;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int r = lrow + i * RPP;
+            *reinterpret_cast<u32x4*>(sA + (r * 8 + swz(r, lchunk)) * 16) = ra[set][i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            const int r = lrow + i * RPP;
+            *reinterpret_cast<u32x4*>(sB + (r * 8 + swz(r, lchunk)) * 16) = rb[set][i];
+        }
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    auto compute = [&](int buf) {
+        const char* sA = smem + buf * STAGE;
+        const char* sB = sA + BM * 128;
+        typename Mma<T>::Frag fa[2][MI], fb[2][NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[0][i] = Mma<T>::load(sA, wm * WM + i * 32 + li, 0, g);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[0][j] = Mma<T>::load(sB, wn * WN + j * 32 + li, 0, g);
+#pragma unroll
+        for (int ks = 0; ks < Mma<T>::KS; ++ks) {
+            if (ks + 1 < Mma<T>::KS) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) fa[(ks + 1) & 1][i] = Mma<T>::load(sA, wm * WM + i * 32 + li, ks + 1, g);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) fb[(ks + 1) & 1][j] = Mma<T>::load(sB, wn * WN + j * 32 + li, ks + 1, g);
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) Mma<T>::mma(acc[i][j], fa[ks & 1][i], fb[ks & 1][j]);
+        }
+    };
+
+    gload(0, 0);
+    gload(1, 1);
+    float lncs[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) lncs[j] = 0.0f;
+    if (p.ln_stats) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int c = n0 + wn * WN + j * 32 + li;
+            if (c < p.N) lncs[j] = p.ln_colsum[c];
+        }
+        if (tid < BM) ln_tile_row(p, m0, n0, tid, lnrow);
+    }
+    sstore(0, 0);
+    __syncthreads();
+    for (int kt = 0; kt < KH; kt += 2) {
+        gload(0, kt + 2);
+        if (kt < kcnt) compute(0);              // uniform per wave
+        sstore(1, 1);
+        __syncthreads();
+        if (kt + 1 >= KH) break;
+        gload(1, kt + 3);
+        if (kt + 1 < kcnt) compute(1);
+        sstore(0, 0);
+        __syncthreads();
+    }
+
+    static_assert(BM * BN * 4 <= 2 * STAGE, "accumulator tile must fit the stage buffers");
+    block_epilogue<T, BM, BN, WGM, WGN, KG>(p, acc, smem_all, lnrow, lncs, m0, n0);
+}
+
+template <typename T, int BM, int BN, int WGM, int WGN>
+static inline hipError_t launch_tile_splitk(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
+    constexpr int lds = 4 * (BM + BN) * 128 + 8 * BM;
+    static_assert(BM <= 64 * WGM * WGN, "the row statistics are taken by the first BM threads (group 0)");
+    static bool configured = false;
+    if (!configured) {
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (rc == hipSuccess)
+            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (rc != hipSuccess) return rc;
+        configured = true;
+    }
+    if (configure_only) return hipSuccess;
+    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN);
+    dim3 grid(tiles, a.nz > 1 ? a.nz : 1), block(128 * WGM * WGN);
+    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3>), grid, block, lds, s, a);
+    return hipGetLastError();
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN>

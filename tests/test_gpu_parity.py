@@ -181,9 +181,10 @@ def test_cfg2_in_the_pipelined_configuration_the_benchmark_times():
     check_all(spec, *vi.SEEDS["cfg2"], flags=vpe.VPE_FLAG_GRAPHS, lead_frames=6, ring_slots=4, encoder_lanes=3)
 
 
-@pytest.mark.parametrize("tile", ["384", "256", "128", "65", "64"])
+@pytest.mark.parametrize("tile", ["384", "256", "128", "65", "64", "4"])
 def test_direct_to_lds_gemm_variant(tile, monkeypatch):
-    # each direct-to-LDS GEMM shape (384 x 256, 256 x 256, 256 x 128, 64 x 128, 64 x 64 tiles), forced for every GEMM of the model,
+    # each direct-to-LDS GEMM shape (384 x 256, 256 x 256, 256 x 128, 64 x 128, 64 x 64 tiles) and the split-k 64 x 64
+    # shape ("4": two wave groups over halves of the k range, odd and even k-tile counts), forced for every GEMM of the model,
     # through every epilogue: folded LayerNorm + QKV with transposed values, LayerScale residual with row
     # statistics, GELU and SwiGLU, patch embedding, 1x1 and 3x3 convolutions, the fused 1-channel projection
     monkeypatch.setenv("VPE_GEMM_TILE", tile)
