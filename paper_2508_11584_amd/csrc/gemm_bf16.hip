@@ -54,12 +54,13 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
         const float cost = c.alpha * (r > 1.0f ? r : 1.0f) + c.beta * r * (1e-6f * c.bm * c.bn * a.K);
         if (best_cost == 0.0f || cost < best_cost) { best_cost = cost; best = c.kind; }
     }
-    // A 64 x 64 tiling with at most one tile per CU and at least 16 k-tiles: two wave groups per tile, each over
+    // A 64 x 64 tiling with at most one tile per CU and at least 4 k-tiles: two wave groups per tile, each over
     // half of the k range (in-engine: ViT-S fc2 14.4 -> 12.5 us, the 3x3 convolution on the 34x45 grid 20.7 -> 17.5,
-    // the detection towers 26.9 -> 23.8; frame latency 1.13 -> 1.10 ms, pipelined rate unchanged within noise).
+    // the detection towers 26.9 -> 23.8; ViT-S 476x630 frame latency 1.13 -> 1.08 ms, sequential baseline 396 -> 418
+    // frames/s, pipelined rate +0.5 %; with the threshold at 16 k-tiles 1.10 ms / 408 / +0 %).
     // VPE_NO_SPLITK in the environment switches it off (a tuning aid).
     static const bool no_splitk = getenv("VPE_NO_SPLITK") != nullptr;
-    if (!no_splitk && best == 3 && a.K >= 1024 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
+    if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
     if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
     if (forced == 4) best = a.epi == EPI_SWIGLU ? 2 : 4;
     if (forced == 64 && fits) best = a.epi == EPI_SWIGLU ? 65 : 64;
