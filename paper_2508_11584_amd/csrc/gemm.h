@@ -689,16 +689,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
     block_epilogue<T, BM, BN, WGM, WGN>(p, acc, smem, lnrow, lncs, m0, n0);
 }
 
-// The same tile computed by two groups of WGM x WGN waves, each over half of the k range (group 0 the first
-// ceil(KT / 2) k-tiles, group 1 the rest), with its own pair of LDS buffers; the two partial sums are added in
+// The same tile computed by KG groups of WGM x WGN waves, each over 1 / KG of the k range (group g the k-tiles
+// [g ceil(KT / KG), (g + 1) ceil(KT / KG))), with its own pair of LDS buffers; the partial sums are added in
 // LDS in a fixed order by the epilogue.  For problems with less than one tile per CU and a long k loop (the
 // ViT-S fc2 GEMM, the 3x3 convolutions on the patch grid): such a loop is a serial chain of load, barrier, LDS
 // read and MFMA in one wave per SIMD, and the second group's chain runs in the gaps of the first.
-// Dynamic LDS: 4 * STAGE + 8 * BM bytes.
-template <typename T, int BM, int BN, int WGM, int WGN, int AMODE>
-__global__ __launch_bounds__(128 * WGM * WGN, 2) void gemm_splitk_kernel(const GemmArgs args) {
+// Dynamic LDS: 2 KG * STAGE + 8 * BM bytes.
+template <typename T, int BM, int BN, int WGM, int WGN, int AMODE, int KG>
+__global__ __launch_bounds__(64 * KG * WGM * WGN, KG * WGM * WGN / 4) void gemm_splitk_kernel(const GemmArgs args) {
     const GemmArgs p = select_problem(args);
-    constexpr int KG = 2, NTG = 64 * WGM * WGN;
+    constexpr int NTG = 64 * WGM * WGN;
     constexpr int CE = Elem<T>::CE;
     constexpr int BK = 8 * CE;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
@@ -746,9 +746,9 @@ __global__ __launch_bounds__(128 * WGM * WGN, 2) void gemm_splitk_kernel(const G
     const T* wptr = W + (int64_t)(n0 + lrow) * p.K + lchunk * CE;
     const T* zptr = reinterpret_cast<const T*>(p.zeros);
 
-    // this group's k-tiles: [kbeg, kbeg + kcnt) of the KT tiles; both groups run ceil(KT / 2) iterations (the
+    // this group's k-tiles: [kbeg, kbeg + kcnt) of the KT tiles; all groups run ceil(KT / KG) iterations (the
     // barriers are common), a group with fewer tiles re-loads its last one and skips the multiply
-    const int KT = p.K / BK, KH = (KT + 1) / 2;
+    const int KT = p.K / BK, KH = (KT + KG - 1) / KG;
     const int kbeg = kg * KH;
     const int kcnt = KT - kbeg < KH ? (KT - kbeg > 0 ? KT - kbeg : 0) : KH;
     auto tile_of = [&](int local) {
@@ -858,25 +858,26 @@ __global__ __launch_bounds__(128 * WGM * WGN, 2) void gemm_splitk_kernel(const G
     block_epilogue<T, BM, BN, WGM, WGN, KG>(p, acc, smem_all, lnrow, lncs, m0, n0);
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN>
+template <typename T, int BM, int BN, int WGM, int WGN, int KG>
 static inline hipError_t launch_tile_splitk(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
-    constexpr int lds = 4 * (BM + BN) * 128 + 8 * BM;
+    constexpr int lds = KG * 2 * (BM + BN) * 128 + 8 * BM;
+    static_assert(lds <= 160 * 1024 && 64 * KG * WGM * WGN <= 1024, "LDS and workgroup size limits");
     static_assert(BM <= 64 * WGM * WGN, "the row statistics are taken by the first BM threads (group 0)");
     static bool configured = false;
     if (!configured) {
-        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN>),
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN, KG>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc == hipSuccess)
-            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3>),
+            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3, KG>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc != hipSuccess) return rc;
         configured = true;
     }
     if (configure_only) return hipSuccess;
     const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN);
-    dim3 grid(tiles, a.nz > 1 ? a.nz : 1), block(128 * WGM * WGN);
-    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3>), grid, block, lds, s, a);
+    dim3 grid(tiles, a.nz > 1 ? a.nz : 1), block(64 * KG * WGM * WGN);
+    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN, KG>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3, KG>), grid, block, lds, s, a);
     return hipGetLastError();
 }
 

@@ -69,7 +69,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
         case 64: case 65: case 128: case 256: case 384: return launch_gemm_dma_bf16(best, a, amode, s);
         case 1: return launch_tile<bf16, 128, 128, 2, 2>(a, amode, s);
         case 2: return launch_tile<bf16, 64, 128, 2, 2>(a, amode, s);
-        case 4: return launch_tile_splitk<bf16, 64, 64, 2, 2>(a, amode, s);
+        case 4: return launch_tile_splitk<bf16, 64, 64, 2, 2, 2>(a, amode, s);
         default: return launch_tile<bf16, 64, 64, 2, 2>(a, amode, s);
     }
 }
@@ -77,6 +77,6 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
 // LDS opt-in of the split-k kernel; called once at engine creation, outside any stream capture.
 hipError_t configure_gemm_bf16() {
     GemmArgs a{};
-    return launch_tile_splitk<bf16, 64, 64, 2, 2>(a, A_PLAIN, nullptr, true);
+    return launch_tile_splitk<bf16, 64, 64, 2, 2, 2>(a, A_PLAIN, nullptr, true);
 }
 }  // namespace vpe
