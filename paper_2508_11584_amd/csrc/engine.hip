@@ -941,6 +941,7 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
     if (hip(configure_attention(), "configure_attention")) return bail(VPE_EHIP);
     if (hip(configure_gemm(), "configure_gemm")) return bail(VPE_EHIP);
     if (hip(configure_gemm_bf16(), "configure_gemm_bf16")) return bail(VPE_EHIP);
+    if (hip(configure_gemm_f32(), "configure_gemm_f32")) return bail(VPE_EHIP);
     Bump real;
     real.base = e->ws;
     layout(*e, real);

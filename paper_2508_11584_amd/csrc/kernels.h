@@ -14,6 +14,7 @@ hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s);
 hipError_t configure_attention();
 hipError_t configure_gemm();
 hipError_t configure_gemm_bf16();
+hipError_t configure_gemm_f32();
 
 hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const float* g, const float* b,
                             float eps, void* y, hipStream_t s);
