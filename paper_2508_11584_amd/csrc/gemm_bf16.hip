@@ -58,7 +58,9 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     // half of the k range (in-engine: ViT-S fc2 14.4 -> 12.5 us, the 3x3 convolution on the 34x45 grid 20.7 -> 17.5,
     // the detection towers 26.9 -> 23.8; ViT-S 476x630 frame latency 1.13 -> 1.08 ms, sequential baseline 396 -> 418
     // frames/s, pipelined rate +0.5 %; with the threshold at 16 k-tiles 1.10 ms / 408 / +0 %).
-    // VPE_NO_SPLITK in the environment switches it off (a tuning aid).
+    // VPE_NO_SPLITK in the environment switches it off (a tuning aid).  A limit of 288 tiles, which takes in the
+    // ViT-B proj / fc2 GEMMs (264 tiles), brings that model's frame latency from 1.79 to 1.70 ms but costs 1.5 % of its
+    // pipelined rate with three encoder lanes.
     static const bool no_splitk = getenv("VPE_NO_SPLITK") != nullptr;
     if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
     if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
