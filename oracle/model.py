@@ -102,12 +102,12 @@ def _grid(spec, feat) -> np.ndarray:
     return np.ascontiguousarray(g.reshape(spec.gh, spec.gw, spec.dim).transpose(2, 0, 1))
 
 
-def _decide(z: np.ndarray, decide_dtype) -> np.ndarray:
-    """Channel argmax taken in the precision the GPU path decides in (ties -> lowest)."""
-    return ops.argmax_channels(np.asarray(z, dtype=decide_dtype).astype(np.float64))
+def _decide(z: np.ndarray) -> np.ndarray:
+    """Channel argmax of the fp64 scores (ties -> lowest index)."""
+    return ops.argmax_channels(np.asarray(z, dtype=np.float64))
 
 
-def seg_head(spec, hw, feats, decide_dtype=np.float32) -> Dict[str, np.ndarray]:
+def seg_head(spec, hw, feats) -> Dict[str, np.ndarray]:
     """Linear segmentation head on one image's features.
 
     z = 1x1 conv D->C on the final patch tokens; Z = bilinear(z -> HxW); class = argmax_c Z.
@@ -115,10 +115,10 @@ def seg_head(spec, hw, feats, decide_dtype=np.float32) -> Dict[str, np.ndarray]:
     """
     z = ops.conv1x1(_grid(spec, feats[3]), hw["seg_w"], hw["seg_b"])
     Z = ops.bilinear(z, spec.img_h, spec.img_w)
-    return {"logits": z, "classmap": _decide(Z, decide_dtype)}
+    return {"logits": z, "classmap": _decide(Z)}
 
 
-def det_head(spec, hw, feats, decide_dtype=np.float32) -> Dict[str, np.ndarray]:
+def det_head(spec, hw, feats) -> Dict[str, np.ndarray]:
     """Dense detection head: two parallel 3x3 conv towers (D -> Ch, ReLU) on the final
     patch grid; class tower -> 1x1 to the class logits, box tower -> 1x1 to 4 offsets.
     Raw outputs (no sigmoid, decoding or NMS).  Returns logits [K][gh][gw], box [4][gh][gw],
@@ -128,7 +128,7 @@ def det_head(spec, hw, feats, decide_dtype=np.float32) -> Dict[str, np.ndarray]:
     tb = ops.conv3x3(g, hw["box_tower_w"], hw["box_tower_b"], relu=True)
     logits = ops.conv1x1(tc, hw["cls_w"], hw["cls_b"])
     box = ops.conv1x1(tb, hw["box_w"], hw["box_b"])
-    return {"logits": logits, "box": box, "classmap": _decide(logits, decide_dtype)}
+    return {"logits": logits, "box": box, "classmap": _decide(logits)}
 
 
 def depth_head(spec, hw, feats, return_stages: bool = False) -> Dict[str, np.ndarray]:
@@ -152,8 +152,8 @@ def depth_head(spec, hw, feats, return_stages: bool = False) -> Dict[str, np.nda
             stages.append({"p": p, "z": z, "r": r})
     d = ops.conv1x1(y, hw["out_w"], hw["out_b"])
     pre = ops.bilinear(d, spec.img_h, spec.img_w)[0]
-    # "pre_relu" is returned as the yardstick for errors: with random weights the map can be clipped
-    # almost everywhere, and max |depth| then says nothing about the size of the signal
+    # "pre_relu" (the map before its final ReLU) is returned beside the result so that a test can tell how much
+    # of the signal the ReLU removed
     out = {"depth": np.maximum(pre, 0.0), "pre_relu": pre}
     if return_stages:
         out["stages"] = stages

@@ -156,8 +156,8 @@ def test_encoder_and_heads_equal_library_composition(mlp_kind, registers):
     tfeats = _torch_encoder(spec, w, img)
     for a, b in zip(feats, tfeats):
         assert relerr(a, b.numpy()) < 1e-12
-    seg = model.seg_head(spec, hs, feats, decide_dtype=np.float64)
-    det = model.det_head(spec, hd, feats, decide_dtype=np.float64)
+    seg = model.seg_head(spec, hs, feats)
+    det = model.det_head(spec, hd, feats)
     dep = model.depth_head(spec, hp, feats)
     tseg, tsegmap, tlog, tbox, tdepth = _torch_heads(spec, hs, hd, hp, tfeats)
     assert relerr(seg["logits"], tseg.numpy()) < 1e-12
