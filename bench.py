@@ -14,12 +14,22 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
-# HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
-# calibrated against a 1 GiB copy (profiles/conv3x3_cfg2_hbm_traffic.txt); only the workload measured has one.
-TRAFFIC_BYTES = {"vits14_bf16_476x630": 64.3e6}
+
+
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of the dominant kernel as the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes measured
+    them (calibrated against a 1 GiB copy): the `traffic_bytes_per_launch:` line of the tracked summary
+    profiles/<kernel>_<workload>_hbm_traffic.txt, or None when no such pass has been taken for this workload."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.strip().startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def backbone_flops(spec) -> float:
@@ -286,7 +296,7 @@ def main() -> None:
 
     import paper_2508_11584_amd as vpe
     import vpe_inputs as vi
-    from helpers import make_engine
+    from paper_2508_11584_amd.synthetic import make_engine
 
     if args.experiment == "multihead":
         multihead_experiment(args, vpe, vi, make_engine, np, torch)
@@ -304,6 +314,7 @@ def main() -> None:
         spec = vi.with_(spec, head_ch=args.head_ch)
     flags = 0 if args.no_graphs else vpe.VPE_FLAG_GRAPHS
     eng, w, hw = make_engine(spec, wseed, kinds=kinds, ring_slots=args.ring_slots, flags=flags, encoder_lanes=args.encoder_lanes)
+    head_streams = min(len(kinds), max(1, 4 - args.encoder_lanes))      # the engine's rule (include/vpe.h, head_streams = 0)
     images_np = vi.make_batch(spec, iseed)
     # two distinct resident frames, alternated, so no step can reuse the previous step's result
     frames = [torch.from_numpy(images_np).cuda(), torch.from_numpy(np.ascontiguousarray(images_np[..., ::-1])).cuda()]
@@ -322,12 +333,18 @@ def main() -> None:
             fh = eng.encode(frames[i & 1], stream=one)
             eng.run_head(h, fh, stream=one)
 
+    def independent_pipelined_step(i):
+        # the same baseline given everything the shared path gets -- the engine's encoder lanes, head streams,
+        # ring and hardware queues: one encoder pass per head, consecutive passes overlapping on the lanes
+        for h in range(nh):
+            fh = eng.encode(frames[i & 1])
+            eng.run_head(h, fh)
+
     def encode_step(i):
         eng.encode(frames[i & 1])
 
-    def timed(fn, steps, warmup):
-        for i in range(warmup):
-            fn(i)
+    def bracketed(fn, steps):
+        """Seconds for `steps` steps between two synchronisations (pipeline fill and drain included)."""
         eng.sync()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -335,7 +352,20 @@ def main() -> None:
             fn(i)
         eng.sync()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        return time.perf_counter() - t0
+
+    def timed(fn, steps, warmup):
+        """Seconds per step in steady state.  A run of n steps between two synchronisations costs the steady
+        time of n steps plus one fill-and-drain of the pipeline (about one frame latency, whatever n is); timing
+        `prime + steps` steps and `prime` steps and taking the difference leaves exactly `steps` steady-state
+        steps, so a short run and a long run report the same rate.  Returns (steady, bracketed) seconds per step,
+        the second being the plain synchronise / steps / synchronise figure."""
+        for i in range(warmup):
+            fn(i)
+        prime = 2 * args.encoder_lanes + 2
+        short = sorted(bracketed(fn, prime) for _ in range(5))[2]
+        long_ = bracketed(fn, prime + steps)
+        return (long_ - short) / steps, bracketed(fn, steps) / steps
 
     if args.roofline_only:
         shared_step(0)
@@ -352,23 +382,26 @@ def main() -> None:
         eng.close()
         return
 
-    t_shared = timed(shared_step, args.steps, args.warmup)
+    t_shared, t_shared_bracketed = timed(shared_step, args.steps, args.warmup)
 
     # the same step fed from raw camera frames (paper: 1920x1080 streams): uint8 -> resize -> normalise on the GPU
     # in front of the encoder, each frame on the engine stream its encoder pass will use
     cams = [torch.from_numpy(vi.make_camera_frame(1080, 1920, iseed + 100 + i)[None].repeat(spec.batch, axis=0)).cuda() for i in range(2)]
-    cam_imgs = [torch.empty_like(frames[0]) for _ in range(args.ring_slots)]
+    # one image buffer per encoder lane: the transform of frame i runs on the stream of lane i % lanes, after that
+    # lane's previous encoder pass (frame i - lanes), the only reader of the buffer it overwrites
+    cam_imgs = [torch.empty_like(frames[0]) for _ in range(args.encoder_lanes)]
 
     def camera_step(i):
-        img = cam_imgs[i % args.ring_slots]
+        img = cam_imgs[eng.stats()[0] % args.encoder_lanes]
         vpe.preprocess_u8(cams[i & 1], img, vi.CAMERA_MEAN, vi.CAMERA_STD, stream=eng.next_encode_stream())
         fh = eng.encode(img)
         for h in range(nh):
             eng.run_head(h, fh)
 
-    t_cam = timed(camera_step, args.steps, args.warmup)
-    t_seq = timed(sequential_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
-    t_enc = timed(encode_step, args.steps, args.warmup)
+    t_cam, _ = timed(camera_step, args.steps, args.warmup)
+    t_seq, _ = timed(sequential_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
+    t_ind, _ = timed(independent_pipelined_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
+    t_enc, _ = timed(encode_step, args.steps, args.warmup)
     fps = spec.batch / t_shared
 
     # unloaded latency of one frame as the host sees it: submit encode + heads on an idle GPU, wait for all
@@ -397,8 +430,18 @@ def main() -> None:
             peak = MFMA_PEAK_TFLOPS[spec.dtype]
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
-                        "frac": round(ach / peak, 4), "traffic": args.traffic_bytes if args.traffic_bytes is not None else (TRAFFIC_BYTES.get(spec.name) if name == "depth_conv3x3" and not args.head_ch else None), "us_per_launch": round(ms * 1e3, 2),
+                        "frac": round(ach / peak, 4),
+                        "traffic": args.traffic_bytes if args.traffic_bytes is not None else (measured_traffic(name, spec.name) if not args.head_ch else None),
+                        "us_per_launch": round(ms * 1e3, 2),
                         "algorithmic_bytes": by, "algorithmic_flops": fl}
+
+    # the same step on an engine created with the library's defaults (one encoder lane, ring of two, as many head
+    # streams as heads): what an application gets without choosing lanes, ring and hardware queues
+    eng.close()
+    eng, _, _ = make_engine(spec, wseed, kinds=kinds, ring_slots=2, flags=flags, encoder_lanes=1, weights=w)
+    lanes_used, args.encoder_lanes = args.encoder_lanes, 1
+    t_default, _ = timed(shared_step, max(args.steps // 3, 10), max(args.warmup // 3, 3))
+    args.encoder_lanes = lanes_used
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -418,11 +461,20 @@ def main() -> None:
         "ms_per_step": round(t_shared * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "batch": spec.batch, "img": [spec.img_h, spec.img_w], "tokens": spec.tokens,
-                   "heads": list(kinds), "ring_slots": args.ring_slots, "encoder_lanes": args.encoder_lanes, "hw_queues": args.hw_queues, "hip_graphs": not args.no_graphs},
+                   "heads": list(kinds), "ring_slots": args.ring_slots, "encoder_lanes": args.encoder_lanes, "head_streams": head_streams,
+                   "hw_queues": args.hw_queues, "hip_graphs": not args.no_graphs, "timing": "steady state: (t(prime + steps) - t(prime)) / steps"},
         "backbone_tflops": round(bb_tflops, 2), "backbone_ms": round(t_enc * 1e3, 4),
         "backbone_mfma_frac": round(bb_tflops / MFMA_PEAK_TFLOPS[spec.dtype], 4),
         "from_1080p_uint8_fps": round(spec.batch / t_cam, 2),
-        "sequential_baseline_fps": round(spec.batch / t_seq, 2), "shared_vs_sequential": round(t_seq / t_shared, 3),
+        "library_defaults_fps": round(spec.batch / t_default, 2),
+        "fps_incl_fill_and_drain": round(spec.batch / t_shared_bracketed, 2),
+        # sequential baseline (each head recomputes its own backbone pass): on one stream, one frame at a time, and
+        # with the same lanes / streams / queues as the shared path; the like-for-like ratios are latency against
+        # latency and pipelined against pipelined
+        "sequential_baseline_fps": round(spec.batch / t_seq, 2), "sequential_baseline_pipelined_fps": round(spec.batch / t_ind, 2),
+        "shared_vs_sequential": round(t_ind / t_shared, 3),
+        "shared_vs_sequential_latency": round(t_seq * 1e3 / latency["median"], 3),
+        "shared_pipelined_vs_sequential_one_stream": round(t_seq / t_shared, 3),
         "frame_latency_ms": latency, "kernels": kern, "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

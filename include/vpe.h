@@ -22,6 +22,15 @@
   *     that call (one stream per encoder lane, one stream per head, all at default priority).
  *   - vpe_encode and vpe_run_head only enqueue work; vpe_sync blocks until it is done.
  *   - an engine may be driven from one host thread at a time.
+ *
+ * Throughput.  With the defaults (encoder_lanes = 1) frames pass through the encoder one after another and a
+ * ViT-S pass leaves most of the 256 compute units idle (about 1000 frames/s at 476x630 with three heads).  The
+ * pipelined rate the benchmark reports (about 1800 frames/s) needs encoder_lanes = 3 and ring_slots = 4 (lanes + 1),
+ * which makes the engine use 3 encoder streams + 1 head stream, AND a process that may use five hardware queues:
+ * export GPU_MAX_HW_QUEUES=5 before the HIP runtime initialises (the runtime's default of 4 leaves three for the
+ * engine beside the default stream's, and the fourth engine stream then shares a queue and serialises; with the
+ * default limit the best choice is encoder_lanes = 2, ring_slots = 3: about 1450 frames/s).  The batched
+ * configurations (4 or 8 views per step) want encoder_lanes = 2, ring_slots = 3.
  */
 #ifndef VPE_H
 #define VPE_H
@@ -48,8 +57,10 @@ enum {
     VPE_FLAG_GRAPHS = 1,     /* replay the encoder and the heads as captured HIP graphs */
     VPE_FLAG_HOST_ONLY = 2,  /* no device at all: calls do the scheduling bookkeeping only (slot ring, rates,
                                 staleness, counters); for exercising the host logic on a machine without a GPU */
-    VPE_FLAG_WALL_CLOCK = 4  /* vpe_encode stamps each frame with the host's steady clock (seconds since
+    VPE_FLAG_WALL_CLOCK = 4, /* vpe_encode stamps each frame with the host's steady clock (seconds since
                                 vpe_create), so limits in Hz act on real time without the caller keeping one */
+    VPE_FLAG_TIMING = 8      /* record HIP events with timing around every encoder pass and head run, for
+                                vpe_stage_times (two more event records per enqueue) */
 };
 
 /*
@@ -142,7 +153,8 @@ typedef struct {
     uint64_t weights_bytes;
 } vpe_head_cfg;
 
-/* Device bytes the engine needs for weights, scratch, the feature ring and head outputs.
+/* Device bytes the engine needs for weights, scratch, the feature ring and head outputs (paper, Sec. "Memory
+ * Management": buffer sizes are fixed by the configuration and allocated once at start-up).
  * Returns 0 and sets *bytes, or VPE_EINVAL. */
 int vpe_workspace_bytes(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_heads, uint64_t* bytes);
 
@@ -154,9 +166,12 @@ int vpe_workspace_bytes(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, 
 int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_heads,
                void* workspace, uint64_t workspace_bytes, vpe_engine** out);
 
-/* Encode one batch: images = DEVICE fp32 [batch][3][img_h][img_w], already normalised; it must
+/* The foundation module's step (paper, Sec. "Foundation Module": input -> foundation model -> middle buffer,
+ * and Sec. "Data Flow": the middle buffer is a circular buffer that overwrites its oldest entry).
+ * Encode one batch: images = DEVICE fp32 [batch][3][img_h][img_w], already normalised; it must
  * stay valid until the enqueued work has run.  Picks ring slot frame % ring_slots, waits (on
- * the GPU) for heads still reading that slot, runs the encoder, and returns the handle. */
+ * the GPU) for heads still reading that slot, runs the encoder, and returns the handle.
+ * Errors: VPE_EINVAL (null engine / images / out), VPE_EHIP (a launch failed). */
 int vpe_encode(vpe_engine* e, const float* images, void* stream, vpe_feat* out);
 
 /* Camera-frame transform in front of vpe_encode (paper, Sec. "Transforms": the pre-processing adapter between
@@ -182,8 +197,12 @@ int vpe_next_encode_stream(vpe_engine* e, void** stream);
  * not limited in Hz, unless the engine was created with VPE_FLAG_WALL_CLOCK.  t_seconds must not decrease from one frame to the next (VPE_EINVAL). */
 int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_seconds, vpe_feat* out);
 
-/* Run head `head` on a frame's features.  Returns VPE_SKIPPED when fh.frame % every_n != 0,
- * VPE_ESTALE when the slot has been reused by a later frame. */
+/* A head module's step (paper, Sec. "Head Module": each head reads the middle buffer asynchronously, by
+ * reference, runs its model and leaves its post-processed result in its output buffer; Sec. "Dynamic Frequency
+ * Control" for the rate).  Enqueues head `head` on the features of frame fh, in place, on `stream` (NULL = the
+ * head's own stream) after the frame's encoder pass and the head's previous run.  Returns VPE_SKIPPED when
+ * fh.frame % every_n != 0 or a limit in Hz says the frame is not due, VPE_ESTALE when the slot has been reused by
+ * a later frame, VPE_EINVAL for an unknown head or a handle this engine did not produce, VPE_EHIP. */
 int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream);
 
 /* Has the encoder finished writing this frame's features?  VPE_OK = yes, VPE_BUSY = still executing,
@@ -215,7 +234,9 @@ int vpe_run_head_latest(vpe_engine* e, int head, void* stream, vpe_feat* ran_on)
  *   out[7] reserved (0). */
 int vpe_head_counters(vpe_engine* e, int head, int64_t out[8]);
 
-/* Change a head's rate; takes effect from the next vpe_run_head.  every_n_frames < 1 -> VPE_EINVAL. */
+/* Change a head's rate at run time (paper, Sec. "Dynamic Frequency Control": the rate of every head can be
+ * adjusted while the engine runs): the head runs on frame f iff f % every_n_frames == 0.  Takes effect from the
+ * next vpe_run_head.  every_n_frames < 1 or an unknown head -> VPE_EINVAL. */
 int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames);
 
 /* Upper limit on a head's rate in runs per second of frame time (paper, Sec. "Dynamic Frequency Control"
@@ -229,29 +250,56 @@ int vpe_set_head_rate(vpe_engine* e, int head, int every_n_frames);
  * (both must pass).  Takes effect from the next vpe_run_head; max_hz < 0 or not finite -> VPE_EINVAL. */
 int vpe_set_head_rate_hz(vpe_engine* e, int head, double max_hz);
 
-/* Borrowed DEVICE pointer to feature map `tap` (0..3, 3 = final tokens) of a frame:
- * [batch][N][dim] in the engine's dtype.  Valid until the slot is reused. */
+/* The middle buffer's labelled entries (paper, Sec. "Data Flow": features are kept as named tensors and handed
+ * over by reference; Sec. "Memory Management": no copies between modules).  Borrowed DEVICE pointer to feature
+ * map `tap` (0..3 = after blocks taps[0..3], 3 = the final tokens) of a frame: [batch][N][dim] in the engine's
+ * dtype.  Valid until the slot is reused (VPE_ESTALE once it has been); VPE_EINVAL for a bad tap or handle. */
 int vpe_feat_view(vpe_engine* e, vpe_feat fh, int tap, const void** dev_ptr, int64_t shape[3]);
 
-/* Borrowed DEVICE pointer to output `which` of a head (see vpe_head_cfg); shape is padded
- * with 1s to four entries.  Contents are those of the head's most recent run. */
+/* A head's output buffer (paper, Sec. "Head Module": post-processed results are placed in an output buffer).
+ * Borrowed DEVICE pointer to output `which` of a head (see vpe_head_cfg); shape is padded with 1s to four
+ * entries.  One instance per head: contents are those of the head's most recent run once vpe_head_done says it
+ * has finished, and the head's next run overwrites them (a consumer that needs a result for longer copies it,
+ * or orders its own stream after the run with the stream argument of vpe_run_head).  VPE_EINVAL if the head
+ * has no such output. */
 int vpe_head_output(vpe_engine* e, int head, int which, const void** dev_ptr, int64_t shape[4]);
 
-/* Block until everything enqueued through this engine has finished. */
+/* Has head `head` finished its most recent run (paper, Sec. "Head Module": consumers take results from the
+ * head's output buffer; Sec. "Decentralization": nobody blocks on anybody)?  VPE_OK = yes (or it never ran),
+ * VPE_BUSY = still executing.  Never blocks.  vpe_wait_head blocks the host until that run has finished (that
+ * head only: other heads and the encoder keep going). */
+int vpe_head_done(vpe_engine* e, int head);
+int vpe_wait_head(vpe_engine* e, int head);
+
+/* Block until everything enqueued through THIS engine has finished (its encoder passes and head runs, on
+ * whichever streams they were put); other work of the process on the device is not waited for. */
 int vpe_sync(vpe_engine* e);
 
-/* Counters: frames encoded, and per head (up to n entries) how often it ran / was skipped. */
+/* Counters (paper, Appendix "Rate-Limiting Experiment": delivered runs per head): frames encoded, and per head
+ * (up to n entries) how often it ran / was skipped.  Any output pointer may be NULL. */
 int vpe_stats(vpe_engine* e, int64_t* frames, int64_t* head_runs, int64_t* head_skips, int n);
 
-/* Timing aid for benchmarks: enqueue `reps` repetitions of one internal kernel family on the
- * encoder stream with HIP events around them and return the mean milliseconds per launch.
+/* Device time of the most recent encoder pass and of each head's most recent run, in milliseconds (paper, Sec.
+ * "Example implementation" reports per-head inference times): *encode_ms and head_ms[0 .. n-1]; -1 where nothing
+ * has run yet or the run is still executing.  Needs VPE_FLAG_TIMING (else VPE_EINVAL).  Never blocks.  The span
+ * is from the start of the stage's first kernel to the end of its last on its stream; under load it includes
+ * the time the stage's kernels shared the device with other stages. */
+int vpe_stage_times(vpe_engine* e, float* encode_ms, float* head_ms, int n);
+
+/* Timing aid for benchmarks and counter passes (not part of the data path): waits until the engine is idle, then
+ * enqueues `reps` repetitions of one internal kernel family on the encoder stream with HIP events around them and
+ * returns the mean milliseconds per launch.  It overwrites scratch of encoder lane 0 and of the depth head only
+ * (buffers that the next encode / head run rewrites before reading); feature slots and head outputs are untouched.
  * which: 0 = the fused-QKV GEMM of block 0 on the current activations, 1 = the attention
  * kernel of block 0, 2 = LayerNorm, 3 = the depth head's largest 3x3 convolution (last fusion stage; needs a
  * depth head), 4 = the resample-and-add kernel that writes that convolution's input (needs a depth head).
  * Also reports the algorithmic flops and bytes of one launch. */
 int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes);
 
-const char* vpe_last_error(vpe_engine* e);            /* engine may be NULL: last create error */
+/* Message of the most recent failure of a call on this engine (engine may be NULL: the last failure of a call
+ * that had no engine, on this thread).  Borrowed; valid until the next failing call. */
+const char* vpe_last_error(vpe_engine* e);
+/* Waits for the device, destroys streams, events and graphs, frees the workspace if the library allocated it. */
 void vpe_destroy(vpe_engine* e);
 
 #ifdef __cplusplus

@@ -16,7 +16,7 @@ VPE_OK, VPE_SKIPPED, VPE_BUSY, VPE_EINVAL, VPE_ENOMEM, VPE_ESTALE, VPE_EHIP = 0,
 VPE_F32, VPE_BF16 = 0, 1
 VPE_MLP_GELU, VPE_MLP_SWIGLU = 0, 1
 VPE_HEAD_SEG, VPE_HEAD_DEPTH, VPE_HEAD_DET, VPE_HEAD_DPT = 0, 1, 2, 3
-VPE_FLAG_GRAPHS, VPE_FLAG_HOST_ONLY, VPE_FLAG_WALL_CLOCK = 1, 2, 4
+VPE_FLAG_GRAPHS, VPE_FLAG_HOST_ONLY, VPE_FLAG_WALL_CLOCK, VPE_FLAG_TIMING = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libvpe.so")
@@ -73,6 +73,9 @@ def load_library(path: Optional[str] = None):
     L.vpe_feat_view.argtypes = [vp, vpe_feat, i32, C.POINTER(vp), i64p]
     L.vpe_head_output.argtypes = [vp, i32, i32, C.POINTER(vp), i64p]
     L.vpe_sync.argtypes = [vp]
+    L.vpe_head_done.argtypes = [vp, i32]
+    L.vpe_wait_head.argtypes = [vp, i32]
+    L.vpe_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32]
     L.vpe_stats.argtypes = [vp, i64p, i64p, i64p, i32]
     L.vpe_time_kernel.argtypes = [vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.vpe_last_error.argtypes = [vp]
@@ -81,7 +84,7 @@ def load_library(path: Optional[str] = None):
     L.vpe_destroy.restype = None
     for n in ("vpe_workspace_bytes", "vpe_create", "vpe_encode", "vpe_encode_at", "vpe_run_head", "vpe_set_head_rate",
               "vpe_set_head_rate_hz", "vpe_preprocess_u8", "vpe_next_encode_stream", "vpe_feat_view",
-              "vpe_head_output", "vpe_sync", "vpe_stats", "vpe_time_kernel", "vpe_run_head_latest", "vpe_head_counters", "vpe_frame_ready"):
+              "vpe_head_output", "vpe_sync", "vpe_head_done", "vpe_wait_head", "vpe_stage_times", "vpe_stats", "vpe_time_kernel", "vpe_run_head_latest", "vpe_head_counters", "vpe_frame_ready"):
         getattr(L, n).restype = C.c_int
     if path is None:
         _lib = L
@@ -228,6 +231,30 @@ def vpe_sync(engine) -> None:
         raise VpeError(rc, vpe_last_error(engine))
 
 
+def vpe_head_done(engine, head: int) -> int:
+    """VPE_OK or VPE_BUSY."""
+    rc = lib().vpe_head_done(engine, head)
+    if rc < 0:
+        raise VpeError(rc, vpe_last_error(engine))
+    return rc
+
+
+def vpe_wait_head(engine, head: int) -> None:
+    rc = lib().vpe_wait_head(engine, head)
+    if rc:
+        raise VpeError(rc, vpe_last_error(engine))
+
+
+def vpe_stage_times(engine, n_heads: int):
+    """(encode_ms, [head_ms...]); -1 where there is no figure yet."""
+    enc = C.c_float(-1.0)
+    heads = (C.c_float * max(n_heads, 1))()
+    rc = lib().vpe_stage_times(engine, C.byref(enc), heads, n_heads)
+    if rc:
+        raise VpeError(rc, vpe_last_error(engine))
+    return float(enc.value), [float(v) for v in heads][:n_heads]
+
+
 def vpe_stats(engine, n_heads: int):
     frames = C.c_int64(0)
     runs = (C.c_int64 * max(n_heads, 1))()
@@ -334,6 +361,15 @@ class Engine:
 
     def stats(self):
         return vpe_stats(self.handle, self.n_heads)
+
+    def head_done(self, head: int) -> bool:
+        return vpe_head_done(self.handle, head) == VPE_OK
+
+    def wait_head(self, head: int) -> None:
+        vpe_wait_head(self.handle, head)
+
+    def stage_times(self):
+        return vpe_stage_times(self.handle, self.n_heads)
 
     def time_kernel(self, which: int, reps: int):
         return vpe_time_kernel(self.handle, which, reps)

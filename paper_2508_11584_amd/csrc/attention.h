@@ -16,15 +16,19 @@
 
 namespace vpe {
 
-// The loader reads up to 2 * 4 * 64 key rows past the last token of qk and as many columns past the end of vt
-// (prefetch of tiles that do not exist); both buffers must be readable that far.  What is read there is never
-// used.
+// The loader prefetches one iteration (KW key tiles) ahead without clamping, so a workgroup with KW key waves
+// reads up to 2 KW 64 key rows past the last token of qk and as many elements past the end of vt (tiles that do
+// not exist); both buffers must be readable that far.  What is read there is never used.  `pad` states how many
+// rows of qk / elements of vt past their ends the caller made readable; a launch whose shape needs more is refused.
+constexpr int ATTN_MAX_KW = 4;                        // widest key split of any instantiation
+constexpr int ATTN_PAD = 2 * ATTN_MAX_KW * 64;        // rows / elements a caller has to provide for any shape
 struct AttnArgs {
     const void* qk;
     const void* vt;
     void* out;
     int B, N, npad, dim, heads;
     float scale_log2e;   // (1 / sqrt(64)) * log2(e)
+    int pad;             // readable rows of qk / elements of vt past their ends
 };
 
 // --- per-type pieces: fragments for S^T = K Q^T and O^T = V^T P^T over a block of 32 keys
@@ -124,6 +128,7 @@ template <> struct AttnMma<float> {
 template <typename T, int QB, int QW, int KW>
 __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs p) {
     constexpr int NW = QW * KW, NT = 64 * NW;
+    static_assert(KW <= ATTN_MAX_KW, "the loader's overshoot is budgeted for at most ATTN_MAX_KW key waves");
     constexpr int CE = Elem<T>::CE;
     constexpr int CPR = 64 / CE;                 // 16-byte chunks per 64-element row
     constexpr int ROWB = AttnMma<T>::ROWB;
@@ -366,6 +371,7 @@ static inline hipError_t launch_attention_variant(const AttnArgs& a, hipStream_t
         configured = true;
     }
     if (configure_only) return hipSuccess;
+    if (a.pad < 2 * KW * 64 || a.npad % 64 || a.npad < a.N || a.dim != a.heads * 64) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attention_kernel<T, QB, QW, KW>), dim3(cdiv(a.N, 32 * QB * QW), a.B * a.heads),
                        dim3(64 * QW * KW), lds, s, a);
     return hipGetLastError();

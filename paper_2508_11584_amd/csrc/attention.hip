@@ -24,8 +24,13 @@ static hipError_t launch_variant(int variant, const AttnArgs& a, hipStream_t s, 
     return hipErrorInvalidValue;
 }
 
+// VPE_ATTN_VARIANT = 100 QB + 10 QW + KW overrides the choice of shape (tuning aid; read when an engine is created).
+static int g_forced_variant = 0;
+
 // LDS opt-in for every instantiation; called once at engine creation, outside any stream capture.
 hipError_t configure_attention() {
+    const char* env = getenv("VPE_ATTN_VARIANT");
+    g_forced_variant = env ? atoi(env) : 0;
     static const int all[] = {114, 141, 214, 122, 124, 224};
     AttnArgs a{};
     for (int v : all) {
@@ -38,8 +43,7 @@ hipError_t configure_attention() {
 }
 
 hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {
-    const char* env = getenv("VPE_ATTN_VARIANT");
-    const int forced = env ? atoi(env) : 0;
+    const int forced = g_forced_variant;
     // Workgroup shapes measured on MI355X (QB, QW, KW = query blocks per wave, query waves, key waves), us:
     //                                         (1,2,4) (1,2,2) (2,2,4) (1,4,1) (2,1,4) (1,1,4)
     //   ViT-S 476x630   (6 x N 1531)            15.8    19.5    22.9    30.0    20.6    28.0
@@ -48,7 +52,6 @@ hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {
     //   ViT-g 518x518 x8 (192 x N 1374)        251.2   217.1   212.1   193.3   334.0   447.4
     // Few (head, 32-query block) pairs want the key axis split over waves to fill the chip; many want one
     // wave per query block over all keys (no merge, small LDS footprint, several workgroups per CU).
-    // VPE_ATTN_VARIANT = 100 QB + 10 QW + KW overrides the choice (tuning aid).
     const int64_t qblocks = (int64_t)cdiv(a.N, 32) * a.B * a.heads;
     int variant = qblocks >= 2048 ? 141 : qblocks >= 400 ? 224 : 124;
     if (forced) variant = forced;

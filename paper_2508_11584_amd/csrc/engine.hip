@@ -104,6 +104,7 @@ struct Head {
     // scheduling
     hipStream_t stream = nullptr;     // one of the engine's head streams (shared when heads outnumber them)
     hipEvent_t last_done = nullptr;   // completion of the most recent run (any slot)
+    hipEvent_t t_begin = nullptr, t_end = nullptr;   // around the most recent run (engines created with VPE_FLAG_TIMING)
     bool ran = false;
     int64_t runs = 0, skips = 0;
     double period = 0.0;              // 1 / max_hz, 0 = no limit in Hz
@@ -122,7 +123,8 @@ struct Head {
 
 struct vpe_engine {
     vpe_backbone_cfg cfg{};
-    bool bf = true, host_only = false, graphs = false, owns_ws = false;
+    bool bf = true, host_only = false, graphs = false, owns_ws = false, timing = false;
+    int last_lane = -1;                  // lane of the most recent encode
     int D = 0, L = 0, nh = 0, Mh = 0, F = 0, R = 0, B = 0, H = 0, W = 0, gh = 0, gw = 0, P = 0, N = 0, T = 0;
     int npad = 0, esz = 2, S = 1;
     char* ws = nullptr;
@@ -145,6 +147,7 @@ struct vpe_engine {
         float* lev[2] = {nullptr, nullptr};   // [T] row levels the copy u is stored against, alternating (see ln_gemm)
         hipStream_t stream = nullptr;
         hipEvent_t done = nullptr;      // completion of the lane's most recent encode
+        hipEvent_t t_begin = nullptr, t_end = nullptr;   // around it (engines created with VPE_FLAG_TIMING)
         bool used = false;
     };
     int lanes = 1;
@@ -260,6 +263,7 @@ void derive(vpe_engine& e, const vpe_backbone_cfg& c, const vpe_head_cfg* heads,
     e.esz = e.bf ? 2 : 4;
     e.host_only = false;
     e.graphs = (c.flags & VPE_FLAG_GRAPHS) != 0;
+    e.timing = (c.flags & VPE_FLAG_TIMING) != 0;
     e.D = c.dim; e.L = c.depth; e.nh = c.heads; e.Mh = c.mlp_hidden;
     e.F = c.mlp_hidden * (c.mlp_kind == VPE_MLP_SWIGLU ? 2 : 1);
     e.R = c.registers; e.B = c.batch; e.H = c.img_h; e.W = c.img_w;
@@ -338,9 +342,9 @@ void layout(vpe_engine& e, Bump& b) {
         L.stats = f32(T * (D / 64) * 2);
         L.lev[0] = f32(T); L.lev[1] = f32(T);
         L.u = b.take(T * D * esz);
-        // + 512 rows / columns that the attention loader may prefetch past the end (never used)
-        L.qk = b.take((T + 512) * 2 * D * esz);
-        L.vt = b.take((B * D * e.npad + 512) * esz);
+        // + ATTN_PAD rows / elements that the attention loader may prefetch past the end (never used)
+        L.qk = b.take((T + ATTN_PAD) * 2 * D * esz);
+        L.vt = b.take((B * D * e.npad + ATTN_PAD) * esz);
         L.att = b.take(T * D * esz);
         L.hid = b.take(T * e.Mh * esz);
     }
@@ -656,7 +660,7 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         {
-            AttnArgs a{L.qk, L.vt, L.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f};
+            AttnArgs a{L.qk, L.vt, L.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f, ATTN_PAD};
             HIPCHK(&e, launch_attention(dt, a, s));
         }
         {
@@ -875,8 +879,10 @@ void destroy_engine(vpe_engine* e) {
         for (auto ev : e->done) if (ev) (void)hipEventDestroy(ev);
         for (auto& L : e->lane) {
             if (L.stream) (void)hipStreamDestroy(L.stream);
-            if (L.done) (void)hipEventDestroy(L.done);
+            for (hipEvent_t ev : {L.done, L.t_begin, L.t_end}) if (ev) (void)hipEventDestroy(ev);
         }
+        for (auto& h : e->heads)
+            for (hipEvent_t ev : {h.t_begin, h.t_end}) if (ev) (void)hipEventDestroy(ev);
         if (e->owns_ws && e->ws) (void)hipFree(e->ws);
     }
     delete e;
@@ -991,6 +997,14 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
         if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
     for (auto& ev : e->done)
         if (hip(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate")) return bail(VPE_EHIP);
+    if (e->timing) {
+        for (int l = 0; l < e->lanes; ++l)
+            for (hipEvent_t* ev : {&e->lane[l].t_begin, &e->lane[l].t_end})
+                if (hip(hipEventCreate(ev), "hipEventCreate")) return bail(VPE_EHIP);
+        for (auto& h : e->heads)
+            for (hipEvent_t* ev : {&h.t_begin, &h.t_end})
+                if (hip(hipEventCreate(ev), "hipEventCreate")) return bail(VPE_EHIP);
+    }
     e->enc_graphs.assign((size_t)e->S * e->lanes, nullptr);
     for (auto& h : e->heads) h.graphs.assign(e->S, nullptr);
     if (hip(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(VPE_EHIP);
@@ -1047,6 +1061,7 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
         if (e->slot_frame[slot] >= 0) HIPCHK(e, hipStreamWaitEvent(s, e->ready[slot], 0));
         // a lane's scratch is single-instance: order after the lane's previous encode
         if (L.used) HIPCHK(e, hipStreamWaitEvent(s, L.done, 0));
+        if (e->timing) HIPCHK(e, hipEventRecord(L.t_begin, s));
         HIPCHK(e, launch_im2col(e->bf, images, e->B, e->H, e->W, KPATCH_PAD, L.apatch, e->special, 1 + e->R,
                                 e->N, e->D, L.x, e->bf ? L.u : nullptr, L.stats, e->bf ? e->lev0 : nullptr, s));
         if (e->graphs) {
@@ -1056,8 +1071,10 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
         } else {
             TRY(enqueue_encoder_body(*e, slot, ln, s));
         }
+        if (e->timing) HIPCHK(e, hipEventRecord(L.t_end, s));
         HIPCHK(e, hipEventRecord(L.done, s));
         L.used = true;
+        e->last_lane = ln;
         HIPCHK(e, hipEventRecord(e->ready[slot], s));
     }
     for (int h = 0; h < nh; ++h) e->done_set[(size_t)slot * nh + h] = 0;
@@ -1094,6 +1111,7 @@ int start_head(vpe_engine* e, int head, int slot, int64_t frame, void* stream) {
         HIPCHK(e, hipStreamWaitEvent(s, e->ready[slot], 0));
         // the head's scratch and outputs are single-instance: order after its previous run
         if (h.ran) HIPCHK(e, hipStreamWaitEvent(s, h.last_done, 0));
+        if (e->timing) HIPCHK(e, hipEventRecord(h.t_begin, s));
         if (e->graphs) {
             if (!h.graphs[slot])
                 TRY(capture(*e, &h.graphs[slot], [&](hipStream_t cs) { return enqueue_head_body(*e, h, slot, cs); }));
@@ -1101,6 +1119,7 @@ int start_head(vpe_engine* e, int head, int slot, int64_t frame, void* stream) {
         } else {
             TRY(enqueue_head_body(*e, h, slot, s));
         }
+        if (e->timing) HIPCHK(e, hipEventRecord(h.t_end, s));
         hipEvent_t ev = e->done[(size_t)slot * nh + head];
         HIPCHK(e, hipEventRecord(ev, s));
         h.last_done = ev;
@@ -1226,7 +1245,58 @@ int vpe_head_output(vpe_engine* e, int head, int which, const void** dev_ptr, in
 int vpe_sync(vpe_engine* e) {
     if (!e) return VPE_EINVAL;
     if (e->host_only) return VPE_OK;
-    HIPCHK(e, hipDeviceSynchronize());
+    // every enqueue through the engine ends in an event of its own, whichever stream it went to: wait for those,
+    // not for the device (other work of the process is none of the engine's business)
+    for (int l = 0; l < e->lanes; ++l)
+        if (e->lane[l].used) HIPCHK(e, hipEventSynchronize(e->lane[l].done));
+    // (the slots' ready events follow the lanes' on the same streams; waiting for them too makes
+    // vpe_frame_ready answer VPE_OK for every frame as soon as this returns)
+    for (int sl = 0; sl < e->S; ++sl)
+        if (e->slot_frame[sl] >= 0) HIPCHK(e, hipEventSynchronize(e->ready[sl]));
+    for (Head& h : e->heads)
+        if (h.ran) HIPCHK(e, hipEventSynchronize(h.last_done));
+    return VPE_OK;
+}
+
+int vpe_head_done(vpe_engine* e, int head) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    const Head& h = e->heads[head];
+    if (e->host_only || !h.ran) return VPE_OK;
+    const hipError_t q = hipEventQuery(h.last_done);
+    if (q == hipErrorNotReady) return VPE_BUSY;
+    HIPCHK(e, q);
+    return VPE_OK;
+}
+
+int vpe_wait_head(vpe_engine* e, int head) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    const Head& h = e->heads[head];
+    if (e->host_only || !h.ran) return VPE_OK;
+    HIPCHK(e, hipEventSynchronize(h.last_done));
+    return VPE_OK;
+}
+
+int vpe_stage_times(vpe_engine* e, float* encode_ms, float* head_ms, int n) {
+    if (!e) return VPE_EINVAL;
+    if (!e->timing) return e->fail(VPE_EINVAL, "the engine was not created with VPE_FLAG_TIMING");
+    auto span = [&](bool ran, hipEvent_t b, hipEvent_t t, float* out) -> int {
+        *out = -1.0f;
+        if (!ran || e->host_only) return VPE_OK;
+        const hipError_t q = hipEventQuery(t);
+        if (q == hipErrorNotReady) return VPE_OK;              // still executing: no figure yet
+        HIPCHK(e, q);
+        HIPCHK(e, hipEventElapsedTime(out, b, t));
+        return VPE_OK;
+    };
+    if (encode_ms) {
+        const bool ran = e->last_lane >= 0;
+        const vpe_engine::Lane& L = e->lane[ran ? e->last_lane : 0];
+        TRY(span(ran, L.t_begin, L.t_end, encode_ms));
+    }
+    for (int i = 0; head_ms && i < n && i < (int)e->heads.size(); ++i)
+        TRY(span(e->heads[i].ran, e->heads[i].t_begin, e->heads[i].t_end, head_ms + i));
     return VPE_OK;
 }
 
@@ -1243,6 +1313,8 @@ int vpe_stats(vpe_engine* e, int64_t* frames, int64_t* head_runs, int64_t* head_
 int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes) {
     if (!e) return VPE_EINVAL;
     if (e->host_only || reps < 1 || !ms_per_launch) return e->fail(VPE_EINVAL, "bad arguments");
+    // the launches below write scratch of encoder lane 0 and of the depth head: nothing of the engine may be in flight
+    TRY(vpe_sync(e));
     hipStream_t s = e->lane[0].stream;
     const vpe_engine::Lane& L0 = e->lane[0];
     hipEvent_t t0, t1;
@@ -1261,10 +1333,11 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 a.epi = EPI_QKV; a.out = L0.qk; a.ldo = 2 * D; a.out2 = L0.vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
             } else if (which == 1) {
-                AttnArgs a{L0.qk, L0.vt, L0.att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f};
+                AttnArgs a{L0.qk, L0.vt, L0.att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f, ATTN_PAD};
                 HIPCHK(e, launch_attention(dt, a, s));
             } else if (which == 2) {
-                HIPCHK(e, launch_layernorm(dt, L0.x, T, D, e->blk[0].ln1_g, e->blk[0].ln1_b, e->cfg.ln_eps, L0.u, s));
+                // into the attention-output scratch: same size as a feature map, rewritten by the next encode before it is read
+                HIPCHK(e, launch_layernorm(dt, L0.x, T, D, e->norm_g, e->norm_b, e->cfg.ln_eps, L0.att, s));
             } else if (which == 4) {
                 // the stage input of that convolution: upsample of the tap projection + x2 upsample of the previous
                 // stage's output, 8x the patch grid (bandwidth-bound: reads 1/4 of what it writes)

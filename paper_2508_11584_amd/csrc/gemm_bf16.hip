@@ -15,7 +15,11 @@ namespace {
 // MI355X with random bf16 data: the QKV / proj / fc1 / fc2 GEMMs of ViT-S, -B, -L (batch 4) and -g (batch 8),
 // the heads' 1x1 projections, and the 3x3 convolutions at 34x45 ... 296x296 grids (batch 1 and 4).  The
 // model's pick is the measured best on 23 of them, within 8 % on four and 15 % on one (0.4 % in total time).
-// VPE_NO_SMALL_DMA in the environment leaves the two small direct-to-LDS shapes out (a tuning aid).
+// Tuning aids, read from the environment when an engine is created (configure_gemm_bf16), never per launch:
+// VPE_GEMM_TILE forces a tiling, VPE_NO_SMALL_DMA leaves the two small direct-to-LDS shapes out, VPE_NO_SPLITK
+// the split-k kernel.
+int g_forced_tile = 0;
+bool g_no_small = false, g_no_splitk = false;
 struct Cand { int kind, bm, bn, held; float alpha, beta; bool dma; };
 constexpr Cand kCands[] = {
     {128, 256, 128, 2, 5.16f, 1.055f, true},    // direct-to-LDS, 8 waves, 64 x 64 wave tiles
@@ -30,15 +34,14 @@ constexpr Cand kCands[] = {
 }  // namespace
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
-    const char* env = getenv("VPE_GEMM_TILE");
-    const int forced = env ? atoi(env) : 0;
+    const int forced = g_forced_tile;
     // the direct-to-LDS loader keeps byte offsets in 32-bit ints
     const int64_t a_rows = amode == A_PLAIN ? (int64_t)(a.M / a.a_rpi + 1) * (a.a_istride > a.a_rpi ? a.a_istride : a.a_rpi)
                                             : (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride;
     const bool fits = a_rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
     int best = 3;
     float best_cost = 0.0f;
-    static const bool no_small = getenv("VPE_NO_SMALL_DMA") != nullptr;
+    const bool no_small = g_no_small;
     for (const Cand& c : kCands) {
         if (c.dma && !fits) continue;
         if (no_small && (c.kind == 64 || c.kind == 65)) continue;
@@ -61,7 +64,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     // VPE_NO_SPLITK in the environment switches it off (a tuning aid).  A limit of 288 tiles, which takes in the
     // ViT-B proj / fc2 GEMMs (264 tiles), brings that model's frame latency from 1.79 to 1.70 ms but costs 1.5 % of its
     // pipelined rate with three encoder lanes.
-    static const bool no_splitk = getenv("VPE_NO_SPLITK") != nullptr;
+    const bool no_splitk = g_no_splitk;
     if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
     if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
     if (forced == 4) best = a.epi == EPI_SWIGLU ? 2 : 4;
@@ -78,6 +81,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
 
 // LDS opt-in of the split-k kernel; called once at engine creation, outside any stream capture.
 hipError_t configure_gemm_bf16() {
+    const char* env = getenv("VPE_GEMM_TILE");
+    g_forced_tile = env ? atoi(env) : 0;
+    g_no_small = getenv("VPE_NO_SMALL_DMA") != nullptr;
+    g_no_splitk = getenv("VPE_NO_SPLITK") != nullptr;
     GemmArgs a{};
     return launch_tile_splitk<bf16, 64, 64, 2, 2, 2>(a, A_PLAIN, nullptr, true);
 }

@@ -379,3 +379,18 @@ def test_preprocess_rejects_bad_arguments_before_touching_the_device():
                          (dict(src_h=40000, src_w=40000), "too large")]:
         with pytest.raises(vpe.VpeError, match=needle):
             vpe.vpe_preprocess_u8(**{**ok, **over})
+
+
+def test_head_completion_and_stage_times_without_a_device():
+    eng, _, _ = make_engine(vi.small_spec(), 1, flags=vpe.VPE_FLAG_HOST_ONLY | vpe.VPE_FLAG_TIMING)
+    assert eng.head_done(0)                                     # never ran: nothing to wait for
+    fh = eng.encode(None)
+    assert eng.run_head(1, fh) == vpe.VPE_OK
+    assert eng.head_done(1)
+    eng.wait_head(1)
+    assert eng.stage_times() == (-1.0, [-1.0, -1.0, -1.0])      # no device, no figures
+    with pytest.raises(vpe.VpeError):
+        vpe.vpe_head_done(eng.handle, 3)
+    plain, _, _ = make_engine(vi.small_spec(), 1, flags=vpe.VPE_FLAG_HOST_ONLY)
+    with pytest.raises(vpe.VpeError, match="VPE_FLAG_TIMING"):
+        plain.stage_times()

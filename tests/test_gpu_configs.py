@@ -2,10 +2,11 @@
 
 cfg 3 (ViT-B/14, 518x518, rates 1/2/3 over a 300-frame sequence) is run whole: every frame is pushed
 through the engine without host synchronisation, run counts are exact, and frames 0, 6 and 299 are
-compared with the oracle.  cfgs 4 and 5 (ViT-L batch 4, ViT-g batch 8) cost minutes per image in the
-fp64 oracle, so parity is taken on the same model with the SAME per-layer shapes (width, heads, MLP,
-tokens, batch, registers, head widths -- hence the same kernels, tiles and launch shapes) but only four
-blocks, plus properties that hold at full depth: batch independence, determinism, finite outputs.
+compared with the oracle.  cfgs 4 and 5 (ViT-L batch 4 with 24 blocks, ViT-g batch 8 with 40 blocks) are run
+whole as well, as the benchmark launches them (HIP graphs), and compared with the oracle at full depth on
+batch element 0 (the fp64 loops take about 15 s and 50 s for one image); the other batch elements are tied
+to element 0 by batch independence: swapping two views swaps the results bit for bit.  The four-block cuts
+of the same shapes stay as the quick variant (they also check the last batch element against the oracle).
 """
 import numpy as np
 import pytest
@@ -13,7 +14,7 @@ import torch
 
 import paper_2508_11584_amd as vpe
 import vpe_inputs as vi
-from helpers import depth_err, make_engine, relerr
+from helpers import depth_errs, depth_gate, make_engine, relerr
 from oracle import model
 from test_gpu_parity import check_all
 
@@ -47,15 +48,16 @@ def test_cfg3_vitb_sequence_rates_and_parity():
     eng.close()
     for t, g in got.items():
         feats = model.encode_image(spec, w, g["host"][0])
-        e = {"feat3": relerr(g["feat3"], feats[3]),
-             "depth": depth_err(g["depth"], model.depth_head(spec, hw[0], feats))}
+        de = depth_errs(g["depth"], model.depth_head(spec, hw[0], feats))
+        e = {"feat3": relerr(g["feat3"], feats[3]), "depth": de["stated"], "depth_pre_relu": de["pre_relu"],
+             "depth_positive": de["positive"]}
         if g["seg"] is not None:
             e["seg_agree"] = float(np.mean(g["seg"] == model.seg_head(spec, hw[1], feats)["classmap"]))
         if g["det"] is not None:
             o = model.det_head(spec, hw[2], feats)
             e["det_logits"] = relerr(g["det"][..., :80].transpose(2, 0, 1), o["logits"])
         print("cfg3 frame", t, {k: round(v, 5) for k, v in e.items()}, flush=True)
-        assert e["feat3"] <= 2e-2 and e["depth"] <= 2e-2
+        assert e["feat3"] <= 2e-2 and depth_gate(de, 2e-2), (e, de)
         assert e.get("seg_agree", 1.0) >= 0.99 and e.get("det_logits", 0.0) <= 2e-2
 
 
@@ -69,34 +71,36 @@ def test_cfg5_shapes_vitg_swiglu_batch8_four_blocks():
     check_all(spec, 1005, 2008, batch_check=(0, 7))
 
 
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("cfg", ["cfg4", "cfg5"])
-def test_full_depth_large_configs_run_and_are_consistent(cfg):
+def test_full_depth_large_configs_match_the_oracle_and_are_consistent(cfg):
     spec = vi.CONFIGS[cfg]
     wseed, iseed = vi.SEEDS[cfg]
-    eng, w, hw = make_engine(spec, wseed, flags=vpe.VPE_FLAG_GRAPHS)
-    del w, hw
-    imgs = vi.make_batch(spec, iseed)
-    dev = torch.from_numpy(imgs).cuda()
-    outs = []
-    for _ in range(2):
-        fh = eng.encode(dev)
+
+    def on_device(eng, imgs, fh0, feats0, outs0):
+        # determinism (the second pass lands in the other ring slot and replays its own graphs)
+        fh = eng.encode(torch.from_numpy(imgs).cuda())
         for h in range(3):
             assert eng.run_head(h, fh) == 0
         eng.sync()
-        outs.append([eng.feat_view(fh, 3).clone(), eng.head_output(1, 0).clone(), eng.head_output(0, 1).clone()])
-    for a, b in zip(*outs):
-        assert torch.equal(a, b)                              # deterministic, and both ring slots agree
-    feat, depth, segmap = outs[0]
-    assert torch.isfinite(feat.float()).all() and torch.isfinite(depth).all() and depth.min() >= 0
-    assert not torch.equal(feat[0], feat[1])                  # different views give different features
-    assert int(segmap.max()) < spec.seg_classes
-    # batch independence at full depth: a batch with two views swapped gives the swapped results
-    perm = list(range(spec.batch))
-    perm[0], perm[-1] = perm[-1], perm[0]
-    fh = eng.encode(torch.from_numpy(np.ascontiguousarray(imgs[perm])).cuda())
-    for h in range(3):
-        eng.run_head(h, fh)
-    eng.sync()
-    assert torch.equal(eng.feat_view(fh, 3)[0], feat[-1]) and torch.equal(eng.feat_view(fh, 3)[-1], feat[0])
-    assert torch.equal(eng.head_output(1, 0)[0], depth[-1])
-    eng.close()
+        feat = eng.feat_view(fh, 3).clone()
+        depth = eng.head_output(1, 0).clone()
+        assert np.array_equal(feat.float().cpu().numpy(), feats0[3])
+        assert np.array_equal(depth.cpu().numpy(), outs0[1][0])
+        assert np.array_equal(eng.head_output(0, 1).cpu().numpy(), outs0[0][1])
+        assert torch.isfinite(feat.float()).all() and torch.isfinite(depth).all() and depth.min() >= 0
+        assert not torch.equal(feat[0], feat[1])                  # different views give different features
+        assert int(outs0[0][1].max()) < spec.seg_classes
+        # batch independence at full depth: a batch with two views swapped gives the swapped results
+        perm = list(range(spec.batch))
+        perm[0], perm[-1] = perm[-1], perm[0]
+        fh = eng.encode(torch.from_numpy(np.ascontiguousarray(imgs[perm])).cuda())
+        for h in range(3):
+            eng.run_head(h, fh)
+        eng.sync()
+        assert torch.equal(eng.feat_view(fh, 3)[0], feat[-1]) and torch.equal(eng.feat_view(fh, 3)[-1], feat[0])
+        assert torch.equal(eng.head_output(1, 0)[0], depth[-1]) and torch.equal(eng.head_output(1, 0)[-1], depth[0])
+        for b in range(1, spec.batch - 1):
+            assert torch.equal(eng.feat_view(fh, 3)[b], feat[b])
+
+    check_all(spec, wseed, iseed, flags=vpe.VPE_FLAG_GRAPHS, batch_check=(0,), on_device=on_device)

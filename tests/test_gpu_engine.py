@@ -298,3 +298,46 @@ def test_newest_frame_policy_on_the_device_never_queues_behind_a_running_head():
     for a, b in zip(got, outputs(eng)):
         assert torch.equal(a, b)
     eng.close()
+
+
+def test_head_completion_query_and_stage_times():
+    # a consumer takes a head's result without waiting for the rest of the engine (paper, Sec. "Head Module":
+    # results go to the head's output buffer; Sec. "Decentralization": nobody blocks on anybody)
+    eng, _, _ = make_engine(SPEC, 11, flags=vpe.VPE_FLAG_TIMING, ring_slots=2)
+    assert eng.head_done(1) and eng.stage_times() == (-1.0, [-1.0, -1.0, -1.0])
+    fr = frames(2)
+    fh = eng.encode(fr[0])
+    for h in range(3):
+        assert eng.run_head(h, fh) == 0
+    eng.wait_head(0)                                             # seg only; depth may still be running
+    assert eng.head_done(0)
+    seg = eng.head_output(0, 1).clone()
+    eng.sync()
+    assert all(eng.head_done(h) for h in range(3))
+    enc_ms, head_ms = eng.stage_times()
+    assert 0.0 < enc_ms < 50.0 and all(0.0 < t < 50.0 for t in head_ms), (enc_ms, head_ms)
+    # a second frame with only the depth head: the seg head's output buffer keeps its result
+    fh = eng.encode(fr[1])
+    assert eng.run_head(1, fh) == 0
+    eng.sync()
+    assert torch.equal(eng.head_output(0, 1), seg)
+    eng.close()
+
+
+def test_sync_waits_for_work_on_caller_streams_too():
+    eng, _, _ = make_engine(SPEC, 11)
+    st = torch.cuda.Stream()
+    img = frames(1)[0]
+    fh = eng.encode(img, stream=st)
+    for h in range(3):
+        eng.run_head(h, fh, stream=st)
+    eng.sync()                                                   # engine events, not a device-wide wait
+    assert st.query()
+    ref = outputs(eng)
+    fh = eng.encode(img)
+    for h in range(3):
+        eng.run_head(h, fh)
+    eng.sync()
+    for a, b in zip(ref, outputs(eng)):
+        assert torch.equal(a, b)
+    eng.close()
