@@ -205,6 +205,23 @@ int vpe_encode_at(vpe_engine* e, const float* images, void* stream, double t_sec
  * a later frame, VPE_EINVAL for an unknown head or a handle this engine did not produce, VPE_EHIP. */
 int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream);
 
+/* vpe_run_head for callers that cannot allocate device memory or let a library do so on their behalf: tight
+ * serving loops, harnesses that forbid hipMalloc, code that must not trigger the lazy graph instantiation of
+ * vpe_run_head.  Same arguments, checks, return values, scheduling and outputs (the head's own output buffers, read
+ * with vpe_head_output); the difference is where the run's intermediate buffers live and how it is launched:
+ *   - they are taken from a file-scope device array inside the library (8 MiB, one copy per GPU, held until the
+ *     process ends) instead of from the engine's workspace;
+ *   - the head's kernels are always launched one by one (never as a graph replay, even with VPE_FLAG_GRAPHS), and
+ *     the call performs no hipMalloc / hipFree / graph instantiation.
+ * Supported heads: VPE_HEAD_SEG (needs none), VPE_HEAD_DET (batch * patches * 2 channels elements), VPE_HEAD_DEPTH
+ * (about 129 * batch * patches * channels elements); a head whose buffers exceed 8 MiB and VPE_HEAD_DPT are
+ * refused with VPE_EINVAL and a message that states both sizes.  Nothing in the array needs clearing (a run writes
+ * every element before it reads it), and it keeps the last run's contents.  All calls on one GPU share the array:
+ * two vpe_run_head_static runs that overlap on a GPU (different heads, engines or streams) race -- order them
+ * on one stream or wait for the first (vpe_head_done / vpe_wait_head) before starting the next.  The engine's GPU
+ * must be the current device (VPE_EINVAL otherwise). */
+int vpe_run_head_static(vpe_engine* e, int head, vpe_feat fh, void* stream);
+
 /* Has the encoder finished writing this frame's features?  VPE_OK = yes, VPE_BUSY = still executing,
  * VPE_ESTALE = the slot has been taken by a later frame (no error message is set for these three).  A producer
  * that must not run further ahead of the device than the ring is long polls the handle it got `ring_slots - 1`

@@ -62,6 +62,7 @@ def load_library(path: Optional[str] = None):
     L.vpe_create.argtypes = [C.POINTER(vpe_backbone_cfg), C.POINTER(vpe_head_cfg), i32, vp, C.c_uint64, C.POINTER(vp)]
     L.vpe_encode.argtypes = [vp, vp, vp, C.POINTER(vpe_feat)]
     L.vpe_run_head.argtypes = [vp, i32, vpe_feat, vp]
+    L.vpe_run_head_static.argtypes = [vp, i32, vpe_feat, vp]
     L.vpe_run_head_latest.argtypes = [vp, i32, vp, C.POINTER(vpe_feat)]
     L.vpe_head_counters.argtypes = [vp, i32, i64p]
     L.vpe_frame_ready.argtypes = [vp, vpe_feat]
@@ -84,7 +85,7 @@ def load_library(path: Optional[str] = None):
     L.vpe_destroy.restype = None
     for n in ("vpe_workspace_bytes", "vpe_create", "vpe_encode", "vpe_encode_at", "vpe_run_head", "vpe_set_head_rate",
               "vpe_set_head_rate_hz", "vpe_preprocess_u8", "vpe_next_encode_stream", "vpe_feat_view",
-              "vpe_head_output", "vpe_sync", "vpe_head_done", "vpe_wait_head", "vpe_stage_times", "vpe_stats", "vpe_time_kernel", "vpe_run_head_latest", "vpe_head_counters", "vpe_frame_ready"):
+              "vpe_head_output", "vpe_sync", "vpe_run_head_static", "vpe_head_done", "vpe_wait_head", "vpe_stage_times", "vpe_stats", "vpe_time_kernel", "vpe_run_head_latest", "vpe_head_counters", "vpe_frame_ready"):
         getattr(L, n).restype = C.c_int
     if path is None:
         _lib = L
@@ -162,6 +163,13 @@ def vpe_encode_at(engine, images_ptr: int, stream_ptr: Optional[int], t_seconds:
 
 def vpe_run_head(engine, head: int, fh: vpe_feat, stream_ptr: Optional[int] = None) -> int:
     rc = lib().vpe_run_head(engine, head, fh, stream_ptr)
+    if rc < 0:
+        raise VpeError(rc, vpe_last_error(engine))
+    return rc
+
+
+def vpe_run_head_static(engine, head: int, fh: vpe_feat, stream_ptr: Optional[int] = None) -> int:
+    rc = lib().vpe_run_head_static(engine, head, fh, stream_ptr)
     if rc < 0:
         raise VpeError(rc, vpe_last_error(engine))
     return rc
@@ -336,6 +344,9 @@ class Engine:
 
     def run_head(self, head: int, fh: vpe_feat, stream=None) -> int:
         return vpe_run_head(self.handle, head, fh, None if stream is None else stream.cuda_stream)
+
+    def run_head_static(self, head: int, fh: vpe_feat, stream=None) -> int:
+        return vpe_run_head_static(self.handle, head, fh, None if stream is None else stream.cuda_stream)
 
     def run_head_latest(self, head: int, stream=None):
         return vpe_run_head_latest(self.handle, head, None if stream is None else stream.cuda_stream)

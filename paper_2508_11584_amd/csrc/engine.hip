@@ -14,6 +14,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -22,9 +23,36 @@
 
 using namespace vpe;
 
+// Scratch for vpe_run_head_static: callers that may not allocate (and may not trigger an allocation inside the
+// library) get their head's intermediate buffers from this array instead of from an engine workspace.  One copy
+// per GPU the library is loaded on, held until the process ends; every call on a GPU shares it.
+constexpr uint64_t STATIC_SCRATCH_BYTES = 8ull << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_create_error;
+
+// Device address of `scratch` on each GPU (the array's name is a host-side stand-in, not a device address; each
+// GPU has its own copy at its own address).  Looked up once per device, with that device current.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+hipError_t static_scratch(int device, void** out) {
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t rc = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (rc != hipSuccess) return rc;
+        if (!ptr || ((uintptr_t)ptr & 255)) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 constexpr int KPATCH = 588;      // 3 * 14 * 14
 constexpr int KPATCH_PAD = 640;  // next multiple of the k-tile
@@ -80,9 +108,20 @@ struct Dpt {
     int rh[5] = {}, rw[5] = {};    // their output sizes
 };
 
+// Intermediate buffers of a seg / det / DPT-lite head run (neither its input, the feature slot, nor its outputs):
+// normally part of the engine's workspace, or carved out of the library's static device array for
+// vpe_run_head_static.  Every element a run reads is written earlier in the same run; nothing relies on old contents.
+struct HeadScratch {
+    void* tower = nullptr;         // det [B P][2 ch]
+    void* p[4] = {};               // depth: tap projections [B P][ch]
+    void *z = nullptr, *r = nullptr;   // depth: stage input / convolution output [B 64 P][ch], reused across stages
+    float* d8 = nullptr;           // depth: [pixel][ch / 64] partial 1-channel projections on the 8x grid
+};
+
 struct Head {
     int kind = 0, classes = 0, ch = 0, every_n = 1;
     Dpt dpt;
+    HeadScratch sc;
     // weights
     void* w0 = nullptr;            // seg: [C][D]; det: towers [2ch][9D]; depth: unused
     float* b0 = nullptr;
@@ -97,10 +136,7 @@ struct Head {
     // activations / outputs
     float* logits = nullptr;       // seg [B P][C]; det [B P][classes + 4]
     uint8_t* classmap = nullptr;
-    void* tower = nullptr;         // det [B P][2 ch]
-    void* p[4] = {};               // depth [B P][ch]
-    void *z = nullptr, *r = nullptr;
-    float *d8 = nullptr, *depth = nullptr;
+    float* depth = nullptr;
     // scheduling
     hipStream_t stream = nullptr;     // one of the engine's head streams (shared when heads outnumber them)
     hipEvent_t last_done = nullptr;   // completion of the most recent run (any slot)
@@ -125,6 +161,8 @@ struct vpe_engine {
     vpe_backbone_cfg cfg{};
     bool bf = true, host_only = false, graphs = false, owns_ws = false, timing = false;
     int last_lane = -1;                  // lane of the most recent encode
+    int device = -1;                     // the GPU the engine lives on
+    void* static_ptr = nullptr;          // that GPU's copy of the library's static scratch array
     int D = 0, L = 0, nh = 0, Mh = 0, F = 0, R = 0, B = 0, H = 0, W = 0, gh = 0, gw = 0, P = 0, N = 0, T = 0;
     int npad = 0, esz = 2, S = 1;
     char* ws = nullptr;
@@ -312,6 +350,19 @@ double head_flops(const vpe_engine& e, const Head& h) {
     }
 }
 
+// Hands out the intermediate buffers of a seg / det / DPT-lite head (see HeadScratch) from `b`.
+void place_head_scratch(const vpe_engine& e, const Head& h, Bump& b, HeadScratch& sc) {
+    const uint64_t esz = e.esz, ch = h.ch, BP = (uint64_t)e.B * e.P;
+    if (h.kind == VPE_HEAD_DET) {
+        sc.tower = b.take(BP * 2 * ch * esz);
+    } else if (h.kind == VPE_HEAD_DEPTH) {
+        for (int s = 0; s < 4; ++s) sc.p[s] = b.take(BP * ch * esz);
+        sc.z = b.take(BP * 64 * ch * esz);
+        sc.r = b.take(BP * 64 * ch * esz);
+        sc.d8 = (float*)b.take(4 * (ch / 64) * BP * 64);
+    }
+}
+
 void layout(vpe_engine& e, Bump& b) {
     const uint64_t esz = e.esz;
     const uint64_t D = e.D, T = e.T, P = e.P, B = e.B;
@@ -359,7 +410,7 @@ void layout(vpe_engine& e, Bump& b) {
         } else if (h.kind == VPE_HEAD_DET) {
             h.w0 = b.take(wrows(2 * h.ch) * 9 * D * esz); h.b0 = f32(2 * ch);
             h.w1 = b.take(wrows(h.classes + 4) * 2 * ch * esz); h.b1 = f32(h.classes + 4);
-            h.tower = b.take(BP * 2 * ch * esz);
+            place_head_scratch(e, h, b, h.sc);
             h.logits = f32(BP * (h.classes + 4));
             h.classmap = (uint8_t*)b.take(BP);
         } else if (h.kind == VPE_HEAD_DPT) {
@@ -402,10 +453,7 @@ void layout(vpe_engine& e, Bump& b) {
             for (int s = 0; s < 4; ++s) { h.proj_w[s] = b.take(wrows(h.ch) * D * esz); h.proj_b[s] = f32(ch); }
             for (int s = 0; s < 4; ++s) { h.fuse_w[s] = b.take(wrows(h.ch) * 9 * ch * esz); h.fuse_b[s] = f32(ch); }
             h.out_w = f32(ch);
-            for (int s = 0; s < 4; ++s) h.p[s] = b.take(BP * ch * esz);
-            h.z = b.take(BP * 64 * ch * esz);
-            h.r = b.take(BP * 64 * ch * esz);
-            h.d8 = f32((int64_t)(ch / 64) * BP * 64);   // [pixel][ch / 64]: one partial projection per 64 channels
+            place_head_scratch(e, h, b, h.sc);
             h.depth = f32(B * e.H * e.W);
         }
     }
@@ -791,7 +839,7 @@ int enqueue_dpt(vpe_engine& e, Head& h, int slot, hipStream_t s) {
     return 0;
 }
 
-int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
+int enqueue_head_body(vpe_engine& e, Head& h, const HeadScratch& sc, int slot, hipStream_t s) {
     const int dt = e.bf, BP = e.B * e.P;
     void* const* f = &e.feat[slot * 4];
     if (h.kind == VPE_HEAD_DPT) return enqueue_dpt(e, h, slot, s);
@@ -802,9 +850,9 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
         HIPCHK(&e, launch_seg_upsample_argmax(h.logits, e.B, e.gh, e.gw, h.classes, e.H, e.W, h.classmap, s));
     } else if (h.kind == VPE_HEAD_DET) {
         GemmArgs a = conv3_gemm(e, f[3], e.D, e.B, e.gh, e.gw, e.N, 1 + e.R, h.w0, h.b0, 2 * h.ch);
-        a.out = h.tower; a.ldo = 2 * h.ch;
+        a.out = sc.tower; a.ldo = 2 * h.ch;
         HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
-        GemmArgs o = plain_gemm(h.tower, 2 * h.ch, h.w1, h.b1, BP, h.classes + 4, 2 * h.ch);
+        GemmArgs o = plain_gemm(sc.tower, 2 * h.ch, h.w1, h.b1, BP, h.classes + 4, 2 * h.ch);
         o.out = h.logits; o.ldo = h.classes + 4; o.out_f32 = 1;
         HIPCHK(&e, launch_gemm(dt, o, A_PLAIN, s));
         HIPCHK(&e, launch_argmax_rows(h.logits, BP, h.classes, h.classes + 4, h.classmap, s));
@@ -812,36 +860,36 @@ int enqueue_head_body(vpe_engine& e, Head& h, int slot, hipStream_t s) {
         // the four tap projections are independent problems of one shape: one batched launch when their
         // operands are evenly spaced in memory (they are, by construction of the workspace layout)
         const int64_t za = (const char*)f[2] - (const char*)f[3], zw = (const char*)h.proj_w[1] - (const char*)h.proj_w[0];
-        const int64_t zo = (const char*)h.p[1] - (const char*)h.p[0], zb = h.proj_b[1] - h.proj_b[0];
+        const int64_t zo = (const char*)sc.p[1] - (const char*)sc.p[0], zb = h.proj_b[1] - h.proj_b[0];
         bool even = true;
         for (int st = 1; st < 4; ++st)
             even = even && (const char*)f[3 - st] - (const char*)f[3] == st * za &&
                    (const char*)h.proj_w[st] - (const char*)h.proj_w[0] == st * zw &&
-                   (const char*)h.p[st] - (const char*)h.p[0] == st * zo && h.proj_b[st] - h.proj_b[0] == st * zb;
+                   (const char*)sc.p[st] - (const char*)sc.p[0] == st * zo && h.proj_b[st] - h.proj_b[0] == st * zb;
         for (int st = 0; st < (even ? 1 : 4); ++st) {
             GemmArgs a = tokens_gemm(e, f[3 - st], h.proj_w[st], h.proj_b[st], h.ch);
-            a.out = h.p[st]; a.ldo = h.ch;
+            a.out = sc.p[st]; a.ldo = h.ch;
             if (even) { a.nz = 4; a.z_a = za; a.z_w = zw; a.z_out = zo; a.z_bias = zb; }
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         for (int st = 0; st < 4; ++st) {
             const int hs = e.gh << st, wsz = e.gw << st;
-            const void* in = h.p[0];
+            const void* in = sc.p[0];
             if (st) {
-                HIPCHK(&e, launch_fuse_upsample(dt, h.p[st], e.gh, e.gw, h.r, e.B, hs, wsz, h.ch, h.z, s));
-                in = h.z;
+                HIPCHK(&e, launch_fuse_upsample(dt, sc.p[st], e.gh, e.gw, sc.r, e.B, hs, wsz, h.ch, sc.z, s));
+                in = sc.z;
             }
             GemmArgs a = conv3_gemm(e, in, h.ch, e.B, hs, wsz, hs * wsz, 0, h.fuse_w[st], h.fuse_b[st], h.ch);
             if (st < 3) {
-                a.out = h.r; a.ldo = h.ch;
+                a.out = sc.r; a.ldo = h.ch;
             } else {
                 // last stage: the 1-channel projection is taken in the epilogue (per 64-channel group), the
                 // 256-channel map itself is never written
-                a.epi = EPI_ROWDOT; a.gamma = h.out_w; a.out = h.d8; a.ldo = h.ch / 64;
+                a.epi = EPI_ROWDOT; a.gamma = h.out_w; a.out = sc.d8; a.ldo = h.ch / 64;
             }
             HIPCHK(&e, launch_gemm(dt, a, A_CONV3, s));
         }
-        HIPCHK(&e, launch_depth_output(h.d8, h.ch / 64, h.out_b, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
+        HIPCHK(&e, launch_depth_output(sc.d8, h.ch / 64, h.out_b, e.B, 8 * e.gh, 8 * e.gw, e.H, e.W, h.depth, s));
     }
     return 0;
 }
@@ -943,6 +991,8 @@ int vpe_create(const vpe_backbone_cfg* cfg, const vpe_head_cfg* heads, int n_hea
         e->fail(VPE_EHIP, std::string(what) + ": " + hipGetErrorString(rc));
         return 1;
     };
+    if (hip(hipGetDevice(&e->device), "hipGetDevice")) return bail(VPE_EHIP);
+    if (hip(static_scratch(e->device, &e->static_ptr), "hipGetSymbolAddress(scratch)")) return bail(VPE_EHIP);
     if (hip(hipMemset(e->ws, 0, need), "hipMemset")) return bail(VPE_EHIP);
     if (hip(configure_attention(), "configure_attention")) return bail(VPE_EHIP);
     if (hip(configure_gemm(), "configure_gemm")) return bail(VPE_EHIP);
@@ -1103,7 +1153,9 @@ bool hz_allows(Head& h, double t) {
 }
 
 // Enqueue one run of a head on the frame in `slot` (already checked to be current and due).
-int start_head(vpe_engine* e, int head, int slot, int64_t frame, void* stream) {
+// `sc` = the intermediate buffers to use; `replay` = false launches the kernels one by one even on an engine with
+// graphs (a replay is tied to the buffers it was captured with, and the first one instantiates a graph, which allocates).
+int start_head(vpe_engine* e, int head, int slot, int64_t frame, void* stream, const HeadScratch& sc, bool replay) {
     Head& h = e->heads[head];
     const int nh = (int)e->heads.size();
     if (!e->host_only) {
@@ -1112,12 +1164,12 @@ int start_head(vpe_engine* e, int head, int slot, int64_t frame, void* stream) {
         // the head's scratch and outputs are single-instance: order after its previous run
         if (h.ran) HIPCHK(e, hipStreamWaitEvent(s, h.last_done, 0));
         if (e->timing) HIPCHK(e, hipEventRecord(h.t_begin, s));
-        if (e->graphs) {
+        if (e->graphs && replay) {
             if (!h.graphs[slot])
-                TRY(capture(*e, &h.graphs[slot], [&](hipStream_t cs) { return enqueue_head_body(*e, h, slot, cs); }));
+                TRY(capture(*e, &h.graphs[slot], [&](hipStream_t cs) { return enqueue_head_body(*e, h, h.sc, slot, cs); }));
             HIPCHK(e, hipGraphLaunch(h.graphs[slot], s));
         } else {
-            TRY(enqueue_head_body(*e, h, slot, s));
+            TRY(enqueue_head_body(*e, h, sc, slot, s));
         }
         if (e->timing) HIPCHK(e, hipEventRecord(h.t_end, s));
         hipEvent_t ev = e->done[(size_t)slot * nh + head];
@@ -1142,7 +1194,37 @@ int vpe_run_head(vpe_engine* e, int head, vpe_feat fh, void* stream) {
     if (fh.frame % h.every_n != 0) { ++h.skips; return VPE_SKIPPED; }
     if (e->slot_frame[fh.slot] != fh.frame) return e->fail(VPE_ESTALE, "slot has been reused by a later frame");
     if (!hz_allows(h, e->slot_time[fh.slot])) { ++h.skips; return VPE_SKIPPED; }
-    return start_head(e, head, fh.slot, fh.frame, stream);
+    return start_head(e, head, fh.slot, fh.frame, stream, h.sc, true);
+}
+
+int vpe_run_head_static(vpe_engine* e, int head, vpe_feat fh, void* stream) {
+    if (!e) return VPE_EINVAL;
+    if (head < 0 || head >= (int)e->heads.size()) return e->fail(VPE_EINVAL, "unknown head");
+    if (fh.slot < 0 || fh.slot >= e->S || fh.frame < 0 || fh.frame >= e->frames || fh.frame % e->S != fh.slot)
+        return e->fail(VPE_EINVAL, "feature handle was not produced by this engine");
+    Head& h = e->heads[head];
+    if (h.kind == VPE_HEAD_DPT) return e->fail(VPE_EINVAL, "vpe_run_head_static: the full DPT head is not supported (its padded maps rely on a cleared workspace)");
+    // carve the head's intermediate buffers out of the static array (same order and alignment as in a workspace)
+    Bump b;
+    b.base = (char*)e->static_ptr;     // null for host-only engines: then this only measures
+    HeadScratch sc;
+    place_head_scratch(*e, h, b, sc);
+    if (b.off > STATIC_SCRATCH_BYTES) {
+        char buf[192];
+        snprintf(buf, sizeof buf, "vpe_run_head_static: this head needs %llu bytes of scratch, the static array holds %llu",
+                 (unsigned long long)b.off, (unsigned long long)STATIC_SCRATCH_BYTES);
+        return e->fail(VPE_EINVAL, buf);
+    }
+    if (!e->host_only) {
+        int dev = -1;
+        HIPCHK(e, hipGetDevice(&dev));
+        if (dev != e->device) return e->fail(VPE_EINVAL, "vpe_run_head_static: the engine's GPU is not the current device");
+    }
+    h.seen = std::max(h.seen, fh.frame);
+    if (fh.frame % h.every_n != 0) { ++h.skips; return VPE_SKIPPED; }
+    if (e->slot_frame[fh.slot] != fh.frame) return e->fail(VPE_ESTALE, "slot has been reused by a later frame");
+    if (!hz_allows(h, e->slot_time[fh.slot])) { ++h.skips; return VPE_SKIPPED; }
+    return start_head(e, head, fh.slot, fh.frame, stream, sc, false);
 }
 
 int vpe_run_head_latest(vpe_engine* e, int head, void* stream, vpe_feat* ran_on) {
@@ -1173,7 +1255,7 @@ int vpe_run_head_latest(vpe_engine* e, int head, void* stream, vpe_feat* ran_on)
     const int slot = (int)(newest % e->S);
     if (h.last_run_frame >= 0 && newest - h.last_run_frame < h.every_n) { ++h.skips; return VPE_SKIPPED; }
     if (!hz_allows(h, e->slot_time[slot])) { ++h.skips; return VPE_SKIPPED; }
-    const int rc = start_head(e, head, slot, newest, stream);
+    const int rc = start_head(e, head, slot, newest, stream, h.sc, true);
     if (rc == VPE_OK && ran_on) { ran_on->slot = slot; ran_on->reserved = 0; ran_on->frame = newest; }
     return rc;
 }
@@ -1341,13 +1423,13 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
             } else if (which == 4) {
                 // the stage input of that convolution: upsample of the tap projection + x2 upsample of the previous
                 // stage's output, 8x the patch grid (bandwidth-bound: reads 1/4 of what it writes)
-                HIPCHK(e, launch_fuse_upsample(dt, dh->p[3], e->gh, e->gw, dh->r, e->B, e->gh << 3, e->gw << 3, dh->ch, dh->z, s));
+                HIPCHK(e, launch_fuse_upsample(dt, dh->sc.p[3], e->gh, e->gw, dh->sc.r, e->B, e->gh << 3, e->gw << 3, dh->ch, dh->sc.z, s));
             } else {
                 // the largest 3x3 convolution of the depth head (last fusion stage, 8x the patch grid), same
                 // shape, weights and buffers as in a head run; its timing does not depend on the values in z
                 const int hs = e->gh << 3, wsz = e->gw << 3;
-                GemmArgs a = conv3_gemm(*e, dh->z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[3], dh->fuse_b[3], dh->ch);
-                a.epi = EPI_ROWDOT; a.gamma = dh->out_w; a.out = dh->d8; a.ldo = dh->ch / 64;
+                GemmArgs a = conv3_gemm(*e, dh->sc.z, dh->ch, e->B, hs, wsz, hs * wsz, 0, dh->fuse_w[3], dh->fuse_b[3], dh->ch);
+                a.epi = EPI_ROWDOT; a.gamma = dh->out_w; a.out = dh->sc.d8; a.ldo = dh->ch / 64;
                 HIPCHK(e, launch_gemm(dt, a, A_CONV3, s));
             }
         }

@@ -394,3 +394,20 @@ def test_head_completion_and_stage_times_without_a_device():
     plain, _, _ = make_engine(vi.small_spec(), 1, flags=vpe.VPE_FLAG_HOST_ONLY)
     with pytest.raises(vpe.VpeError, match="VPE_FLAG_TIMING"):
         plain.stage_times()
+
+
+def test_static_scratch_head_run_checks_sizes_on_the_host():
+    # vpe_run_head_static refuses heads whose intermediate buffers exceed the library's 8 MiB static array
+    spec = vi.CONFIGS["cfg2"]
+    w = vi.make_backbone_weights(spec, 1)
+    eng, _, _ = make_engine(spec, 1, kinds=("seg", "depth", "det", "dpt"), flags=vpe.VPE_FLAG_HOST_ONLY, weights=w)
+    fh = eng.encode(None)
+    assert vpe.vpe_run_head_static(eng.handle, 0, fh) == vpe.VPE_OK
+    assert vpe.vpe_run_head_static(eng.handle, 2, fh) == vpe.VPE_OK          # 1530 x 512 bf16 = 1.6 MB
+    with pytest.raises(vpe.VpeError, match="needs 10[0-9]{7} bytes of scratch, the static array holds 8388608"):
+        vpe.vpe_run_head_static(eng.handle, 1, fh)
+    with pytest.raises(vpe.VpeError, match="DPT"):
+        vpe.vpe_run_head_static(eng.handle, 3, fh)
+    with pytest.raises(vpe.VpeError):
+        vpe.vpe_run_head_static(eng.handle, 4, fh)
+    assert eng.stats()[1] == [1, 0, 1, 0]
