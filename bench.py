@@ -272,6 +272,9 @@ def main() -> None:
     ap.add_argument("--roofline-only", action="store_true",
                     help="one frame, a 1 GiB device copy (counter calibration) and the dominant-kernel timing leg only; "
                          "the mode the rocprofv3 --pmc passes are taken in")
+    ap.add_argument("--kernel-pass", action="store_true",
+                    help="one frame, then every kernel family of the timing aid alone (1 + --kernel-reps launches each): "
+                         "the mode the per-kernel rocprofv3 --pmc passes are taken in")
     ap.add_argument("--experiment", choices=["multihead", "freshness"], default=None,
                     help="multihead: frame latency against the number of identical heads (1, 2, 4, 8), for depth heads "
                          "(the paper's single-backbone-vs-independent-models experiment) and detection heads (its "
@@ -367,6 +370,29 @@ def main() -> None:
         long_ = bracketed(fn, prime + steps)
         return (long_ - short) / steps, bracketed(fn, steps) / steps
 
+    if args.kernel_pass:
+        # every kernel family the timing aid knows, alone, back to back: the shape the rocprofv3 --pmc passes
+        # of profiles/ are taken in (per family: 1 warm-up + --kernel-reps launches, in this order)
+        shared_step(0)
+        eng.sync()
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")     # counter calibration: 1 GiB read + 1 GiB written
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+        fams = ["qkv_gemm", "attention", "layernorm", "depth_conv3x3", "depth_fuse_upsample", "proj_gemm", "fc1_gemm", "fc2_gemm"]
+        rows = {}
+        for which, name in enumerate(fams):
+            if which in (3, 4) and "depth" not in kinds:
+                continue
+            ms, fl, by = eng.time_kernel(which, args.kernel_reps)
+            rows[name] = {"us": round(ms * 1e3, 2), "tflops": round(fl / ms / 1e9, 2), "gbps": round(by / ms / 1e6, 1),
+                          "algorithmic_flops": fl, "algorithmic_bytes": by}
+        print(json.dumps({"mode": "kernel-pass", "workload": spec.name, "reps": args.kernel_reps, "kernels": rows}))
+        eng.close()
+        return
+
     if args.roofline_only:
         shared_step(0)
         eng.sync()
@@ -421,7 +447,7 @@ def main() -> None:
     kern = {}
     shared_step(0)
     eng.sync()
-    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm")) + (((3, "depth_conv3x3"), (4, "depth_fuse_upsample")) if "depth" in kinds else ()):
+    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm"), (5, "proj_gemm"), (6, "fc1_gemm"), (7, "fc2_gemm")) + (((3, "depth_conv3x3"), (4, "depth_fuse_upsample")) if "depth" in kinds else ()):
         ms, fl, by = eng.time_kernel(which, args.kernel_reps)
         kern[name] = {"us": round(ms * 1e3, 2), "tflops": round(fl / ms / 1e9, 2), "gbps": round(by / ms / 1e6, 1)}
         if name in ("layernorm", "depth_fuse_upsample"):            # bandwidth-bound kernels: fraction of the 8 TB/s HBM peak

@@ -309,7 +309,9 @@ int vpe_stage_times(vpe_engine* e, float* encode_ms, float* head_ms, int n);
  * (buffers that the next encode / head run rewrites before reading); feature slots and head outputs are untouched.
  * which: 0 = the fused-QKV GEMM of block 0 on the current activations, 1 = the attention
  * kernel of block 0, 2 = LayerNorm, 3 = the depth head's largest 3x3 convolution (last fusion stage; needs a
- * depth head), 4 = the resample-and-add kernel that writes that convolution's input (needs a depth head).
+ * depth head), 4 = the resample-and-add kernel that writes that convolution's input (needs a depth head),
+ * 5 = the out-projection GEMM of block 0 (LayerScale + residual epilogue), 6 = its fc1 GEMM (LayerNorm folded in,
+ * GELU or SwiGLU epilogue), 7 = its fc2 GEMM (LayerScale + residual epilogue).
  * Also reports the algorithmic flops and bytes of one launch. */
 int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes);
 

@@ -31,6 +31,17 @@ struct AttnArgs {
     int pad;             // readable rows of qk / elements of vt past their ends
 };
 
+// Exchange between the two halves of a wave without going through LDS (v_permlane32_swap): both operands are the
+// lane's own value, after the swap one holds the lower half's values in all 64 lanes and the other the upper half's.
+__device__ __forceinline__ float halves_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // --- per-type pieces: fragments for S^T = K Q^T and O^T = V^T P^T over a block of 32 keys
 template <typename T> struct AttnMma;
 
@@ -125,8 +136,20 @@ template <> struct AttnMma<float> {
 // the KW partial results of a query group are merged in LDS by its kw = 0 wave (fixed order, so
 // results are deterministic).  KW > 1 gives small problems enough waves to fill 1024 SIMDs;
 // QW > 1 and QB = 2 cut the L2 -> LDS traffic per query on large ones.
+// Launch bound: at least two waves per SIMD wherever the kernel fits 256 registers.  Besides the occupancy, this
+// is what makes the compiler keep the MFMA accumulators in ordinary vector registers: with up to 512 registers
+// allowed it places them in the accumulation-register file, and since the softmax works on the scores with
+// vector instructions every tile then pays ~190 register-file moves per lane (measured on the four-wave shapes:
+// 158 + 48 registers and 300 vector instructions per tile without the bound, 164 + 0 and 105 with it).  Two
+// shapes would spill under the bound and keep the old one.
+template <typename T, int KW>
+constexpr bool attn_double_buffered() { return 2 * KW * 2 * 64 * AttnMma<T>::ROWB <= 128 * 1024; }
+
 template <typename T, int QB, int QW, int KW>
-__global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs p) {
+constexpr int attn_min_waves() { return (QW * KW == 4 && (QB == 2 || (sizeof(T) == 4 && KW == 4))) ? 1 : 2; }
+
+template <typename T, int QB, int QW, int KW>
+__global__ __launch_bounds__(64 * QW * KW, (attn_min_waves<T, QB, QW, KW>())) void attention_kernel(const AttnArgs p) {
     constexpr int NW = QW * KW, NT = 64 * NW;
     static_assert(KW <= ATTN_MAX_KW, "the loader's overshoot is budgeted for at most ATTN_MAX_KW key waves");
     constexpr int CE = Elem<T>::CE;
@@ -134,6 +157,8 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
     constexpr int ROWB = AttnMma<T>::ROWB;
     constexpr int TILE = 64 * ROWB;
     constexpr int CH = KW * 2 * 64 * CPR / NT;   // chunks per thread per iteration
+    constexpr int STAGE = KW * 2 * TILE;         // K and V tiles of one iteration
+    constexpr bool DB = attn_double_buffered<T, KW>();
     static_assert((KW * 2 * 64 * CPR) % NT == 0 && NT % CPR == 0, "loader mapping");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -180,7 +205,7 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
     const int KT = p.npad / 64;
     const int NIT = (KT + KW - 1) / KW;
     const int lchunk = tid % CPR;
-    u32x4 rg[CH];
+    u32x4 rg[DB ? 1 : CH];                             // register staging: single-buffer shapes only
     // chunk i of this thread: linear index tid + i NT over (tile j, K|V, row, chunk).  Its address advances by a
     // fixed step per iteration (KW tiles), so the loader keeps one running pointer per chunk instead of
     // recomputing tile, row and clamps each time.  Nothing is clamped: tiles past the last one and key rows past
@@ -195,7 +220,7 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
     int64_t kadv = 0, vadv = 0;
     auto gload = [&]() {                               // loads the next iteration's tiles
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
+        for (int i = 0; i < (DB ? 0 : CH); ++i) {
             const int r0 = (i * RPP) & 63, which = ((i * RPP) >> 6) & 1, j = (i * RPP) >> 7;
             const T* src = which ? vthr + (int64_t)r0 * p.npad + j * 64 + vadv
                                  : kthr + (int64_t)(j * 64 + r0) * ld + kadv;
@@ -204,92 +229,138 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
         kadv += (int64_t)KW * 64 * ld;
         vadv += KW * 64;
     };
-    auto sstore = [&]() {
+    auto sstore = [&](char* base) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
+        for (int i = 0; i < (DB ? 0 : CH); ++i) {
             const int idx = (tid + i * NT) / CPR;
             const int row = idx & 63;
             const int phys = (lchunk & ~7) | swz(row, lchunk & 7);
-            *reinterpret_cast<u32x4*>(smem + (idx >> 6) * TILE + (row * CPR + phys) * 16) = rg[i];
+            *reinterpret_cast<u32x4*>(base + (idx >> 6) * TILE + (row * CPR + phys) * 16) = rg[i];
         }
     };
 
-    gload();
-    for (int it = 0; it < NIT; ++it) {
-        __syncthreads();           // everyone is done reading the previous tiles
-        sstore();
+    // Double-buffered shapes load straight into LDS (global_load_lds_dwordx4: no staging registers, no ds_write).
+    // One instruction of a wave fills 1 KB = RPI consecutive rows of a tile; lane l lands on row l / CPR, physical
+    // chunk l % CPR of that row group, so it fetches the logical chunk that belongs there under the swizzle.
+    // Instruction i of wave w fills slot w + NW i of the stage (tile i / PPT, pass i % PPT over its row groups):
+    // a lane's row within the tile is (w + NW pass) RPI + l / CPR -- the passes differ by multiples of 16 rows, which
+    // leave the swizzle term unchanged, so one logical chunk and two thread pointers serve every instruction.
+    constexpr int RPI = 1024 / ROWB, G = TILE / 1024;  // rows per instruction, instructions per tile
+    constexpr int PPT = G / NW > 0 ? G / NW : 1;       // passes of the workgroup over one tile
+    constexpr int NDMA = KW * 2 * G / NW;              // instructions per wave per iteration
+    static_assert(!DB || (G % NW == 0 && (NW * RPI) % 16 == 0) || NW == G, "loader mapping of the direct-to-LDS path");
+    const int drow = wave * RPI + lane / CPR;
+    const int dlc = ((lane % CPR) & ~7) | (((lane % CPR) & 7) ^ ((drow >> 1) & 7));
+    const T* kdma = kbase + (int64_t)drow * ld + dlc * CE;
+    const T* vdma = vt + (int64_t)drow * p.npad + dlc * CE;
+    auto dma = [&](char* base, int it) {               // tiles of iteration `it` into the stage at `base`
+        const int64_t ka = (int64_t)it * KW * 64 * ld;
+        const int va = it * KW * 64;
+#pragma unroll
+        for (int i = 0; i < (DB ? NDMA : 0); ++i) {
+            const int ti = i / PPT, pass = i % PPT, j = ti >> 1, which = ti & 1, r0 = pass * NW * RPI;
+            const T* src = which ? vdma + (int64_t)r0 * p.npad + j * 64 + va : kdma + (int64_t)(j * 64 + r0) * ld + ka;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(base + (wave + NW * i) * 1024), 16, 0, 0);
+        }
+    };
+    // Two buffers: the loads of iteration it + 1 are issued at the top of iteration it into the buffer that was read
+    // in iteration it - 1, and one barrier per iteration is enough (everyone has finished reading buffer b, and the
+    // loads into buffer b ^ 1 have landed).  Shapes whose two buffers would not fit the CU's LDS keep one buffer,
+    // register staging and two barriers.
+    if constexpr (DB) {
+        dma(smem, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the loads into LDS have landed
         __syncthreads();
-        gload();               // unconditional (reads past the end land in padding): keeps the in-flight load count static
+    } else {
+        gload();
+    }
+    for (int it = 0; it < NIT; ++it) {
+        const char* stage = smem;
+        if constexpr (DB) {
+            if (it + 1 < NIT) dma(smem + ((it + 1) & 1) * STAGE, it + 1);
+            stage = smem + (it & 1) * STAGE;
+        } else {
+            __syncthreads();           // everyone is done reading the previous tiles
+            sstore(smem);
+            __syncthreads();
+            if (it + 1 < NIT) gload();
+        }
         const int t = it * KW + kw;
-        if (t >= KT) continue;     // (barriers above are reached by every wave in every iteration)
-        const char* sK = smem + (kw * 2) * TILE;
-        const char* sV = sK + TILE;
-        const bool last = t == KT - 1;     // keys past N only exist in the last tile
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            f32x16 s[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[kb][v] = 0.0f;
-                AttnMma<T>::qk(s[kb], sK, kb * 32 + li, q[qb], g);
-            }
-            if (last) {
-#pragma unroll
+        if (t < KT) {                  // (a wave without a tile in the last iteration still takes part in the barriers)
+            const char* sK = stage + (kw * 2) * TILE;
+            const char* sV = sK + TILE;
+            const bool last = t == KT - 1;     // keys past N only exist in the last tile
+    #pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                f32x16 s[2];
+    #pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+    #pragma unroll
+                    for (int v = 0; v < 16; ++v) s[kb][v] = 0.0f;
+                    AttnMma<T>::qk(s[kb], sK, kb * 32 + li, q[qb], g);
+                }
+                if (last) {
+    #pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+    #pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                            if (key >= p.N) s[kb][v] = -INFINITY;
+                        }
+                }
+                float mx = s[0][0];
+    #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                        if (key >= p.N) s[kb][v] = -INFINITY;
+    #pragma unroll
+                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
+                mx = halves_max(mx);
+                // Lazy rescaling: m_run is the reference the exponentials are taken against (in log2 units), not
+                // necessarily the running maximum.  It only moves when a query's maximum has grown by more than 8
+                // (probabilities stay <= 2^8, exact in fp32 and harmless in bf16), which after the first tile is
+                // rare -- and then the whole wave skips the 32 multiplications of the accumulator.  On the first
+                // tile the reference is -inf, alpha = 0 and the (zero) accumulators are overwritten.
+                const float mxs = mx * p.scale_log2e;
+                const bool grow = mxs > m_run[qb] + 8.0f;
+                if (__any(grow)) {
+                    const float m_new = grow ? mxs : m_run[qb];
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+                    l_run[qb] *= alpha;
+                    m_run[qb] = m_new;
+                    if (LMFMA) {
+    #pragma unroll
+                        for (int v = 0; v < 16; ++v) lacc[qb][v] *= alpha;
                     }
-            }
-            float mx = s[0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            // Lazy rescaling: m_run is the reference the exponentials are taken against (in log2 units), not
-            // necessarily the running maximum.  It only moves when a query's maximum has grown by more than 8
-            // (probabilities stay <= 2^8, exact in fp32 and harmless in bf16), which after the first tile is
-            // rare -- and then the whole wave skips the 32 multiplications of the accumulator.  On the first
-            // tile the reference is -inf, alpha = 0 and the (zero) accumulators are overwritten.
-            const float mxs = mx * p.scale_log2e;
-            const bool grow = mxs > m_run[qb] + 8.0f;
-            if (__any(grow)) {
-                const float m_new = grow ? mxs : m_run[qb];
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-                l_run[qb] *= alpha;
-                m_run[qb] = m_new;
+    #pragma unroll
+                    for (int d = 0; d < 2; ++d)
+    #pragma unroll
+                        for (int v = 0; v < 16; ++v) o[qb][d][v] *= alpha;
+                }
+                const float mc = m_run[qb];
+                float psum = 0.0f;
+    #pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+    #pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][v], p.scale_log2e, -mc));
+                        s[kb][v] = e;
+                        if (!LMFMA) psum += e;
+                    }
                 if (LMFMA) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) lacc[qb][v] *= alpha;
+                    AttnMma<T>::rowsum(lacc[qb], s[0]);
+                    AttnMma<T>::rowsum(lacc[qb], s[1]);
+                } else {
+                    l_run[qb] += psum;
                 }
-#pragma unroll
-                for (int d = 0; d < 2; ++d)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) o[qb][d][v] *= alpha;
+    #pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+    #pragma unroll
+                    for (int d = 0; d < 2; ++d) AttnMma<T>::pv(o[qb][d], sV, d * 32 + li, kb, s[kb], g);
             }
-            const float mc = m_run[qb];
-            float psum = 0.0f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][v], p.scale_log2e, -mc));
-                    s[kb][v] = e;
-                    if (!LMFMA) psum += e;
-                }
-            if (LMFMA) {
-                AttnMma<T>::rowsum(lacc[qb], s[0]);
-                AttnMma<T>::rowsum(lacc[qb], s[1]);
-            } else {
-                l_run[qb] += psum;
-            }
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int d = 0; d < 2; ++d) AttnMma<T>::pv(o[qb][d], sV, d * 32 + li, kb, s[kb], g);
+        }
+        if constexpr (DB) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
         }
     }
 
@@ -340,7 +411,7 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
     // each lane half summed its own keys; the query's denominator is the sum of both halves
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+        const float l_tot = halves_sum(l_run[qb]);
         const float inv = 1.0f / l_tot;
         const int qi = q0 + qb * 32 + li;
         if (qi < p.N) {
@@ -361,7 +432,7 @@ __global__ __launch_bounds__(64 * QW * KW) void attention_kernel(const AttnArgs 
 template <typename T, int QB, int QW, int KW>
 static inline hipError_t launch_attention_variant(const AttnArgs& a, hipStream_t s, bool configure_only) {
     constexpr int TILE = 64 * AttnMma<T>::ROWB;
-    constexpr int kv = KW * 2 * TILE, red = (KW - 1) * QW * QB * 34 * 64 * 4;
+    constexpr int kv = (attn_double_buffered<T, KW>() ? 2 : 1) * KW * 2 * TILE, red = (KW - 1) * QW * QB * 34 * 64 * 4;
     constexpr int lds = kv > red ? kv : red;
     static bool configured = false;       // opt in to more than 64 KB of LDS once per instantiation
     if (!configured) {

@@ -1417,6 +1417,21 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
             } else if (which == 1) {
                 AttnArgs a{L0.qk, L0.vt, L0.att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f, ATTN_PAD};
                 HIPCHK(e, launch_attention(dt, a, s));
+            } else if (which == 5 || which == 7) {
+                // out-projection / fc2 of block 0 with the LayerScale residual epilogue (the residual stream of lane 0
+                // accumulates over the repetitions; the next encode rewrites it)
+                const BlockW& w = e->blk[0];
+                GemmArgs a = which == 5 ? plain_gemm(L0.att, D, w.proj_w, w.proj_b, T, D, D)
+                                        : plain_gemm(L0.hid, e->Mh, w.fc2_w, w.fc2_b, T, D, e->Mh);
+                a.epi = EPI_RESID; a.gamma = which == 5 ? w.ls1 : w.ls2;
+                produce_stats(*e, L0, a, L0.lev[1]);
+                HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
+            } else if (which == 6) {
+                GemmArgs a = ln_gemm(*e, L0, e->blk[0].fc1_w, e->blk[0].fc1_b, e->blk[0].fc1_s, e->F, L0.lev[1], nullptr);
+                a.out = L0.hid; a.ldo = e->Mh;
+                if (e->cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
+                else a.act = ACT_GELU;
+                HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
             } else if (which == 2) {
                 // into the attention-output scratch: same size as a feature map, rewritten by the next encode before it is read
                 HIPCHK(e, launch_layernorm(dt, L0.x, T, D, e->norm_g, e->norm_b, e->cfg.ln_eps, L0.att, s));
@@ -1436,7 +1451,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
         if (timed) HIPCHK(e, hipEventRecord(t1, s));
         return 0;
     };
-    if (which < 0 || which > 4 || (which >= 3 && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
+    if (which < 0 || which > 7 || ((which == 3 || which == 4) && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
     if (!rc) rc = body(false);   // warm-up launch
     if (!rc) rc = body(true);
     if (!rc && hipEventSynchronize(t1) != hipSuccess) rc = e->fail(VPE_EHIP, "hipEventSynchronize failed");
@@ -1449,6 +1464,9 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
     if (which == 0) { fl = 2.0 * T * D * 3.0 * D; by = esz * ((double)T * D + 3.0 * D * D + 3.0 * T * D); }
     else if (which == 1) { fl = 4.0 * e->B * (double)e->N * e->N * D; by = esz * 4.0 * T * D; }
     else if (which == 2) { fl = 8.0 * T * D; by = (4.0 + esz) * T * D; }
+    else if (which == 5) { fl = 2.0 * T * D * D; by = esz * ((double)T * D + (double)D * D) + (8.0 + esz) * T * D; }
+    else if (which == 6) { fl = 2.0 * T * D * (double)e->F; by = esz * ((double)T * D + (double)D * e->F + (double)T * e->Mh); }
+    else if (which == 7) { fl = 2.0 * T * D * (double)e->Mh; by = esz * ((double)T * e->Mh + (double)D * e->Mh) + (8.0 + esz) * T * D; }
     else if (which == 4) {
         const double ch = dh->ch, pix = (double)e->B * e->P;
         fl = 14.0 * 64.0 * pix * ch;                                   // two bilinear blends and an add per output value
