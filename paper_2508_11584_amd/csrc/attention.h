@@ -61,34 +61,79 @@ template <> struct AttnMma<bf16> {
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[ks], s, 0, 0, 0);
         }
     }
-    // O^T block (32 dh x 32 queries) += V^T[dh][32 keys of block kb] P^T.  The k slot (g, kk) of
-    // step s is key 16 s + 8 (kk / 4) + 4 g + kk % 4 -- exactly where accumulator element
-    // v = 8 s + kk of the score block sits, so P needs no shuffle.
-    static __device__ __forceinline__ void pv(f32x16& o, const char* sV, int drow, int kb, const f32x16& p, int g) {
+    // Both 32-key blocks of a tile at once: S0^T, S1^T = K[0..31], K[32..63] times Q^T.  The two accumulation chains
+    // alternate (consecutive MFMAs are independent) and the K fragments of k-step ks + 1 are read while the MFMAs of
+    // step ks run, instead of read - wait - multiply eight times in a row.
+    static __device__ __forceinline__ void qk2(f32x16& s0, f32x16& s1, const char* sK, int li, const QFrag* q, int g) {
+        // Accumulator row r of the score block is fed from key row pi(r) = r with bits 2 and 3 exchanged: lane half g
+        // then holds, for k-step s of the second product, the eight CONSECUTIVE keys 16 s + 8 g .. + 7 (see pv_tile)
+        const int kr = (li & 0x13) | ((li & 8) >> 1) | ((li & 4) << 1);
+        const int sw = (kr >> 1) & 7;                      // rows kr and kr + 32 share the swizzle term
+        const char* r0 = sK + kr * 128;
+        const char* r1 = r0 + 32 * 128;
+        bf16x8 a[2][2];
+        a[0][0] = *reinterpret_cast<const bf16x8*>(r0 + ((g ^ sw) * 16));
+        a[0][1] = *reinterpret_cast<const bf16x8*>(r1 + ((g ^ sw) * 16));
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            bf16x8 b;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) b[kk] = (bf16)p[8 * s + kk];
-            const int c0 = 4 * kb + 2 * s;     // 16-byte chunk holding keys 32 kb + 16 s .. + 7
-            const bf16x4 lo = *reinterpret_cast<const bf16x4*>(sV + (drow * 8 + swz(drow, c0)) * 16 + 8 * g);
-            const bf16x4 hi = *reinterpret_cast<const bf16x4*>(sV + (drow * 8 + swz(drow, c0 + 1)) * 16 + 8 * g);
-            const bf16x8 a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o, 0, 0, 0);
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) {
+                a[(ks + 1) & 1][0] = *reinterpret_cast<const bf16x8*>(r0 + (((2 * ks + 2 + g) ^ sw) * 16));
+                a[(ks + 1) & 1][1] = *reinterpret_cast<const bf16x8*>(r1 + (((2 * ks + 2 + g) ^ sw) * 16));
+            }
+            __builtin_amdgcn_sched_barrier(0);         // the reads above stay ahead of the MFMAs below
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][0], q[ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][1], q[ks], s1, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    // Row sums of the probabilities on the matrix pipe: ones[32 x 16] P^T adds the 16 keys of a k-step for
-    // every query, in every row of the accumulator (lane halves included), using the same rounded
-    // probabilities as the numerator.  Four of these per tile replace 32 VALU additions per lane.
+    // Key (within its 32-key block) of accumulator element v of the score block in lane half g, under the row
+    // permutation of qk2.
+    static __device__ __forceinline__ int key_of(int v, int g) { return 16 * (v >> 3) + 8 * g + (v & 7); }
+    // O^T (64 dh x 32 queries, two accumulators) += V^T[dh][64 keys] P^T, and the row sums of P.  Four k-steps of 16
+    // keys; the k slot (g, kk) of step (kb, s) is key 32 kb + 16 s + 8 g + kk -- where accumulator element
+    // v = 8 s + kk of score block kb sits, so P needs no shuffle, and a lane's eight keys are one 16-byte chunk of
+    // a V^T row (one conflict-free ds_read_b128 per accumulator and step).  The reads of step + 1 are issued before
+    // the MFMAs of step.
+    // Row sums on the matrix pipe (LM): ones[32 x 16] P^T adds the 16 keys of a k-step for every query, in every
+    // row of the accumulator (lane halves included), using the same rounded probabilities as the numerator; four
+    // of these per tile replace 32 VALU additions per lane.
     static constexpr bool MFMA_ROWSUM = true;
-    static __device__ __forceinline__ void rowsum(f32x16& l, const f32x16& p) {
+    // `sc` holds the raw scores; element e becomes 2^(sc[e] * scale - ref).  The exponentials of step + 1 are issued
+    // behind the MFMAs of step, so the vector pipe works on them while the matrix pipe runs.  psum (LM == false)
+    // receives the lane's sum of probabilities.
+    template <bool LM>
+    static __device__ __forceinline__ void pv_tile(f32x16& o0, f32x16& o1, f32x16& l, float& psum, const char* sV, int li,
+                                                   f32x16* sc, float scale, float ref, int g) {
         const bf16x8 ones = {(bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f, (bf16)1.0f};
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        const int sw = (li >> 1) & 7;                      // rows li and li + 32 share the swizzle term
+        const char* r0 = sV + li * 128;
+        const char* r1 = r0 + 32 * 128;
+        auto probs = [&](int st) {
             bf16x8 b;
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) b[kk] = (bf16)p[8 * s + kk];
-            l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, b, l, 0, 0, 0);
+            for (int kk = 0; kk < 8; ++kk) {
+                const float e = __builtin_amdgcn_exp2f(fmaf(sc[st >> 1][8 * (st & 1) + kk], scale, -ref));
+                if (!LM) psum += e;
+                b[kk] = (bf16)e;
+            }
+            return b;
+        };
+        bf16x8 a[2][2], b[2];
+        a[0][0] = *reinterpret_cast<const bf16x8*>(r0 + ((g ^ sw) * 16));
+        a[0][1] = *reinterpret_cast<const bf16x8*>(r1 + ((g ^ sw) * 16));
+        b[0] = probs(0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            if (st < 3) {
+                a[(st + 1) & 1][0] = *reinterpret_cast<const bf16x8*>(r0 + (((2 * st + 2 + g) ^ sw) * 16));
+                a[(st + 1) & 1][1] = *reinterpret_cast<const bf16x8*>(r1 + (((2 * st + 2 + g) ^ sw) * 16));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            o0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st & 1][0], b[st & 1], o0, 0, 0, 0);
+            o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st & 1][1], b[st & 1], o1, 0, 0, 0);
+            if (LM) l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, b[st & 1], l, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (st < 3) b[(st + 1) & 1] = probs(st + 1);
         }
     }
 };
@@ -115,9 +160,29 @@ template <> struct AttnMma<float> {
             for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x2f32(hi[i], q[ks].hi[i], s, 0, 0, 0);
         }
     }
+    static __device__ __forceinline__ void qk2(f32x16& s0, f32x16& s1, const char* sK, int li, const QFrag* q, int g) {
+        qk(s0, sK, li, q, g);
+        qk(s1, sK, 32 + li, q, g);
+    }
+    static __device__ __forceinline__ int key_of(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
+    template <bool LM>
+    static __device__ __forceinline__ void pv_tile(f32x16& o0, f32x16& o1, f32x16&, float& psum, const char* sV, int li,
+                                                   f32x16* sc, float scale, float ref, int g) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                sc[kb][v] = __builtin_amdgcn_exp2f(fmaf(sc[kb][v], scale, -ref));
+                psum += sc[kb][v];
+            }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            pv(o0, sV, li, kb, sc[kb], g);
+            pv(o1, sV, 32 + li, kb, sc[kb], g);
+        }
+    }
     // one MFMA per score element index v: k slot g is key 8 (v / 4) + 4 g + v % 4 of the block
     static constexpr bool MFMA_ROWSUM = false;
-    static __device__ __forceinline__ void rowsum(f32x16&, const f32x16&) {}
     static __device__ __forceinline__ void pv(f32x16& o, const char* sV, int drow, int kb, const f32x16& p, int g) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -165,8 +230,14 @@ __global__ __launch_bounds__(64 * QW * KW, (attn_min_waves<T, QB, QW, KW>())) vo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qw = wave % QW, kw = wave / QW;
     const int g = lane >> 5, li = lane & 31;
-    const int bh = blockIdx.y, b = bh / p.heads, h = bh % p.heads;
-    const int q0 = blockIdx.x * (32 * QB * QW) + qw * 32 * QB;
+    // One-dimensional grid, (image, head)-major: the hardware deals consecutive workgroups round-robin to the 8 XCDs,
+    // so ids are remapped to give each XCD one contiguous range -- all query blocks of an (image, head) pair then run
+    // on the same XCD and its keys and values are fetched into that L2 once, not into all eight (measured at ViT-g x8:
+    // 615 MB fetched per launch against 135 MB of operands before the remapping).
+    const int nqb = cdiv(p.N, 32 * QB * QW);
+    const int lin = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int bh = lin / nqb, b = bh / p.heads, h = bh % p.heads;
+    const int q0 = (lin % nqb) * (32 * QB * QW) + qw * 32 * QB;
     const int ld = 2 * p.dim;
 
     const T* __restrict__ qk = reinterpret_cast<const T*>(p.qk) + (int64_t)b * p.N * ld + h * 64;
@@ -291,28 +362,27 @@ __global__ __launch_bounds__(64 * QW * KW, (attn_min_waves<T, QB, QW, KW>())) vo
             const char* sK = stage + (kw * 2) * TILE;
             const char* sV = sK + TILE;
             const bool last = t == KT - 1;     // keys past N only exist in the last tile
-    #pragma unroll
+#pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 f32x16 s[2];
-    #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-    #pragma unroll
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
                     for (int v = 0; v < 16; ++v) s[kb][v] = 0.0f;
-                    AttnMma<T>::qk(s[kb], sK, kb * 32 + li, q[qb], g);
-                }
+                AttnMma<T>::qk2(s[0], s[1], sK, li, q[qb], g);
                 if (last) {
-    #pragma unroll
+#pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
-    #pragma unroll
+#pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                            const int key = t * 64 + kb * 32 + AttnMma<T>::key_of(v, g);
                             if (key >= p.N) s[kb][v] = -INFINITY;
                         }
                 }
                 float mx = s[0][0];
-    #pragma unroll
+#pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
-    #pragma unroll
+#pragma unroll
                     for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
                 mx = halves_max(mx);
                 // Lazy rescaling: m_run is the reference the exponentials are taken against (in log2 units), not
@@ -328,34 +398,17 @@ __global__ __launch_bounds__(64 * QW * KW, (attn_min_waves<T, QB, QW, KW>())) vo
                     l_run[qb] *= alpha;
                     m_run[qb] = m_new;
                     if (LMFMA) {
-    #pragma unroll
+#pragma unroll
                         for (int v = 0; v < 16; ++v) lacc[qb][v] *= alpha;
                     }
-    #pragma unroll
+#pragma unroll
                     for (int d = 0; d < 2; ++d)
-    #pragma unroll
+#pragma unroll
                         for (int v = 0; v < 16; ++v) o[qb][d][v] *= alpha;
                 }
-                const float mc = m_run[qb];
                 float psum = 0.0f;
-    #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-    #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][v], p.scale_log2e, -mc));
-                        s[kb][v] = e;
-                        if (!LMFMA) psum += e;
-                    }
-                if (LMFMA) {
-                    AttnMma<T>::rowsum(lacc[qb], s[0]);
-                    AttnMma<T>::rowsum(lacc[qb], s[1]);
-                } else {
-                    l_run[qb] += psum;
-                }
-    #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-    #pragma unroll
-                    for (int d = 0; d < 2; ++d) AttnMma<T>::pv(o[qb][d], sV, d * 32 + li, kb, s[kb], g);
+                AttnMma<T>::template pv_tile<LMFMA>(o[qb][0], o[qb][1], lacc[LMFMA ? qb : 0], psum, sV, li, s, p.scale_log2e, m_run[qb], g);
+                if (!LMFMA) l_run[qb] += psum;
             }
         }
         if constexpr (DB) {
@@ -443,7 +496,7 @@ static inline hipError_t launch_attention_variant(const AttnArgs& a, hipStream_t
     }
     if (configure_only) return hipSuccess;
     if (a.pad < 2 * KW * 64 || a.npad % 64 || a.npad < a.N || a.dim != a.heads * 64) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attention_kernel<T, QB, QW, KW>), dim3(cdiv(a.N, 32 * QB * QW), a.B * a.heads),
+    hipLaunchKernelGGL((attention_kernel<T, QB, QW, KW>), dim3(cdiv(a.N, 32 * QB * QW) * a.B * a.heads),
                        dim3(64 * QW * KW), lds, s, a);
     return hipGetLastError();
 }

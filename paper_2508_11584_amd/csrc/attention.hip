@@ -45,15 +45,17 @@ hipError_t configure_attention() {
 hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {
     const int forced = g_forced_variant;
     // Workgroup shapes measured on MI355X (QB, QW, KW = query blocks per wave, query waves, key waves), us:
-    //                                         (1,2,4) (1,2,2) (2,2,4) (1,4,1) (2,1,4) (1,1,4)
-    //   ViT-S 476x630   (6 x N 1531)            15.8    19.5    22.9    30.0    20.6    28.0
-    //   ViT-B 518x518   (12 x N 1370)           29.4    25.8    25.0    29.0    39.9    42.2
-    //   ViT-L 518x518 x4 (64 x N 1374)          95.1    85.2    78.5    76.7   121.4   158.7
-    //   ViT-g 518x518 x8 (192 x N 1374)        251.2   217.1   212.1   193.3   334.0   447.4
-    // Few (head, 32-query block) pairs want the key axis split over waves to fill the chip; many want one
-    // wave per query block over all keys (no merge, small LDS footprint, several workgroups per CU).
+    //                                         (1,2,4) (1,2,2) (2,2,4) (1,4,1) (1,4,2) (1,8,1)
+    //   ViT-S 476x630   (6 x N 1531)            14.0    15.1    22.3    23.5    19.6      -
+    //   ViT-B 518x518   (12 x N 1370)           25.9    20.3    22.4    22.7      -     31.1
+    //   ViT-L 518x518 x4 (64 x N 1374)          80.2    59.0    67.6    50.9      -     76.2
+    //   ViT-g 518x518 x8 (192 x N 1374)        217.0   153.6   190.7   145.0   164.3   182.0
+    // Few (head, 32-query block) pairs want the key axis split over waves to fill the chip; many want four
+    // query waves sharing each key tile and no merge.  Wider workgroups (eight query waves, or two query blocks per
+    // wave) halve the L2 -> LDS traffic and are slower all the same; narrower ones (two waves) double it and are
+    // slower too.
     const int64_t qblocks = (int64_t)cdiv(a.N, 32) * a.B * a.heads;
-    int variant = qblocks >= 2048 ? 141 : qblocks >= 400 ? 224 : 124;
+    int variant = qblocks >= 2048 ? 141 : qblocks >= 400 ? 122 : 124;
     if (forced) variant = forced;
     return dtype ? launch_variant<bf16>(variant, a, s) : launch_variant<float>(forced == 141 || qblocks >= 2048 ? 141 : 114, a, s);
 }
