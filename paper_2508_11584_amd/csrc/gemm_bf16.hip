@@ -5,6 +5,8 @@
 #include "kernels.h"
 namespace vpe {
 hipError_t launch_gemm_dma_bf16(int bn, const GemmArgs& a, int amode, hipStream_t s);
+bool conv_strip_applies(const GemmArgs& a);
+hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s);
 
 namespace {
 // Candidate tilings: tile, workgroups a CU holds at once, and the two coefficients of the time model
@@ -66,6 +68,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     // pipelined rate with three encoder lanes.
     const bool no_splitk = g_no_splitk;
     if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
+    // 3x3 convolutions: the strip kernel (conv_strip.h) runs where VPE_GEMM_TILE=9 asks for it and it applies
+    if (amode == A_CONV3 && forced == 9 && conv_strip_applies(a) && a.epi != EPI_SWIGLU) return launch_conv_strip_bf16(a, s);
     if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
     if (forced == 4) best = a.epi == EPI_SWIGLU ? 2 : 4;
     if (forced == 64 && fits) best = a.epi == EPI_SWIGLU ? 65 : 64;

@@ -26,6 +26,136 @@ namespace vpe {
 // expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
+// Epilogue of the wave-tiled kernels: each wave stages its MI x NI accumulator blocks 32 rows at a time in its own
+// 32 x WN fp32 block of LDS (the operand buffers are free by now; the caller has put a barrier behind its last
+// read of them) and leaves with 8-column chunks per lane.  lnrow: (mean, rstd) per tile row for GEMMs with a
+// folded LayerNorm (ignored otherwise).
+template <int MI, int NI, int WM, int WN>
+__device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&acc)[MI][NI], char* smem, const float* lnrow,
+                                                   int wave, int wm, int wn, int lane, int m0, int n0) {
+    typedef bf16 T;
+    const int g = lane >> 5, li = lane & 31;
+    float* sC = reinterpret_cast<float*>(smem) + wave * (32 * WN);
+    const int wrow0 = m0 + wm * WM, wcol0 = n0 + wn * WN;
+    // one pass per 32-row block of the wave tile; the block index is a compile-time constant of each pass (a
+    // loop that the optimizer declines to unroll would turn the accumulators into an indexed array in scratch)
+    auto pass = [&](auto I) {
+        constexpr int i = decltype(I)::value;
+        if (p.ln_stats) {
+            // (column sums are loaded here, not before the k loop: this kernel has no registers to spare)
+            float lncs[NI];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int c = wcol0 + j * 32 + li;
+                lncs[j] = c < p.N ? p.ln_colsum[c] : 0.0f;
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const f32x2 st = *reinterpret_cast<const f32x2*>(lnrow + 2 * row);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[i][j][v] = st[1] * (acc[i][j][v] - st[0] * lncs[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sC[(8 * (v >> 2) + 4 * g + (v & 3)) * WN + j * 32 + li] = acc[i][j][v];
+        const int rblk = wrow0 + i * 32;
+        if (p.epi == EPI_SWIGLU) {
+            // groups of 64 physical columns: 32 gate columns, then their 32 linear partners
+            constexpr int CG = WN / 16;                  // 8-wide gate chunks per row
+            T* out = reinterpret_cast<T*>(p.out);
+            for (int it = lane; it < 32 * CG; it += 64) {
+                const int rr = it / CG, cg = it % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
+                const int r = rblk + rr, ca = wcol0 + grp * 64 + j0;
+                if (r < p.M && ca + 40 <= p.N) {
+                    const float* src = sC + rr * WN + grp * 64 + j0;
+                    float h[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float a = src[e] + p.bias[ca + e], b = src[32 + e] + p.bias[ca + 32 + e];
+                        h[e] = a / (1.0f + __expf(-a)) * b;
+                    }
+                    store8(out + (int64_t)r * p.ldo + (ca >> 6) * 32 + j0, h);
+                }
+            }
+        } else if (p.epi == EPI_QKV && wcol0 >= 2 * p.dim) {
+            // value columns, written transposed: one column and 8 consecutive tokens per lane
+            T* vt = reinterpret_cast<T*>(p.out2);
+            for (int it = lane; it < WN * 4; it += 64) {
+                const int cc = it >> 2, rr = (it & 3) * 8;      // 4 lanes = 32 consecutive tokens of a column
+                const int r = rblk + rr, c2 = wcol0 + cc - 2 * p.dim;
+                if (r < p.M && wcol0 + cc < p.N) {
+                    const float bias = p.bias[wcol0 + cc];
+                    float v[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * WN + cc] + bias;
+                    store_tokens8<T>(p, vt, r, c2, v);
+                }
+            }
+        } else if ((p.epi == EPI_RESID || p.epi == EPI_PATCH) && (p.st_out || p.xb_out)) {
+            // 8 consecutive lanes hold the 8 chunks of one 64-column statistics group of a row
+            if constexpr (WN % 64 == 0) {
+                constexpr int CG = WN / 8;
+#pragma unroll
+                for (int it = lane; it < 32 * CG; it += 64) {
+                    const int rr = it / CG, cg = it % CG;
+                    const int r = rblk + rr, c = wcol0 + cg * 8;
+                    const bool active = r < p.M && c < p.N;
+                    float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (active) {
+                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
+                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
+                        v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+                        v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+                    }
+                    resid_stats_chunk<T>(p, r, c, v, active, cg & 7);
+                }
+            }
+        } else if (p.epi == EPI_ROWDOT) {
+            // 8 consecutive lanes hold the 8 chunks of one 64-column projection group of a row
+            if constexpr (WN % 64 == 0) {
+                constexpr int CG = WN / 8;
+                float* out = reinterpret_cast<float*>(p.out);
+#pragma unroll
+                for (int it = lane; it < 32 * CG; it += 64) {
+                    const int rr = it / CG, cg = it % CG;
+                    const int r = rblk + rr, c = wcol0 + cg * 8;
+                    float sum = 0.0f;
+                    if (r < p.M && c < p.N) {
+                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
+                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
+                        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        sum = rowdot_chunk(p, c, v);
+                    }
+                    sum += __shfl_xor(sum, 1);
+                    sum += __shfl_xor(sum, 2);
+                    sum += __shfl_xor(sum, 4);
+                    if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
+                }
+            }
+        } else {
+            constexpr int CG = WN / 8;
+            for (int it = lane; it < 32 * CG; it += 64) {
+                const int rr = it / CG, cg = it % CG;
+                const int r = rblk + rr, c = wcol0 + cg * 8;
+                if (r < p.M && c < p.N) {
+                    const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
+                    const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
+                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    epilogue_chunk<T>(p, r, c, v);
+                }
+            }
+        }
+    };
+    pass(std::integral_constant<int, 0>{});
+    if constexpr (MI > 1) pass(std::integral_constant<int, 1>{});
+    if constexpr (MI > 2) pass(std::integral_constant<int, 2>{});
+    if constexpr (MI > 3) pass(std::integral_constant<int, 3>{});
+    static_assert(MI <= 4, "passes are written out up to four row blocks");
+}
+
 // BK = 64 or 32 elements per k-tile (LDS rows of 128 or 64 bytes), S LDS stages: the loads of tile
 // kt + S - 1 are in flight while tile kt is multiplied, so a load has S - 1 tile times to arrive.
 // OCC workgroups per CU (the launch bound is given in waves per SIMD: OCC * waves / 4).
@@ -232,127 +362,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
         return;
     }
 
-    // --- epilogue.  Each wave stages its accumulators 32 rows at a time in its own 32 x WN fp32
-    // block of LDS (the stage buffers are free now) and leaves with 8-column chunks per lane.
-    float* sC = reinterpret_cast<float*>(smem) + wave * (32 * WN);
-    const int wrow0 = m0 + wm * WM, wcol0 = n0 + wn * WN;
-    // one pass per 32-row block of the wave tile; the block index is a compile-time constant of each pass (a
-    // loop that the optimizer declines to unroll would turn the accumulators into an indexed array in scratch)
-    auto pass = [&](auto I) {
-        constexpr int i = decltype(I)::value;
-        if (p.ln_stats) {
-            // (column sums are loaded here, not before the k loop: this kernel has no registers to spare)
-            float lncs[NI];
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int c = wcol0 + j * 32 + li;
-                lncs[j] = c < p.N ? p.ln_colsum[c] : 0.0f;
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                const f32x2 st = *reinterpret_cast<const f32x2*>(lnrow + 2 * row);
-#pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j][v] = st[1] * (acc[i][j][v] - st[0] * lncs[j]);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sC[(8 * (v >> 2) + 4 * g + (v & 3)) * WN + j * 32 + li] = acc[i][j][v];
-        const int rblk = wrow0 + i * 32;
-        if (p.epi == EPI_SWIGLU) {
-            // groups of 64 physical columns: 32 gate columns, then their 32 linear partners
-            constexpr int CG = WN / 16;                  // 8-wide gate chunks per row
-            T* out = reinterpret_cast<T*>(p.out);
-            for (int it = lane; it < 32 * CG; it += 64) {
-                const int rr = it / CG, cg = it % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
-                const int r = rblk + rr, ca = wcol0 + grp * 64 + j0;
-                if (r < p.M && ca + 40 <= p.N) {
-                    const float* src = sC + rr * WN + grp * 64 + j0;
-                    float h[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float a = src[e] + p.bias[ca + e], b = src[32 + e] + p.bias[ca + 32 + e];
-                        h[e] = a / (1.0f + __expf(-a)) * b;
-                    }
-                    store8(out + (int64_t)r * p.ldo + (ca >> 6) * 32 + j0, h);
-                }
-            }
-        } else if (p.epi == EPI_QKV && wcol0 >= 2 * p.dim) {
-            // value columns, written transposed: one column and 8 consecutive tokens per lane
-            T* vt = reinterpret_cast<T*>(p.out2);
-            for (int it = lane; it < WN * 4; it += 64) {
-                const int cc = it >> 2, rr = (it & 3) * 8;      // 4 lanes = 32 consecutive tokens of a column
-                const int r = rblk + rr, c2 = wcol0 + cc - 2 * p.dim;
-                if (r < p.M && wcol0 + cc < p.N) {
-                    const float bias = p.bias[wcol0 + cc];
-                    float v[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) v[k] = sC[(rr + k) * WN + cc] + bias;
-                    store_tokens8<T>(p, vt, r, c2, v);
-                }
-            }
-        } else if ((p.epi == EPI_RESID || p.epi == EPI_PATCH) && (p.st_out || p.xb_out)) {
-            // 8 consecutive lanes hold the 8 chunks of one 64-column statistics group of a row
-            if constexpr (WN % 64 == 0) {
-                constexpr int CG = WN / 8;
-#pragma unroll
-                for (int it = lane; it < 32 * CG; it += 64) {
-                    const int rr = it / CG, cg = it % CG;
-                    const int r = rblk + rr, c = wcol0 + cg * 8;
-                    const bool active = r < p.M && c < p.N;
-                    float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-                    if (active) {
-                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
-                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
-                        v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
-                        v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
-                    }
-                    resid_stats_chunk<T>(p, r, c, v, active, cg & 7);
-                }
-            }
-        } else if (p.epi == EPI_ROWDOT) {
-            // 8 consecutive lanes hold the 8 chunks of one 64-column projection group of a row
-            if constexpr (WN % 64 == 0) {
-                constexpr int CG = WN / 8;
-                float* out = reinterpret_cast<float*>(p.out);
-#pragma unroll
-                for (int it = lane; it < 32 * CG; it += 64) {
-                    const int rr = it / CG, cg = it % CG;
-                    const int r = rblk + rr, c = wcol0 + cg * 8;
-                    float sum = 0.0f;
-                    if (r < p.M && c < p.N) {
-                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
-                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
-                        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        sum = rowdot_chunk(p, c, v);
-                    }
-                    sum += __shfl_xor(sum, 1);
-                    sum += __shfl_xor(sum, 2);
-                    sum += __shfl_xor(sum, 4);
-                    if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
-                }
-            }
-        } else {
-            constexpr int CG = WN / 8;
-            for (int it = lane; it < 32 * CG; it += 64) {
-                const int rr = it / CG, cg = it % CG;
-                const int r = rblk + rr, c = wcol0 + cg * 8;
-                if (r < p.M && c < p.N) {
-                    const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
-                    const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
-                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    epilogue_chunk<T>(p, r, c, v);
-                }
-            }
-        }
-    };
-    pass(std::integral_constant<int, 0>{});
-    if constexpr (MI > 1) pass(std::integral_constant<int, 1>{});
-    if constexpr (MI > 2) pass(std::integral_constant<int, 2>{});
-    if constexpr (MI > 3) pass(std::integral_constant<int, 3>{});
-    static_assert(MI <= 4, "passes are written out up to four row blocks");
+    wave_tile_epilogue<MI, NI, WM, WN>(p, acc, smem, lnrow, wave, wm, wn, lane, m0, n0);
 }
 
 template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1, int BM = 256>

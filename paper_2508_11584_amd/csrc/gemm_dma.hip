@@ -1,4 +1,5 @@
 // Instantiations of the large-tile direct-to-LDS GEMM.
+#include "conv_strip.h"
 #include "gemm_dma.h"
 #include "kernels.h"
 namespace vpe {
@@ -18,10 +19,15 @@ hipError_t launch_gemm_dma_bf16(int kind, const GemmArgs& a, int amode, hipStrea
     if (kind == 256) return launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, amode, s);
     return launch_gemm_dma<128, 32, 2, 4, 2, 2>(a, amode, s);
 }
+// 3x3 convolution from an input strip in LDS (conv_strip.h): 384 x 256 tiles, 96 x 128 wave tiles.
+bool conv_strip_applies(const GemmArgs& a) { return conv_strip_fits<384, 256>(a); }
+hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s) { return launch_conv_strip<384, 256, 4, 2, 1>(a, s); }
+
 // LDS opt-in (more than 64 KB) where needed; called once at engine creation.
 hipError_t configure_gemm() {
     GemmArgs a{};
-    hipError_t rc = launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, A_PLAIN, nullptr, true);
+    hipError_t rc = launch_conv_strip<384, 256, 4, 2, 1>(a, nullptr, true);
+    if (rc == hipSuccess) rc = launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, A_PLAIN, nullptr, true);

@@ -214,6 +214,19 @@ def test_direct_to_lds_gemm_variant(tile, monkeypatch):
     check_all(spec, 103, 203)
 
 
+def test_strip_convolution_kernel(monkeypatch):
+    # the 3x3 convolution that forms its nine taps from one input strip in LDS, forced for every convolution it can
+    # take (256 output channels per tile): detection towers reading token rows of two images with register tokens in
+    # between, the depth head's four fusion stages on 11x15 ... 88x120 grids (tiles that span several image rows,
+    # both images and the end of the tensor; taps masked at every edge), the last with the 1-channel projection
+    monkeypatch.setenv("VPE_GEMM_TILE", "9")
+    spec = vi.ModelSpec("strip_conv", dtype="bf16", **{**MEDIUM, "head_ch": 256, "batch": 2, "registers": 4})
+    check_all(spec, 108, 208)
+    # one row of patches (every pixel on the top and bottom edge) and a single patch
+    check_all(vi.ModelSpec("strip_conv_row", dtype="bf16", **{**MEDIUM, "head_ch": 256, "img_h": 14, "img_w": 14 * 9}), 109, 209)
+    check_all(vi.ModelSpec("strip_conv_1x1", dtype="bf16", **{**MEDIUM, "head_ch": 256, "img_h": 14, "img_w": 14}), 110, 210)
+
+
 # ---------------------------------------------------------------- full DPT head
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_dpt_head_small_grids_odd_and_even(dtype):
