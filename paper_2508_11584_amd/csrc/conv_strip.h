@@ -3,36 +3,40 @@
 //
 // The generic implicit GEMM (gemm_dma_kernel<.., A_CONV3>) fetches, for every one of the nine taps, a fresh
 // BM x k-tile slice of the input from L2 into LDS: every input element enters LDS nine times per workgroup, and
-// the direct-to-LDS load path is what limits that kernel.  Here a workgroup owns BM CONSECUTIVE pixels of the
-// flattened (image, row, column) index; tap (dy, dx) of pixel p is pixel p + dy W + dx of the same flattened
-// index, so all nine shifted operands live in one strip of BM + 2 W + 2 pixels, loaded ONCE per 16-channel chunk
-// (3.1x fewer input bytes through the load path at BM = 384, W = 360; with the weights, which stream as before,
-// 41 % fewer bytes in all).  What a flat shift gets wrong -- taps that leave the image on the left / right /
-// top / bottom edge and would read the neighbouring row or image instead of zero padding -- is put right on the
-// consumer side: each lane knows, for each of its accumulator row blocks, which of the nine taps are inside
-// the image, and clears the fragment it has read otherwise (four v_and per fragment, in the shadow of the
-// MFMAs).  Strip positions before the first / after the last pixel of the tensor are clamped to valid memory
-// and always masked.
+// the direct-to-LDS load path is what limits that kernel.  Here a workgroup owns BM CONSECUTIVE positions of a
+// padded, flattened pixel index
+//     P(image, y, x) = (image (H + 1) + y + 1) (W + 1) + x,      x = W and y = -1 (= y = H of the image before) are pads,
+// in which tap (dy, dx) of position P is position P + dy (W + 1) + dx, whatever the pixel: one zero column behind
+// every image row and one zero row between images are all the padding a 3x3 window can reach (left of x = 0 lies
+// the pad column of the row above).  So all nine shifted operands of a tile live in one strip of
+// BM + 2 (W + 1) + 2 positions, loaded ONCE per 16-channel chunk (3.1x fewer input bytes through the load path
+// at BM = 384, W = 360; with the weights, which stream as before, 41 % fewer bytes in all), and the zero padding
+// is made by the loader: a pad position fetches from a page of zeros.  The k loop has no masks and no special
+// cases; the price is that pad positions are computed like pixels and thrown away (0.6 % at 272 x 360), and that
+// tile rows are translated back to pixels in the epilogue.
 //
 // k order: channel chunk (16 channels = one MFMA k-step) outer, tap row dy, tap column dx inner.  LDS:
-//   strip   2 stages x SP pixels x 32 bytes   (SP = BM + 2 W + 2 rounded up to 32; stage c & 1 holds chunk c)
-//   weights 2 stages x 3 taps x BN rows x 32 bytes (one tap row per step)
-// One barrier per step (3 taps = 36 MFMAs per wave at a 96 x 128 wave tile); the loads of the next step's
-// weights and a third of the next chunk's strip are issued right behind it.  Rows of both operands are 32 bytes,
+//   strip   2 stages x SP positions x 32 bytes   (SP = BM + 2 W + 4 rounded up to 32; stage c & 1 holds chunk c)
+//   weights 3 stages x 3 taps x BN rows x 32 bytes (one tap row per step)
+// One barrier per step (3 taps = 36 MFMAs per wave at a 96 x 128 wave tile).  Rows of both operands are 32 bytes,
 // a lane's fragment is 16 of them and 32 consecutive lanes read 32 consecutive rows: every ds_read_b128 covers
 // one contiguous kilobyte, no swizzle needed.
 //
-// Same GemmArgs, output maps and epilogues as the generic kernels (A_CONV3 conventions of gemm.h).
+// Same GemmArgs (M = pixels), output maps and epilogues as the generic kernels (A_CONV3 conventions of gemm.h).
 #pragma once
 #include "gemm_dma.h"
 
 namespace vpe {
 
 constexpr int STRIP_KC = 16;              // channels per chunk = one MFMA k-step
-constexpr int STRIP_MAX_SLOTS = 7;        // strip load instructions per wave and chunk (8 waves x 7 x 32 pixels = 1792 at most)
+constexpr int STRIP_MAX_SLOTS = 7;        // strip load instructions per wave and chunk (8 waves x 7 x 32 positions = 1792 at most)
+
+// Padded positions from the first pixel of the first image to the last pixel of the last one (tiles cover exactly
+// this range: the leading pad row and whatever follows the last pixel are nobody's output).
+static inline int64_t strip_positions(int images, int H, int W) { return ((int64_t)(images - 1) * (H + 1) + H) * (W + 1) - 1; }
 
 template <int BM, int BN, int WGM, int WGN, int OCC>
-__global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_strip_kernel(const GemmArgs args, int sp_rows) {
+__global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_strip_kernel(const GemmArgs args, int sp_rows, int tiles_m) {
     const GemmArgs p = select_problem(args);
     constexpr int NW = WGM * WGN;
     static_assert(NW == 8 && BN == 32 * NW, "loader mapping: eight waves, each loads 32 weight rows per tap");
@@ -43,73 +47,68 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int g = lane >> 5, li = lane & 31;
-    const int Wd = p.cW, HW = p.cH * p.cW, C = p.cC;
+    const int Wp = p.cW + 1, Hp = p.cH + 1, C = p.cC;
+    const int images = p.M / (p.cH * p.cW);
 
     int tm, tn;
-    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), tiles_m, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = Wp + tm * BM, n0 = tn * BN;            // position W + 1 is pixel (0, 0) of the first image
 
     const int strip_bytes = sp_rows * 32;
     char* const s_strip = smem;                         // [2][sp_rows][32]
-    char* const s_w = smem + 2 * strip_bytes;           // [2][3][BN][32]
+    char* const s_w = smem + 2 * strip_bytes;           // [3][3][BN][32]
 
     const char* __restrict__ A = reinterpret_cast<const char*>(p.A);
     const char* __restrict__ Wt = reinterpret_cast<const char*>(p.W);
+    const char* zpage = reinterpret_cast<const char*>(p.zeros);
 
-    // --- loader state.  Strip instruction `slot` (32 pixels): lane l fetches half l & 1 of the 32-byte chunk of strip
-    // pixel 32 slot + l / 2, i.e. of flattened pixel m0 - W - 1 + that, clamped into the tensor.  The address is formed
-    // per instruction (a dozen integer operations, seven times per chunk) rather than kept in seven registers.
+    // --- loader.  Strip instruction `slot` (32 positions): lane l fetches half l & 1 of the 32-byte chunk of strip
+    // position 32 slot + l / 2, i.e. of padded position m0 - (W + 1) - 1 + that: a pixel's channels, or zeros for a pad
+    // and for positions outside the tensor.  The address is formed per instruction (two dozen integer operations,
+    // seven times per chunk) rather than kept in seven registers.
     const int nslots = sp_rows / 32;
-    const int qbase = m0 - Wd - 1 + (lane >> 1);
-    const float inv_hw = 1.0f / (float)HW;
+    const int qbase = m0 - Wp - 1 + (lane >> 1);
+    const float inv_wp = 1.0f / (float)Wp, inv_hp = 1.0f / (float)Hp;
     auto strip_src = [&](int slot, int c) -> const char* {
-        int q = qbase + 32 * slot;
-        q = q < 0 ? 0 : (q < p.M ? q : p.M - 1);
-        int img = (int)((float)q * inv_hw);              // q / HW, put right below (the product may be off by one ulp)
-        img += (img + 1) * HW <= q;
-        img -= img * HW > q;
-        const int64_t row = (int64_t)img * p.a_istride + p.a_off + (q - img * HW);
-        return A + (row * p.lda + c * STRIP_KC) * 2 + (lane & 1) * 16;
+        const int q = qbase + 32 * slot;
+        const int qq = q < 0 ? 0 : q;
+        int line = (int)((float)qq * inv_wp);            // qq / Wp, put right below (the product may be off by one)
+        line += (line + 1) * Wp <= qq;
+        line -= line * Wp > qq;
+        const int x = qq - line * Wp;
+        int img = (int)((float)line * inv_hp);
+        img += (img + 1) * Hp <= line;
+        img -= img * Hp > line;
+        const int y = line - img * Hp - 1;
+        const bool pixel = q >= 0 && x < p.cW && y >= 0 && img < images;
+        const int64_t row = (int64_t)img * p.a_istride + p.a_off + y * p.cW + x;
+        const char* src = A + (row * p.lda + c * STRIP_KC) * 2 + (lane & 1) * 16;
+        return pixel ? src : zpage + (lane & 1) * 16;
     };
     // weight rows: lane l fetches half l & 1 of row n0 + 32 wave + l / 2
     const int woff = (int)(((int64_t)(n0 + 32 * wave + (lane >> 1)) * p.K) * 2 + (lane & 1) * 16);
 
-    // third `part` (0..2) of chunk c's strip into strip stage c & 1: slots i with i % 3 == part
+    // this wave's i-th strip instruction (i < STRIP_MAX_SLOTS) of chunk c, into strip stage c & 1
+    auto dma_strip1 = [&](int c, int i) {
+        const int slot = wave + NW * i;
+        if (slot < nslots)
+            __builtin_amdgcn_global_load_lds(VPE_GPTR(strip_src(slot, c)), VPE_LPTR(s_strip + (c & 1) * strip_bytes + slot * 1024), 16, 0, 0);
+    };
+    // half `part` (0 / 1) of chunk c's strip: this wave's instructions with i % 2 == part
     auto dma_strip = [&](int c, int part) {
-        char* dst = s_strip + (c & 1) * strip_bytes;
 #pragma unroll
-        for (int i = 0; i < STRIP_MAX_SLOTS; ++i) {
-            if (i % 3 != part) continue;
-            const int slot = wave + NW * i;
-            if (slot < nslots)
-                __builtin_amdgcn_global_load_lds(VPE_GPTR(strip_src(slot, c)), VPE_LPTR(dst + slot * 1024), 16, 0, 0);
-        }
+        for (int i = 0; i < STRIP_MAX_SLOTS; ++i)
+            if ((i & 1) == part) dma_strip1(c, i);
     };
-    // the three taps of row dy = tg - 1 for chunk c into weight stage `stage`
+    // tap i of row dy = tg - 1 for chunk c into weight stage `stage`
+    auto dma_w1 = [&](int stage, int c, int tg, int i) {
+        __builtin_amdgcn_global_load_lds(VPE_GPTR(Wt + woff + (((tg * 3 + i) * C) + c * STRIP_KC) * 2),
+                                         VPE_LPTR(s_w + stage * WSTAGE + wave * 1024 + i * WTAP), 16, 0, 0);
+    };
     auto dma_w = [&](int stage, int c, int tg) {
-        char* dst = s_w + stage * WSTAGE + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
-            __builtin_amdgcn_global_load_lds(VPE_GPTR(Wt + woff + (((tg * 3 + i) * C) + c * STRIP_KC) * 2), VPE_LPTR(dst + i * WTAP), 16, 0, 0);
+        for (int i = 0; i < 3; ++i) dma_w1(stage, c, tg, i);
     };
-
-    // --- which taps stay inside the image, per accumulator row block of this lane: bit t = 3 (dy + 1) + dx + 1
-    // (row block i in bits 9 i .. 9 i + 8 of one register)
-    static_assert(MI <= 3, "nine bits per row block in one 32-bit register");
-    uint32_t inside = 0;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        int r = m0 + wm * WM + i * 32 + li;
-        r = r < p.M ? r : p.M - 1;
-        const int pix = r % HW, y = pix / Wd, x = pix % Wd;
-        uint32_t bits = 0;
-#pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
-            if (yy >= 0 && yy < p.cH && xx >= 0 && xx < Wd) bits |= 1u << t;
-        }
-        inside |= bits << (9 * i);
-    }
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -119,68 +118,93 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // --- operand reads.  Strip row of accumulator row r for tap (tg, i): r + tg W + i (the strip starts W + 1
-    // pixels before the tile); weight row n of tap i: i WTAP + 32 n.
+    // --- operand reads.  Strip row of tile row r for tap (tg, i): r + tg (W + 1) + i (the strip starts W + 2
+    // positions before the tile); weight row n of tap i: i WTAP + 32 n.
+    // One step = the three taps of a tap row = 9 (tap, row block) groups of NI MFMAs.  Weight fragments of a tap stay
+    // in registers for its three row blocks (16 registers) and are re-read for the next tap one by one, each right
+    // behind its last MFMA; strip fragments are double-buffered one group ahead (2 x 4 registers).  The weights sit in
+    // THREE stages, so the operands of step s + 1 are complete and visible a whole step early and the last group of
+    // step s reads the first fragments of step s + 1: the MFMA stream runs through the step boundary and its barrier.
     const int abase = (wm * WM + li) * 32 + g * 16, bbase = (wn * WN + li) * 32 + g * 16;
-    auto compute = [&](const char* strip, const char* wts, int tg) {
+    bf16x8 fb[NI], fa[2];
+    // The step's loads (next-but-one step's weights: lw_* ; half of the next chunk's strip: ls_*) are issued one
+    // instruction per group, between the MFMAs: eight waves issuing all of theirs at once right behind the barrier
+    // queue up at the CU's one address unit, and a wave stuck at issue starts no MFMA either.
+    auto compute = [&](const char* strip, const char* wts, int tg, const char* nstrip, const char* nwts, int ntg, bool more,
+                       bool lw, int lw_stage, int lw_c, int lw_tg, bool ls, int ls_c, int ls_part) {
+        const char* sa = strip + abase + tg * Wp * 32;
+        const char* sb = wts + bbase;
+        const char* na = nstrip + abase + ntg * Wp * 32;
+        const char* nb = nwts + bbase;
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
-            const char* sa = strip + abase + (tg * Wd + i) * 32;
-            const char* sb = wts + bbase + i * WTAP;
-            u32x4 fa[MI];
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) fa[mi] = *reinterpret_cast<const u32x4*>(sa + mi * 32 * 32);
-            if (!(tg == 1 && i == 1)) {           // the centre tap is always inside
+            for (int mi = 0; mi < MI; ++mi) {
+                const int cur = (i * MI + mi) & 1;
+                const bool last = i == 2 && mi == MI - 1;
+                if (mi + 1 < MI) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa + i * 32 + (mi + 1) * 1024);
+                else if (i < 2) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa + (i + 1) * 32);
+                else if (more) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(na);
+                const int k = i * MI + mi;                // group 0..8: weights in groups 0..2, strip instructions in 3..6
+                if (k < 3) { if (lw) dma_w1(lw_stage, lw_c, lw_tg, k); }
+                else if (k - 3 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) dma_strip1(ls_c, 2 * (k - 3) + ls_part); }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    const uint32_t keep = 0u - ((inside >> (9 * mi + tg * 3 + i)) & 1u);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) fa[mi][e] &= keep;
+                for (int nj = 0; nj < NI; ++nj) {
+                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur], fb[nj], acc[mi][nj], 0, 0, 0);
+                    if (mi == MI - 1 && i < 2) fb[nj] = *reinterpret_cast<const bf16x8*>(sb + (i + 1) * WTAP + nj * 1024);
+                    if (last && more) fb[nj] = *reinterpret_cast<const bf16x8*>(nb + nj * 1024);
                 }
-            }
-            // weight fragments one column block at a time (the register file has no room for all four at once)
-#pragma unroll
-            for (int nj = 0; nj < NI; ++nj) {
-                const bf16x8 fb = *reinterpret_cast<const bf16x8*>(sb + nj * 32 * 32);
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[mi]), fb, acc[mi][nj], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        static_assert((3 * MI) % 2 == 1, "nine groups per step: the last one prefetches into the odd buffer");
+        fa[0] = fa[1];                                   // the next step starts on the even buffer again
     };
 
-    // --- main loop: step s = 3 c + tg.  Top of a step: everything this wave has in flight has landed (the current
-    // step's weights, the strip third issued a step ago), barrier (everyone's has, and everyone is done with the
-    // stages about to be overwritten), then the next step's weights and a third of the next chunk's strip.
+    // --- main loop: step s = 3 c + tg.  Top of a step: this wave's loads for step s + 1 have landed, barrier (everyone's
+    // have, and everyone is done with step s - 1), then the loads of step s + 2's weights (into the stage step s - 1
+    // used) and, in the first two steps of a chunk, half of the next chunk's strip (into the stage chunk c - 1 used).
     const int NC = C / STRIP_KC, NS = 3 * NC;
     dma_strip(0, 0);
     dma_strip(0, 1);
-    dma_strip(0, 2);
     dma_w(0, 0, 0);
+    dma_w(1, 0, 1);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+#pragma unroll
+    for (int nj = 0; nj < NI; ++nj) fb[nj] = *reinterpret_cast<const bf16x8*>(s_w + bbase + nj * 1024);
+    fa[0] = *reinterpret_cast<const bf16x8*>(s_strip + abase);
+    int wst = 0;                                         // weight stage of step s (s % 3)
     for (int s = 0; s < NS; ++s) {
         const int c = s / 3, tg = s - 3 * c;
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __syncthreads();
-        if (s + 1 < NS) dma_w((s + 1) & 1, (s + 1) / 3, (s + 1) % 3);
-        if (c + 1 < NC) dma_strip(c + 1, tg);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(s_strip + (c & 1) * strip_bytes, s_w + (s & 1) * WSTAGE, tg);
+        if (s > 0) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();
+        }
+        const int nst = wst == 2 ? 0 : wst + 1, nc = (s + 1) / 3, ntg = (s + 1) - 3 * nc;
+        compute(s_strip + (c & 1) * strip_bytes, s_w + wst * WSTAGE, tg, s_strip + (nc & 1) * strip_bytes, s_w + nst * WSTAGE, ntg, s + 1 < NS,
+                s + 2 < NS, wst == 0 ? 2 : wst - 1, (s + 2) / 3, (s + 2) % 3, c + 1 < NC && tg < 2, c + 1, tg);
+        wst = nst;
     }
     __syncthreads();                                     // the staging blocks of the epilogue overlay the operand buffers
 
-    wave_tile_epilogue<MI, NI, WM, WN>(p, acc, smem, nullptr, wave, wm, wn, lane, m0, n0);
+    wave_tile_epilogue<MI, NI, WM, WN, true>(p, acc, smem, nullptr, wave, wm, wn, lane, m0, n0);
 }
 
-// Strip rows (pixels) a tile needs, rounded up to whole load instructions.
+// Strip rows (positions) a tile needs, rounded up to whole load instructions.
 template <int BM>
-static inline int strip_rows(int W) { return (int)rup(BM + 2 * W + 2, 32); }
+static inline int strip_rows(int W) { return (int)rup(BM + 2 * (W + 1) + 2, 32); }
 
-// Can this convolution run on the strip kernel?  (bf16; whole 256-column tiles; 16-channel chunks; the strip of a
-// tile within the per-wave load slots; 32-bit byte offsets.)
+// Can this convolution run on the strip kernel?  (bf16; whole BN-column tiles; 16-channel chunks; whole images; the
+// strip of a tile within the per-wave load slots and, with the weights, within the LDS; 32-bit byte offsets.)
 template <int BM, int BN>
 static inline bool conv_strip_fits(const GemmArgs& a) {
-    if (a.cC % STRIP_KC || a.N % BN || a.K != 9 * a.cC || a.ln_stats) return false;
-    if (strip_rows<BM>(a.cW) > 8 * STRIP_MAX_SLOTS * 32) return false;
+    if (a.cC % STRIP_KC || a.N % BN || a.K != 9 * a.cC || a.ln_stats || !a.zeros) return false;
+    if (a.cH < 1 || a.cW < 1 || a.M % (a.cH * a.cW)) return false;
+    const int sp = strip_rows<BM>(a.cW);
+    if (sp > 8 * STRIP_MAX_SLOTS * 32 || 2 * sp * 32 + 3 * 3 * BN * 32 > 160 * 1024) return false;
+    if (strip_positions(a.M / (a.cH * a.cW), a.cH, a.cW) + BM >= (int64_t(1) << 31)) return false;
     const int64_t rows = (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride + a.a_off;
     return rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
 }
@@ -199,11 +223,12 @@ static inline hipError_t launch_conv_strip(const GemmArgs& a, hipStream_t s, boo
     if (configure_only) return hipSuccess;
     if (!conv_strip_fits<BM, BN>(a)) return hipErrorInvalidValue;
     const int sp = strip_rows<BM>(a.cW);
-    const int ops_b = 2 * sp * 32 + 2 * 3 * BN * 32;
+    const int ops_b = 2 * sp * 32 + 3 * 3 * BN * 32;
     const int lds = ops_b > epi_b ? ops_b : epi_b;
     if (lds > max_lds) return hipErrorInvalidValue;
-    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
-    hipLaunchKernelGGL((conv_strip_kernel<BM, BN, WGM, WGN, OCC>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a, sp);
+    const int tiles_m = (int)((strip_positions(a.M / (a.cH * a.cW), a.cH, a.cW) + BM - 1) / BM);
+    const int tiles = tiles_m * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
+    hipLaunchKernelGGL((conv_strip_kernel<BM, BN, WGM, WGN, OCC>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a, sp, tiles_m);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@
 namespace vpe {
 hipError_t launch_gemm_dma_bf16(int bn, const GemmArgs& a, int amode, hipStream_t s);
 bool conv_strip_applies(const GemmArgs& a);
+int64_t conv_strip_tiles(const GemmArgs& a);
 hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s);
 
 namespace {
@@ -19,9 +20,9 @@ namespace {
 // model's pick is the measured best on 23 of them, within 8 % on four and 15 % on one (0.4 % in total time).
 // Tuning aids, read from the environment when an engine is created (configure_gemm_bf16), never per launch:
 // VPE_GEMM_TILE forces a tiling, VPE_NO_SMALL_DMA leaves the two small direct-to-LDS shapes out, VPE_NO_SPLITK
-// the split-k kernel.
+// the split-k kernel, VPE_NO_STRIP the strip convolution.
 int g_forced_tile = 0;
-bool g_no_small = false, g_no_splitk = false;
+bool g_no_small = false, g_no_splitk = false, g_no_strip = false;
 struct Cand { int kind, bm, bn, held; float alpha, beta; bool dma; };
 constexpr Cand kCands[] = {
     {128, 256, 128, 2, 5.16f, 1.055f, true},    // direct-to-LDS, 8 waves, 64 x 64 wave tiles
@@ -68,8 +69,14 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     // pipelined rate with three encoder lanes.
     const bool no_splitk = g_no_splitk;
     if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
-    // 3x3 convolutions: the strip kernel (conv_strip.h) runs where VPE_GEMM_TILE=9 asks for it and it applies
-    if (amode == A_CONV3 && forced == 9 && conv_strip_applies(a) && a.epi != EPI_SWIGLU) return launch_conv_strip_bf16(a, s);
+    // 3x3 convolutions: the strip kernel (conv_strip.h) where its 384 x 256 tiles make one well-filled round of the
+    // 256 CUs (measured on 272 x 360 x 256 -> 256, 256 tiles: 128 against 144 us for the generic 384 x 256 kernel on the
+    // same box; with several rounds -- 4 x 296 x 296: 477 against 443 us -- the generic kernels stay ahead).
+    // VPE_GEMM_TILE=9 forces it wherever it applies, any other forced tile switches it off.
+    if (amode == A_CONV3 && (forced == 9 || (forced == 0 && !g_no_strip)) && conv_strip_applies(a) && a.epi != EPI_SWIGLU) {
+        const int64_t t = conv_strip_tiles(a);
+        if (forced == 9 || (t > 192 && t <= 256)) return launch_conv_strip_bf16(a, s);
+    }
     if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
     if (forced == 4) best = a.epi == EPI_SWIGLU ? 2 : 4;
     if (forced == 64 && fits) best = a.epi == EPI_SWIGLU ? 65 : 64;
@@ -89,6 +96,7 @@ hipError_t configure_gemm_bf16() {
     g_forced_tile = env ? atoi(env) : 0;
     g_no_small = getenv("VPE_NO_SMALL_DMA") != nullptr;
     g_no_splitk = getenv("VPE_NO_SPLITK") != nullptr;
+    g_no_strip = getenv("VPE_NO_STRIP") != nullptr;
     GemmArgs a{};
     return launch_tile_splitk<bf16, 64, 64, 2, 2, 2>(a, A_PLAIN, nullptr, true);
 }

@@ -30,7 +30,19 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // 32 x WN fp32 block of LDS (the operand buffers are free by now; the caller has put a barrier behind its last
 // read of them) and leaves with 8-column chunks per lane.  lnrow: (mean, rstd) per tile row for GEMMs with a
 // folded LayerNorm (ignored otherwise).
-template <int MI, int NI, int WM, int WN>
+// Row index of a tile row in the output.  PADDED (the strip convolution): tile rows run over the padded pixel index
+// ((image (H + 1) + y + 1) (W + 1) + x: one zero column behind every image row, one zero row between images); pad
+// positions have no output (returned as a row past M).
+template <bool PADDED>
+__device__ __forceinline__ int epilogue_row(const GemmArgs& p, int r) {
+    if (!PADDED) return r;
+    const int wp = p.cW + 1, hp = p.cH + 1;
+    const int line = r / wp, x = r - line * wp;
+    const int img = line / hp, y = line - img * hp - 1;
+    return (x < p.cW && y >= 0) ? (img * p.cH + y) * p.cW + x : 0x7fffffff;
+}
+
+template <int MI, int NI, int WM, int WN, bool PADDED = false>
 __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&acc)[MI][NI], char* smem, const float* lnrow,
                                                    int wave, int wm, int wn, int lane, int m0, int n0) {
     typedef bf16 T;
@@ -68,7 +80,7 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
             T* out = reinterpret_cast<T*>(p.out);
             for (int it = lane; it < 32 * CG; it += 64) {
                 const int rr = it / CG, cg = it % CG, grp = cg >> 2, j0 = (cg & 3) * 8;
-                const int r = rblk + rr, ca = wcol0 + grp * 64 + j0;
+                const int r = epilogue_row<PADDED>(p, rblk + rr), ca = wcol0 + grp * 64 + j0;
                 if (r < p.M && ca + 40 <= p.N) {
                     const float* src = sC + rr * WN + grp * 64 + j0;
                     float h[8];
@@ -85,7 +97,7 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
             T* vt = reinterpret_cast<T*>(p.out2);
             for (int it = lane; it < WN * 4; it += 64) {
                 const int cc = it >> 2, rr = (it & 3) * 8;      // 4 lanes = 32 consecutive tokens of a column
-                const int r = rblk + rr, c2 = wcol0 + cc - 2 * p.dim;
+                const int r = epilogue_row<PADDED>(p, rblk + rr), c2 = wcol0 + cc - 2 * p.dim;
                 if (r < p.M && wcol0 + cc < p.N) {
                     const float bias = p.bias[wcol0 + cc];
                     float v[8];
@@ -101,7 +113,7 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
 #pragma unroll
                 for (int it = lane; it < 32 * CG; it += 64) {
                     const int rr = it / CG, cg = it % CG;
-                    const int r = rblk + rr, c = wcol0 + cg * 8;
+                    const int r = epilogue_row<PADDED>(p, rblk + rr), c = wcol0 + cg * 8;
                     const bool active = r < p.M && c < p.N;
                     float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
                     if (active) {
@@ -121,7 +133,7 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
 #pragma unroll
                 for (int it = lane; it < 32 * CG; it += 64) {
                     const int rr = it / CG, cg = it % CG;
-                    const int r = rblk + rr, c = wcol0 + cg * 8;
+                    const int r = epilogue_row<PADDED>(p, rblk + rr), c = wcol0 + cg * 8;
                     float sum = 0.0f;
                     if (r < p.M && c < p.N) {
                         const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
@@ -139,7 +151,7 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
             constexpr int CG = WN / 8;
             for (int it = lane; it < 32 * CG; it += 64) {
                 const int rr = it / CG, cg = it % CG;
-                const int r = rblk + rr, c = wcol0 + cg * 8;
+                const int r = epilogue_row<PADDED>(p, rblk + rr), c = wcol0 + cg * 8;
                 if (r < p.M && c < p.N) {
                     const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
                     const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);

@@ -21,6 +21,9 @@ hipError_t launch_gemm_dma_bf16(int kind, const GemmArgs& a, int amode, hipStrea
 }
 // 3x3 convolution from an input strip in LDS (conv_strip.h): 384 x 256 tiles, 96 x 128 wave tiles.
 bool conv_strip_applies(const GemmArgs& a) { return conv_strip_fits<384, 256>(a); }
+int64_t conv_strip_tiles(const GemmArgs& a) {
+    return (strip_positions(a.M / (a.cH * a.cW), a.cH, a.cW) + 383) / 384 * cdiv(a.N, 256) * (a.nz > 1 ? a.nz : 1);
+}
 hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s) { return launch_conv_strip<384, 256, 4, 2, 1>(a, s); }
 
 // LDS opt-in (more than 64 KB) where needed; called once at engine creation.
