@@ -18,9 +18,14 @@
 // k order: channel chunk (16 channels = one MFMA k-step) outer, tap row dy, tap column dx inner.  LDS:
 //   strip   2 stages x SP positions x 32 bytes   (SP = BM + 2 W + 4 rounded up to 32; stage c & 1 holds chunk c)
 //   weights 3 stages x 3 taps x BN rows x 32 bytes (one tap row per step)
-// One barrier per step (3 taps = 36 MFMAs per wave at a 96 x 128 wave tile).  Rows of both operands are 32 bytes,
-// a lane's fragment is 16 of them and 32 consecutive lanes read 32 consecutive rows: every ds_read_b128 covers
-// one contiguous kilobyte, no swizzle needed.
+// One barrier per step (3 taps = 36 MFMAs per wave at a 96 x 128 wave tile).  Rows of both operands are 32 bytes and
+// a lane's fragment is one 16-byte half of a row.  Stored plainly, the 16 lanes the LDS serves per cycle would sit
+// 32 bytes apart and collide two by two on the 64 banks (measured: 2.8 conflict cycles per busy cycle), so the two
+// halves of a row change places in every other group of eight rows: half g of row r sits at
+//     32 r + 16 (g ^ ((r >> 3) & 1)).
+// Rows r and r + 8 then fall into different 16-byte bank groups, for any run of 16 consecutive rows, i.e. for every
+// tap shift; the loader makes the exchange by fetching the other half (adjacent lanes still fetch the two halves
+// of one row).
 //
 // Same GemmArgs (M = pixels), output maps and epilogues as the generic kernels (A_CONV3 conventions of gemm.h).
 #pragma once
@@ -62,12 +67,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     const char* __restrict__ Wt = reinterpret_cast<const char*>(p.W);
     const char* zpage = reinterpret_cast<const char*>(p.zeros);
 
-    // --- loader.  Strip instruction `slot` (32 positions): lane l fetches half l & 1 of the 32-byte chunk of strip
+    // --- loader.  Strip instruction `slot` (32 positions): lane l fetches one half of the 32-byte chunk of strip
     // position 32 slot + l / 2, i.e. of padded position m0 - (W + 1) - 1 + that: a pixel's channels, or zeros for a pad
     // and for positions outside the tensor.  The address is formed per instruction (two dozen integer operations,
     // seven times per chunk) rather than kept in seven registers.
     const int nslots = sp_rows / 32;
-    const int qbase = m0 - Wp - 1 + (lane >> 1);
+    const int qbase = m0 - Wp - 1 + (lane >> 1);          // lane l: row l / 2 of the instruction's 32, physical half l % 2
+    const int lhalf = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;   // ... which holds this logical half (rows 8..15, 24..31 exchanged)
     const float inv_wp = 1.0f / (float)Wp, inv_hp = 1.0f / (float)Hp;
     auto strip_src = [&](int slot, int c) -> const char* {
         const int q = qbase + 32 * slot;
@@ -82,11 +88,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
         const int y = line - img * Hp - 1;
         const bool pixel = q >= 0 && x < p.cW && y >= 0 && img < images;
         const int64_t row = (int64_t)img * p.a_istride + p.a_off + y * p.cW + x;
-        const char* src = A + (row * p.lda + c * STRIP_KC) * 2 + (lane & 1) * 16;
-        return pixel ? src : zpage + (lane & 1) * 16;
+        const char* src = A + (row * p.lda + c * STRIP_KC) * 2 + lhalf;
+        return pixel ? src : zpage;
     };
-    // weight rows: lane l fetches half l & 1 of row n0 + 32 wave + l / 2
-    const int woff = (int)(((int64_t)(n0 + 32 * wave + (lane >> 1)) * p.K) * 2 + (lane & 1) * 16);
+    // weight rows: lane l fetches row n0 + 32 wave + l / 2, the same exchange of halves
+    const int woff = (int)(((int64_t)(n0 + 32 * wave + (lane >> 1)) * p.K) * 2 + lhalf);
 
     // this wave's i-th strip instruction (i < STRIP_MAX_SLOTS) of chunk c, into strip stage c & 1
     auto dma_strip1 = [&](int c, int i) {
@@ -125,16 +131,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     // behind its last MFMA; strip fragments are double-buffered one group ahead (2 x 4 registers).  The weights sit in
     // THREE stages, so the operands of step s + 1 are complete and visible a whole step early and the last group of
     // step s reads the first fragments of step s + 1: the MFMA stream runs through the step boundary and its barrier.
-    const int abase = (wm * WM + li) * 32 + g * 16, bbase = (wn * WN + li) * 32 + g * 16;
+    const int arow = wm * WM + li, bbase = (wn * WN + li) * 32 + ((g ^ ((li >> 3) & 1)) << 4);
+    auto aoff = [&](int row) { return (row << 5) + ((g ^ ((row >> 3) & 1)) << 4); };   // LDS offset of this lane's half of strip row `row`
     bf16x8 fb[NI], fa[2];
     // The step's loads (next-but-one step's weights: lw_* ; half of the next chunk's strip: ls_*) are issued one
     // instruction per group, between the MFMAs: eight waves issuing all of theirs at once right behind the barrier
     // queue up at the CU's one address unit, and a wave stuck at issue starts no MFMA either.
     auto compute = [&](const char* strip, const char* wts, int tg, const char* nstrip, const char* nwts, int ntg, bool more,
                        bool lw, int lw_stage, int lw_c, int lw_tg, bool ls, int ls_c, int ls_part) {
-        const char* sa = strip + abase + tg * Wp * 32;
+        const char* sa[3] = {strip + aoff(arow + tg * Wp), strip + aoff(arow + tg * Wp + 1), strip + aoff(arow + tg * Wp + 2)};
         const char* sb = wts + bbase;
-        const char* na = nstrip + abase + ntg * Wp * 32;
+        const char* na = nstrip + aoff(arow + ntg * Wp);
         const char* nb = nwts + bbase;
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
@@ -142,8 +149,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
             for (int mi = 0; mi < MI; ++mi) {
                 const int cur = (i * MI + mi) & 1;
                 const bool last = i == 2 && mi == MI - 1;
-                if (mi + 1 < MI) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa + i * 32 + (mi + 1) * 1024);
-                else if (i < 2) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa + (i + 1) * 32);
+                if (mi + 1 < MI) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa[i] + (mi + 1) * 1024);
+                else if (i < 2) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa[i + 1]);
                 else if (more) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(na);
                 const int k = i * MI + mi;                // group 0..8: weights in groups 0..2, strip instructions in 3..6
                 if (k < 3) { if (lw) dma_w1(lw_stage, lw_c, lw_tg, k); }
@@ -174,7 +181,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     __syncthreads();
 #pragma unroll
     for (int nj = 0; nj < NI; ++nj) fb[nj] = *reinterpret_cast<const bf16x8*>(s_w + bbase + nj * 1024);
-    fa[0] = *reinterpret_cast<const bf16x8*>(s_strip + abase);
+    fa[0] = *reinterpret_cast<const bf16x8*>(s_strip + aoff(arow));
     int wst = 0;                                         // weight stage of step s (s % 3)
     for (int s = 0; s < NS; ++s) {
         const int c = s / 3, tg = s - 3 * c;
