@@ -381,7 +381,8 @@ def main() -> None:
         b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-        fams = ["qkv_gemm", "attention", "layernorm", "depth_conv3x3", "depth_fuse_upsample", "proj_gemm", "fc1_gemm", "fc2_gemm"]
+        fams = ["qkv_gemm", "attention", "layernorm", "depth_conv3x3", "depth_fuse_upsample", "proj_gemm", "fc1_gemm", "fc2_gemm",
+                "standalone_activation", "fc1_gemm_no_activation"]
         rows = {}
         for which, name in enumerate(fams):
             if which in (3, 4) and "depth" not in kinds:
@@ -447,10 +448,10 @@ def main() -> None:
     kern = {}
     shared_step(0)
     eng.sync()
-    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm"), (5, "proj_gemm"), (6, "fc1_gemm"), (7, "fc2_gemm")) + (((3, "depth_conv3x3"), (4, "depth_fuse_upsample")) if "depth" in kinds else ()):
+    for which, name in ((0, "qkv_gemm"), (1, "attention"), (2, "layernorm"), (5, "proj_gemm"), (6, "fc1_gemm"), (7, "fc2_gemm"), (8, "standalone_activation"), (9, "fc1_gemm_no_activation")) + (((3, "depth_conv3x3"), (4, "depth_fuse_upsample")) if "depth" in kinds else ()):
         ms, fl, by = eng.time_kernel(which, args.kernel_reps)
         kern[name] = {"us": round(ms * 1e3, 2), "tflops": round(fl / ms / 1e9, 2), "gbps": round(by / ms / 1e6, 1)}
-        if name in ("layernorm", "depth_fuse_upsample"):            # bandwidth-bound kernels: fraction of the 8 TB/s HBM peak
+        if name in ("layernorm", "depth_fuse_upsample", "standalone_activation"):            # bandwidth-bound kernels: fraction of the 8 TB/s HBM peak
             kern[name]["hbm_frac"] = round(by / ms / 1e6 / 8000.0, 4)
         if name == "depth_conv3x3" or (name == "qkv_gemm" and "depth" not in kinds):
             peak = MFMA_PEAK_TFLOPS[spec.dtype]

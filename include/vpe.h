@@ -311,7 +311,9 @@ int vpe_stage_times(vpe_engine* e, float* encode_ms, float* head_ms, int n);
  * kernel of block 0, 2 = LayerNorm, 3 = the depth head's largest 3x3 convolution (last fusion stage; needs a
  * depth head), 4 = the resample-and-add kernel that writes that convolution's input (needs a depth head),
  * 5 = the out-projection GEMM of block 0 (LayerScale + residual epilogue), 6 = its fc1 GEMM (LayerNorm folded in,
- * GELU or SwiGLU epilogue), 7 = its fc2 GEMM (LayerScale + residual epilogue).
+ * GELU or SwiGLU epilogue), 7 = its fc2 GEMM (LayerScale + residual epilogue), 8 = a stand-alone activation pass over
+ * the MLP hidden buffer (the bandwidth-bound kernel the fused epilogue replaces), 9 = the fc1 GEMM with a plain store
+ * (no activation; mlp_hidden columns): 9 + 8 against 6 is what the fusion saves.
  * Also reports the algorithmic flops and bytes of one launch. */
 int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, double* flops, double* bytes);
 

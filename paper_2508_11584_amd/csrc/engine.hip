@@ -1426,12 +1426,15 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 a.epi = EPI_RESID; a.gamma = which == 5 ? w.ls1 : w.ls2;
                 produce_stats(*e, L0, a, L0.lev[1]);
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
-            } else if (which == 6) {
+            } else if (which == 6 || which == 9) {
                 GemmArgs a = ln_gemm(*e, L0, e->blk[0].fc1_w, e->blk[0].fc1_b, e->blk[0].fc1_s, e->F, L0.lev[1], nullptr);
                 a.out = L0.hid; a.ldo = e->Mh;
-                if (e->cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
+                if (which == 9) { a.N = e->Mh; }             // plain store of the first mlp_hidden columns: no activation
+                else if (e->cfg.mlp_kind == VPE_MLP_SWIGLU) a.epi = EPI_SWIGLU;
                 else a.act = ACT_GELU;
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
+            } else if (which == 8) {
+                HIPCHK(e, launch_activation(dt, L0.hid, T, e->Mh, e->cfg.mlp_kind == VPE_MLP_SWIGLU, s));
             } else if (which == 2) {
                 // into the attention-output scratch: same size as a feature map, rewritten by the next encode before it is read
                 HIPCHK(e, launch_layernorm(dt, L0.x, T, D, e->norm_g, e->norm_b, e->cfg.ln_eps, L0.att, s));
@@ -1451,7 +1454,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
         if (timed) HIPCHK(e, hipEventRecord(t1, s));
         return 0;
     };
-    if (which < 0 || which > 7 || ((which == 3 || which == 4) && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
+    if (which < 0 || which > 9 || ((which == 3 || which == 4) && !dh)) rc = e->fail(VPE_EINVAL, "no such kernel to time");
     if (!rc) rc = body(false);   // warm-up launch
     if (!rc) rc = body(true);
     if (!rc && hipEventSynchronize(t1) != hipSuccess) rc = e->fail(VPE_EHIP, "hipEventSynchronize failed");
@@ -1466,6 +1469,11 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
     else if (which == 2) { fl = 8.0 * T * D; by = (4.0 + esz) * T * D; }
     else if (which == 5) { fl = 2.0 * T * D * D; by = esz * ((double)T * D + (double)D * D) + (8.0 + esz) * T * D; }
     else if (which == 6) { fl = 2.0 * T * D * (double)e->F; by = esz * ((double)T * D + (double)D * e->F + (double)T * e->Mh); }
+    else if (which == 8) {
+        const double n = (double)T * e->Mh * (e->cfg.mlp_kind == VPE_MLP_SWIGLU ? 0.5 : 1.0);
+        fl = 12.0 * n; by = esz * (e->cfg.mlp_kind == VPE_MLP_SWIGLU ? 3.0 : 2.0) * n;
+    }
+    else if (which == 9) { fl = 2.0 * T * D * (double)e->Mh; by = esz * ((double)T * D + (double)D * e->Mh + (double)T * e->Mh); }
     else if (which == 7) { fl = 2.0 * T * D * (double)e->Mh; by = esz * ((double)T * e->Mh + (double)D * e->Mh) + (8.0 + esz) * T * D; }
     else if (which == 4) {
         const double ch = dh->ch, pix = (double)e->B * e->P;

@@ -18,6 +18,7 @@ hipError_t configure_gemm_f32();
 
 hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const float* g, const float* b,
                             float eps, void* y, hipStream_t s);
+hipError_t launch_activation(int dtype, void* h, int64_t rows, int cols, int gated, hipStream_t s);
 hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
                          const float* special, int nspecial, int ntok, int D, float* x, void* xb, float* stats,
                          const float* level, hipStream_t s);

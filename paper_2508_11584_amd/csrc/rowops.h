@@ -6,6 +6,33 @@
 
 namespace vpe {
 
+// Stand-alone MLP activation over a hidden buffer h [rows][cols] in place, 8 elements per thread: the bandwidth-bound
+// pass that the GEMM epilogues make unnecessary (kept for measuring what the fusion saves).  gated == 0: erf-GELU of
+// every element; gated != 0: column j < cols / 2 becomes SiLU(h[j]) * h[j + cols / 2] (cols multiple of 16).
+template <typename T>
+__global__ __launch_bounds__(256) void activation_kernel(T* __restrict__ h, int64_t rows, int cols, int gated) {
+    const int per_row = (gated ? cols / 2 : cols) / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * per_row) return;
+    const int64_t r = idx / per_row;
+    const int c = (int)(idx - r * per_row) * 8;
+    T* p = h + r * cols + c;
+    float v[8], w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = to_f32(p[i]);
+    if (gated) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = to_f32(p[cols / 2 + i]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = v[i] / (1.0f + __expf(-v[i])) * w[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = gelu_erf(v[i]);
+    }
+    store8(p, v);
+}
+
+
 // LayerNorm over the last axis of the fp32 residual stream: y = g (x - mean) / sqrt(var + eps) + b
 // with the biased variance; statistics in fp32 (mean first, then centred second moment, both
 // from registers).  One wave per row, 4 rows per workgroup.  D multiple of 64, D <= 64 * 32.

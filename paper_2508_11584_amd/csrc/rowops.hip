@@ -15,6 +15,15 @@ hipError_t launch_layernorm(int dtype, const float* x, int rows, int D, const fl
     return hipGetLastError();
 }
 
+hipError_t launch_activation(int dtype, void* h, int64_t rows, int cols, int gated, hipStream_t s) {
+    if (rows <= 0 || cols % 16) return rows <= 0 ? hipSuccess : hipErrorInvalidValue;
+    const int64_t n = rows * ((gated ? cols / 2 : cols) / 8);
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    if (dtype) hipLaunchKernelGGL(activation_kernel<bf16>, dim3(nb), dim3(256), 0, s, (bf16*)h, rows, cols, gated);
+    else hipLaunchKernelGGL(activation_kernel<float>, dim3(nb), dim3(256), 0, s, (float*)h, rows, cols, gated);
+    return hipGetLastError();
+}
+
 hipError_t launch_im2col(int dtype, const float* img, int B, int H, int W, int kpad, void* cols,
                          const float* special, int nspecial, int ntok, int D, float* x, void* xb, float* stats,
                          const float* level, hipStream_t s) {
