@@ -23,6 +23,7 @@ struct GemmArgs {
     const void* W;       // T [N rounded up to 256][K]
     const float* bias;   // [N] in the physical column order of W, may be null
     int M, N, K;         // K multiple of 64 (bf16) / 32 (fp32)
+    int m_begin;         // a launch covers rows m_begin .. M - 1 (row indices stay those of the whole problem)
     // PLAIN: logical row r reads A row (r / a_rpi) * a_istride + a_off + r % a_rpi
     // CONV3: pixel (b, y, x) is A row b * a_istride + a_off + y * cW + x
     int a_rpi, a_istride, a_off;
@@ -544,8 +545,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_kernel(const GemmArgs 
     const int lrow = tid >> 3, lchunk = tid & 7;
 
     int tm, tn;
-    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M - p.m_begin + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = p.m_begin + tm * BM, n0 = tn * BN;
 
 
     const T* __restrict__ A = reinterpret_cast<const T*>(p.A);
@@ -717,8 +718,8 @@ __global__ __launch_bounds__(64 * KG * WGM * WGN, KG * WGM * WGN / 4) void gemm_
     const int lrow = gt >> 3, lchunk = gt & 7;
 
     int tm, tn;
-    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M - p.m_begin + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = p.m_begin + tm * BM, n0 = tn * BN;
 
     const T* __restrict__ A = reinterpret_cast<const T*>(p.A);
     const T* __restrict__ W = reinterpret_cast<const T*>(p.W);
@@ -874,7 +875,7 @@ static inline hipError_t launch_tile_splitk(const GemmArgs& a, int amode, hipStr
         configured = true;
     }
     if (configure_only) return hipSuccess;
-    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN);
+    const int tiles = cdiv(a.M - a.m_begin, BM) * cdiv(a.N, BN);
     dim3 grid(tiles, a.nz > 1 ? a.nz : 1), block(64 * KG * WGM * WGN);
     if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_PLAIN, KG>), grid, block, lds, s, a);
     else hipLaunchKernelGGL((gemm_splitk_kernel<T, BM, BN, WGM, WGN, A_CONV3, KG>), grid, block, lds, s, a);
@@ -883,7 +884,7 @@ static inline hipError_t launch_tile_splitk(const GemmArgs& a, int amode, hipStr
 
 template <typename T, int BM, int BN, int WGM, int WGN>
 static inline hipError_t launch_tile(const GemmArgs& a, int amode, hipStream_t s) {
-    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN);
+    const int tiles = cdiv(a.M - a.m_begin, BM) * cdiv(a.N, BN);
     dim3 grid(tiles, a.nz > 1 ? a.nz : 1), block(64 * WGM * WGN);
     if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, A_PLAIN>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((gemm_kernel<T, BM, BN, WGM, WGN, A_CONV3>), grid, block, 0, s, a);

@@ -20,9 +20,10 @@ namespace {
 // model's pick is the measured best on 23 of them, within 8 % on four and 15 % on one (0.4 % in total time).
 // Tuning aids, read from the environment when an engine is created (configure_gemm_bf16), never per launch:
 // VPE_GEMM_TILE forces a tiling, VPE_NO_SMALL_DMA leaves the two small direct-to-LDS shapes out, VPE_NO_SPLITK
-// the split-k kernel, VPE_NO_STRIP the strip convolution.
+// the split-k kernel, VPE_NO_STRIP the strip convolution, VPE_NO_ROW_SPLIT the two-launch form of a GEMM whose tile
+// count is just above a whole number of rounds.
 int g_forced_tile = 0;
-bool g_no_small = false, g_no_splitk = false, g_no_strip = false;
+bool g_no_small = false, g_no_splitk = false, g_no_strip = false, g_no_split = false;
 struct Cand { int kind, bm, bn, held; float alpha, beta; bool dma; };
 constexpr Cand kCands[] = {
     {128, 256, 128, 2, 5.16f, 1.055f, true},    // direct-to-LDS, 8 waves, 64 x 64 wave tiles
@@ -36,20 +37,17 @@ constexpr Cand kCands[] = {
 };
 }  // namespace
 
-hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
-    const int forced = g_forced_tile;
-    // the direct-to-LDS loader keeps byte offsets in 32-bit ints
-    const int64_t a_rows = amode == A_PLAIN ? (int64_t)(a.M / a.a_rpi + 1) * (a.a_istride > a.a_rpi ? a.a_istride : a.a_rpi)
-                                            : (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride;
-    const bool fits = a_rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
+// The model's pick for rows m_begin .. M - 1 of `a` and its predicted time in us.
+static int pick_tile(const GemmArgs& a, bool fits, float& best_cost) {
     int best = 3;
-    float best_cost = 0.0f;
+    best_cost = 0.0f;
     const bool no_small = g_no_small;
+    const int rows = a.M - a.m_begin;
     for (const Cand& c : kCands) {
         if (c.dma && !fits) continue;
         if (no_small && (c.kind == 64 || c.kind == 65)) continue;
         if (c.bn == 64 && a.epi == EPI_SWIGLU) continue;        // needs 64-column wave tiles
-        const int64_t tiles = (int64_t)cdiv(a.M, c.bm) * cdiv(a.N, c.bn) * (a.nz > 1 ? a.nz : 1);
+        const int64_t tiles = (int64_t)cdiv(rows, c.bm) * cdiv(a.N, c.bn) * (a.nz > 1 ? a.nz : 1);
         // Inside the engine (not in the calibration harness) the small direct-to-LDS shapes lose to their
         // register-staged counterparts when there is less than one tile per CU (ViT-S proj / fc2 with 144 tiles:
         // 12.7 against 11.7 us; 3x3 convolutions on the 34x45 and 68x90 grids: 24.0 against 20.7, 27.8 against
@@ -60,6 +58,60 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
         const float cost = c.alpha * (r > 1.0f ? r : 1.0f) + c.beta * r * (1e-6f * c.bm * c.bn * a.K);
         if (best_cost == 0.0f || cost < best_cost) { best_cost = cost; best = c.kind; }
     }
+    return best;
+}
+
+static hipError_t launch_picked(const GemmArgs& a, int amode, hipStream_t s, int best, bool fits);
+
+hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
+    // the direct-to-LDS loader keeps byte offsets in 32-bit ints
+    const int64_t a_rows = amode == A_PLAIN ? (int64_t)(a.M / a.a_rpi + 1) * (a.a_istride > a.a_rpi ? a.a_istride : a.a_rpi)
+                                            : (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride;
+    const bool fits = a_rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
+    float whole_cost;
+    const int whole = pick_tile(a, fits, whole_cost);
+    // The one-per-CU tiles run in lockstep rounds of 256 and pay for a partly filled last round in full (ViT-g, 8
+    // views: fc2 and the out-projection have 43 x 6 = 258 tiles of 256 x 256, QKV 774).  Two launches instead: whole
+    // rounds of the large tile over the leading rows, then the remaining rows with whatever the model picks for them.
+    if (g_forced_tile == 0 && !g_no_split && fits && a.nz <= 1 && a.m_begin == 0) {
+        float split_cost = whole_cost;
+        int split_kind = 0, split_rows = 0;
+        for (const Cand& c : kCands) {
+            if (!c.dma || c.held != 1) continue;
+            const int tn = cdiv(a.N, c.bn), tm = cdiv(a.M, c.bm);
+            const int64_t tiles = (int64_t)tm * tn;
+            const int rounds = (int)(tiles / 256);
+            if (rounds < 1 || tiles % 256 == 0) continue;
+            const int tm_main = rounds * 256 / tn;              // whole tile rows in `rounds` rounds
+            if (tm_main < 1 || tm_main >= tm) continue;
+            const float main_rounds = (float)cdiv((int64_t)tm_main * tn, 256);
+            const float main_cost = (c.alpha + c.beta * (1e-6f * c.bm * c.bn * a.K)) * main_rounds;
+            GemmArgs tail = a;
+            tail.m_begin = tm_main * c.bm;
+            float tail_cost;
+            pick_tile(tail, fits, tail_cost);
+            if (main_cost + tail_cost < 0.93f * split_cost) {   // a second launch costs a few us the model does not see
+                split_cost = main_cost + tail_cost;
+                split_kind = c.kind;
+                split_rows = tm_main * c.bm;
+            }
+        }
+        if (split_kind) {
+            GemmArgs main = a, tail = a;
+            main.M = split_rows;
+            tail.m_begin = split_rows;
+            hipError_t rc = launch_gemm_dma_bf16(split_kind, main, amode, s);
+            if (rc != hipSuccess) return rc;
+            float unused;
+            return launch_picked(tail, amode, s, pick_tile(tail, fits, unused), fits);
+        }
+    }
+    return launch_picked(a, amode, s, whole, fits);
+}
+
+static hipError_t launch_picked(const GemmArgs& a, int amode, hipStream_t s, int best, bool fits) {
+    const int forced = g_forced_tile;
+    const int rows = a.M - a.m_begin;
     // A 64 x 64 tiling with at most one tile per CU and at least 4 k-tiles: two wave groups per tile, each over
     // half of the k range (in-engine: ViT-S fc2 14.4 -> 12.5 us, the 3x3 convolution on the 34x45 grid 20.7 -> 17.5,
     // the detection towers 26.9 -> 23.8; ViT-S 476x630 frame latency 1.13 -> 1.08 ms, sequential baseline 396 -> 418
@@ -68,12 +120,12 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int amode, hipStream_t s) {
     // ViT-B proj / fc2 GEMMs (264 tiles), brings that model's frame latency from 1.79 to 1.70 ms but costs 1.5 % of its
     // pipelined rate with three encoder lanes.
     const bool no_splitk = g_no_splitk;
-    if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
+    if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(rows, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
     // 3x3 convolutions: the strip kernel (conv_strip.h) where its 384 x 256 tiles make one well-filled round of the
     // 256 CUs (measured on 272 x 360 x 256 -> 256, 256 tiles: 128 against 144 us for the generic 384 x 256 kernel on the
     // same box; with several rounds -- 4 x 296 x 296: 477 against 443 us -- the generic kernels stay ahead).
     // VPE_GEMM_TILE=9 forces it wherever it applies, any other forced tile switches it off.
-    if (amode == A_CONV3 && (forced == 9 || (forced == 0 && !g_no_strip)) && conv_strip_applies(a) && a.epi != EPI_SWIGLU) {
+    if (a.m_begin == 0 && amode == A_CONV3 && (forced == 9 || (forced == 0 && !g_no_strip)) && conv_strip_applies(a) && a.epi != EPI_SWIGLU) {
         const int64_t t = conv_strip_tiles(a);
         if (forced == 9 || (t > 192 && t <= 256)) return launch_conv_strip_bf16(a, s);
     }
@@ -97,6 +149,7 @@ hipError_t configure_gemm_bf16() {
     g_no_small = getenv("VPE_NO_SMALL_DMA") != nullptr;
     g_no_splitk = getenv("VPE_NO_SPLITK") != nullptr;
     g_no_strip = getenv("VPE_NO_STRIP") != nullptr;
+    g_no_split = getenv("VPE_NO_ROW_SPLIT") != nullptr;
     GemmArgs a{};
     return launch_tile_splitk<bf16, 64, 64, 2, 2, 2>(a, A_PLAIN, nullptr, true);
 }

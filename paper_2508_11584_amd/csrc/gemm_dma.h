@@ -194,8 +194,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
     const int g = lane >> 5, li = lane & 31;
 
     int tm, tn;
-    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    tile_coords(xcd_contiguous(blockIdx.x, gridDim.x), (p.M - p.m_begin + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+    const int m0 = p.m_begin + tm * BM, n0 = tn * BN;
 
     // folded LayerNorm: (mean, rstd) of this tile's rows live behind the stage / staging buffers
     constexpr int EPI_BYTES = NW * 32 * WN * 4;
@@ -393,7 +393,7 @@ static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream
         configured = true;
     }
     if (configure_only) return hipSuccess;
-    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
+    const int tiles = cdiv(a.M - a.m_begin, BM) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
     if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
     else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
     return hipGetLastError();
