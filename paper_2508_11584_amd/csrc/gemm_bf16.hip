@@ -118,7 +118,8 @@ static hipError_t launch_picked(const GemmArgs& a, int amode, hipStream_t s, int
     // frames/s, pipelined rate +0.5 %; with the threshold at 16 k-tiles 1.10 ms / 408 / +0 %).
     // VPE_NO_SPLITK in the environment switches it off (a tuning aid).  A limit of 288 tiles, which takes in the
     // ViT-B proj / fc2 GEMMs (264 tiles), brings that model's frame latency from 1.79 to 1.70 ms but costs 1.5 % of its
-    // pipelined rate with three encoder lanes.
+    // pipelined rate with three encoder lanes.  Four wave groups for the heads' long k loops on few tiles (3x3 convolutions
+    // on the patch grid, 36 and 54 k-tiles on 96 and 192 tiles): frame latency 1.084 -> 1.081 ms, pipelined rate -1 %.
     const bool no_splitk = g_no_splitk;
     if (!no_splitk && best == 3 && a.K >= 256 && (int64_t)cdiv(rows, 64) * cdiv(a.N, 64) * (a.nz > 1 ? a.nz : 1) <= 256) best = 4;
     // 3x3 convolutions: the strip kernel (conv_strip.h) where its 384 x 256 tiles make one well-filled round of the
