@@ -40,7 +40,19 @@ constexpr int STRIP_MAX_SLOTS = 7;        // strip load instructions per wave an
 // this range: the leading pad row and whatever follows the last pixel are nobody's output).
 static inline int64_t strip_positions(int images, int H, int W) { return ((int64_t)(images - 1) * (H + 1) + H) * (W + 1) - 1; }
 
-template <int BM, int BN, int WGM, int WGN, int OCC>
+// Sum of a value over the two halves of a wave (lane l and lane l ^ 32), in both.
+__device__ __forceinline__ float strip_halves_sum(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// ROWDOT = true: the instantiation for EPI_ROWDOT alone.  Its MFMAs take the weights as the first operand, so a
+// lane's accumulators are one pixel's channels (pixel = lane % 32, channel 8 (v / 4) + 4 (lane / 32) + v % 4 of the
+// 32-channel block) and the projection over channels is a sum inside the lane plus one exchange between the lane
+// halves: the 384 x 256 accumulators never go through LDS (staging them there and reading them back, at the LDS's
+// 128 bytes per clock with eight waves at once, took 9 of the kernel's 121 us).
+template <int BM, int BN, int WGM, int WGN, int OCC, bool ROWDOT>
 __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_strip_kernel(const GemmArgs args, int sp_rows, int tiles_m) {
     const GemmArgs p = select_problem(args);
     constexpr int NW = WGM * WGN;
@@ -69,42 +81,54 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
 
     // --- loader.  Strip instruction `slot` (32 positions): lane l fetches one half of the 32-byte chunk of strip
     // position 32 slot + l / 2, i.e. of padded position m0 - (W + 1) - 1 + that: a pixel's channels, or zeros for a pad
-    // and for positions outside the tensor.  The address is formed per instruction (two dozen integer operations,
-    // seven times per chunk) rather than kept in seven registers.
+    // and for positions outside the tensor.  Where a lane reads from does not depend on the chunk, so the byte offset of
+    // its pixel (chunk 0) from A, or -1 for the page of zeros, is worked out once per instruction slot (two divisions by
+    // reciprocal, about 45 instructions with eight slow multiplies) and kept in LDS, one word per lane and slot, read
+    // back one MFMA group ahead of the load: done between the MFMAs of every chunk, that arithmetic alone cost 480 of
+    // a step's 3750 clocks, and there are no seven registers to keep the offsets in.
     const int nslots = sp_rows / 32;
-    const int qbase = m0 - Wp - 1 + (lane >> 1);          // lane l: row l / 2 of the instruction's 32, physical half l % 2
-    const int lhalf = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;   // ... which holds this logical half (rows 8..15, 24..31 exchanged)
-    const float inv_wp = 1.0f / (float)Wp, inv_hp = 1.0f / (float)Hp;
-    auto strip_src = [&](int slot, int c) -> const char* {
-        const int q = qbase + 32 * slot;
-        const int qq = q < 0 ? 0 : q;
-        int line = (int)((float)qq * inv_wp);            // qq / Wp, put right below (the product may be off by one)
-        line += (line + 1) * Wp <= qq;
-        line -= line * Wp > qq;
-        const int x = qq - line * Wp;
-        int img = (int)((float)line * inv_hp);
-        img += (img + 1) * Hp <= line;
-        img -= img * Hp > line;
-        const int y = line - img * Hp - 1;
-        const bool pixel = q >= 0 && x < p.cW && y >= 0 && img < images;
-        const int64_t row = (int64_t)img * p.a_istride + p.a_off + y * p.cW + x;
-        const char* src = A + (row * p.lda + c * STRIP_KC) * 2 + lhalf;
-        return pixel ? src : zpage;
-    };
+    int* const s_tab = reinterpret_cast<int*>(s_w + 3 * WSTAGE) + lane;        // [nslots][64]
+    {
+        const int qbase = m0 - Wp - 1 + (lane >> 1);          // lane l: row l / 2 of the instruction's 32, physical half l % 2
+        const int lhalf = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;   // ... which holds this logical half (rows 8..15, 24..31 exchanged)
+        const float inv_wp = 1.0f / (float)Wp, inv_hp = 1.0f / (float)Hp;
+        for (int slot = wave; slot < nslots; slot += NW) {
+            const int q = qbase + 32 * slot;
+            const int qq = q < 0 ? 0 : q;
+            int line = (int)((float)qq * inv_wp);            // qq / Wp, put right below (the product may be off by one)
+            line += (line + 1) * Wp <= qq;
+            line -= line * Wp > qq;
+            const int x = qq - line * Wp;
+            int img = (int)((float)line * inv_hp);
+            img += (img + 1) * Hp <= line;
+            img -= img * Hp > line;
+            const int y = line - img * Hp - 1;
+            const bool pixel = q >= 0 && x < p.cW && y >= 0 && img < images;
+            const int64_t row = (int64_t)img * p.a_istride + p.a_off + y * p.cW + x;
+            s_tab[slot * 64] = pixel ? (int)(row * p.lda * 2 + lhalf) : -1;
+        }
+    }
     // weight rows: lane l fetches row n0 + 32 wave + l / 2, the same exchange of halves
-    const int woff = (int)(((int64_t)(n0 + 32 * wave + (lane >> 1)) * p.K) * 2 + lhalf);
+    const int woff = (int)(((int64_t)(n0 + 32 * wave + (lane >> 1)) * p.K) * 2 + (((lane & 1) ^ ((lane >> 4) & 1)) * 16));
 
-    // this wave's i-th strip instruction (i < STRIP_MAX_SLOTS) of chunk c, into strip stage c & 1
-    auto dma_strip1 = [&](int c, int i) {
+    // the table entry of this wave's i-th strip instruction (i < STRIP_MAX_SLOTS); only the wave itself reads its entries
+    auto strip_off = [&](int i) -> int {
         const int slot = wave + NW * i;
-        if (slot < nslots)
-            __builtin_amdgcn_global_load_lds(VPE_GPTR(strip_src(slot, c)), VPE_LPTR(s_strip + (c & 1) * strip_bytes + slot * 1024), 16, 0, 0);
+        return slot < nslots ? s_tab[slot * 64] : -1;
+    };
+    // this wave's i-th strip instruction of chunk c, into strip stage c & 1, from table entry `off`
+    auto dma_strip1 = [&](int c, int i, int off) {
+        const int slot = wave + NW * i;
+        if (slot < nslots) {
+            const char* src = off >= 0 ? A + off + c * (STRIP_KC * 2) : zpage;
+            __builtin_amdgcn_global_load_lds(VPE_GPTR(src), VPE_LPTR(s_strip + (c & 1) * strip_bytes + slot * 1024), 16, 0, 0);
+        }
     };
     // half `part` (0 / 1) of chunk c's strip: this wave's instructions with i % 2 == part
     auto dma_strip = [&](int c, int part) {
 #pragma unroll
         for (int i = 0; i < STRIP_MAX_SLOTS; ++i)
-            if ((i & 1) == part) dma_strip1(c, i);
+            if ((i & 1) == part) dma_strip1(c, i, strip_off(i));
     };
     // tap i of row dy = tg - 1 for chunk c into weight stage `stage`
     auto dma_w1 = [&](int stage, int c, int tg, int i) {
@@ -141,6 +165,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
                        bool lw, int lw_stage, int lw_c, int lw_tg, bool ls, int ls_c, int ls_part) {
         const char* sa[3] = {strip + aoff(arow + tg * Wp), strip + aoff(arow + tg * Wp + 1), strip + aoff(arow + tg * Wp + 2)};
         const char* sb = wts + bbase;
+        int soff = -1;
         const char* na = nstrip + aoff(arow + ntg * Wp);
         const char* nb = nwts + bbase;
 #pragma unroll
@@ -154,11 +179,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
                 else if (more) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(na);
                 const int k = i * MI + mi;                // group 0..8: weights in groups 0..2, strip instructions in 3..6
                 if (k < 3) { if (lw) dma_w1(lw_stage, lw_c, lw_tg, k); }
-                else if (k - 3 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) dma_strip1(ls_c, 2 * (k - 3) + ls_part); }
+                else if (k - 3 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) dma_strip1(ls_c, 2 * (k - 3) + ls_part, soff); }
+                if (k >= 2 && k - 2 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) soff = strip_off(2 * (k - 2) + ls_part); }   // for the next group
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int nj = 0; nj < NI; ++nj) {
-                    acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur], fb[nj], acc[mi][nj], 0, 0, 0);
+                    acc[mi][nj] = ROWDOT ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[nj], fa[cur], acc[mi][nj], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur], fb[nj], acc[mi][nj], 0, 0, 0);
                     if (mi == MI - 1 && i < 2) fb[nj] = *reinterpret_cast<const bf16x8*>(sb + (i + 1) * WTAP + nj * 1024);
                     if (last && more) fb[nj] = *reinterpret_cast<const bf16x8*>(nb + nj * 1024);
                 }
@@ -196,7 +223,46 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     }
     __syncthreads();                                     // the staging blocks of the epilogue overlay the operand buffers
 
-    wave_tile_epilogue<MI, NI, WM, WN, true>(p, acc, smem, nullptr, wave, wm, wn, lane, m0, n0);
+    if constexpr (ROWDOT) {
+        // bias and projection vector of the tile's BN channels into LDS, read back by broadcast (a lane half reads
+        // four consecutive channels at a time); out[r][c / 64] = sum over the 64 channels of act(acc + bias) * w
+        static_assert(NI % 2 == 0 && 2 * BN <= 64 * WGM * WGN, "whole 64-channel groups per wave; one value per thread");
+        float* sbw = reinterpret_cast<float*>(smem);
+        if (tid < BN) sbw[tid] = p.bias[n0 + tid];
+        else if (tid < 2 * BN) sbw[tid] = p.gamma[n0 + tid - BN];
+        __syncthreads();
+        float* out = reinterpret_cast<float*>(p.out);
+        EpilogueRows<true> rows(p, m0 + wm * WM + li);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int r = rows.row(p);
+            rows.advance(32);
+            float sum[NI / 2];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                float sj = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int ch = wn * WN + j * 32 + 8 * q + 4 * g;
+                    const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbw + ch), w4 = *reinterpret_cast<const f32x4*>(sbw + BN + ch);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float a = acc[i][j][4 * q + e] + b4[e];
+                        if (p.act == ACT_RELU) a = fmaxf(a, 0.0f);
+                        sj += a * w4[e];
+                    }
+                }
+                if (j & 1) sum[j >> 1] += sj; else sum[j >> 1] = sj;
+            }
+#pragma unroll
+            for (int k = 0; k < NI / 2; ++k) {
+                const float tot = strip_halves_sum(sum[k]);
+                if (g == (k & 1) && r < p.M) out[(int64_t)r * p.ldo + ((n0 + wn * WN) >> 6) + k] = tot;
+            }
+        }
+    } else {
+        wave_tile_epilogue<MI, NI, WM, WN, true>(p, acc, smem, nullptr, wave, wm, wn, lane, m0, n0);
+    }
 }
 
 // Strip rows (positions) a tile needs, rounded up to whole load instructions.
@@ -210,32 +276,32 @@ static inline bool conv_strip_fits(const GemmArgs& a) {
     if (a.cC % STRIP_KC || a.N % BN || a.K != 9 * a.cC || a.ln_stats || !a.zeros) return false;
     if (a.cH < 1 || a.cW < 1 || a.M % (a.cH * a.cW)) return false;
     const int sp = strip_rows<BM>(a.cW);
-    if (sp > 8 * STRIP_MAX_SLOTS * 32 || 2 * sp * 32 + 3 * 3 * BN * 32 > 160 * 1024) return false;
+    if (sp > 8 * STRIP_MAX_SLOTS * 32 || 2 * sp * 32 + 3 * 3 * BN * 32 + sp * 8 > 160 * 1024) return false;   // strips, weights, offset table
     if (strip_positions(a.M / (a.cH * a.cW), a.cH, a.cW) + BM >= (int64_t(1) << 31)) return false;
     const int64_t rows = (int64_t)(a.M / (a.cH * a.cW) + 1) * a.a_istride + a.a_off;
     return rows * a.lda * 2 < (int64_t(1) << 31) && (int64_t)(a.N + 256) * a.K * 2 < (int64_t(1) << 31);
 }
 
-template <int BM, int BN, int WGM, int WGN, int OCC>
+template <int BM, int BN, int WGM, int WGN, int OCC, bool ROWDOT>
 static inline hipError_t launch_conv_strip(const GemmArgs& a, hipStream_t s, bool configure_only = false) {
     constexpr int epi_b = WGM * WGN * 32 * (BN / WGN) * 4;
     constexpr int max_lds = 160 * 1024 / OCC;
     static bool configured = false;
     if (!configured) {
-        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_strip_kernel<BM, BN, WGM, WGN, OCC>),
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_strip_kernel<BM, BN, WGM, WGN, OCC, ROWDOT>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
         if (rc != hipSuccess) return rc;
         configured = true;
     }
     if (configure_only) return hipSuccess;
-    if (!conv_strip_fits<BM, BN>(a)) return hipErrorInvalidValue;
+    if (!conv_strip_fits<BM, BN>(a) || ROWDOT != (a.epi == EPI_ROWDOT)) return hipErrorInvalidValue;
     const int sp = strip_rows<BM>(a.cW);
-    const int ops_b = 2 * sp * 32 + 3 * 3 * BN * 32;
+    const int ops_b = 2 * sp * 32 + 3 * 3 * BN * 32 + sp * 8;
     const int lds = ops_b > epi_b ? ops_b : epi_b;
     if (lds > max_lds) return hipErrorInvalidValue;
     const int tiles_m = (int)((strip_positions(a.M / (a.cH * a.cW), a.cH, a.cW) + BM - 1) / BM);
     const int tiles = tiles_m * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
-    hipLaunchKernelGGL((conv_strip_kernel<BM, BN, WGM, WGN, OCC>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a, sp, tiles_m);
+    hipLaunchKernelGGL((conv_strip_kernel<BM, BN, WGM, WGN, OCC, ROWDOT>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a, sp, tiles_m);
     return hipGetLastError();
 }
 

@@ -42,6 +42,35 @@ __device__ __forceinline__ int epilogue_row(const GemmArgs& p, int r) {
     return (x < p.cW && y >= 0) ? (img * p.cH + y) * p.cW + x : 0x7fffffff;
 }
 
+// The same map for tile rows visited in increasing order with a fixed step: one pair of divisions at the start, then
+// additions and compares (a ROWDOT lane visits every 64 / CG-th row of its wave tile).
+template <bool PADDED>
+struct EpilogueRows {
+    int r, x, y, img, wp, hp;          // tile row; PADDED: its column, line within the image's H + 1 lines, image
+    __device__ __forceinline__ EpilogueRows(const GemmArgs& p, int r0) : r(r0), x(0), y(0), img(0), wp(p.cW + 1), hp(p.cH + 1) {
+        if (PADDED) {
+            const int line = r0 / wp;
+            x = r0 - line * wp;
+            img = line / hp;
+            y = line - img * hp;
+        }
+    }
+    __device__ __forceinline__ int row(const GemmArgs& p) const {
+        if (!PADDED) return r;
+        return (x < p.cW && y >= 1) ? (img * p.cH + y - 1) * p.cW + x : 0x7fffffff;
+    }
+    __device__ __forceinline__ void advance(int step) {
+        r += step;
+        if (PADDED) {
+            x += step;
+            while (x >= wp) {
+                x -= wp;
+                if (++y == hp) { y = 0; ++img; }
+            }
+        }
+    }
+};
+
 template <int MI, int NI, int WM, int WN, bool PADDED = false>
 __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&acc)[MI][NI], char* smem, const float* lnrow,
                                                    int wave, int wm, int wn, int lane, int m0, int n0) {
@@ -49,6 +78,18 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
     const int g = lane >> 5, li = lane & 31;
     float* sC = reinterpret_cast<float*>(smem) + wave * (32 * WN);
     const int wrow0 = m0 + wm * WM, wcol0 = n0 + wn * WN;
+    // ROWDOT: a lane keeps one 8-column chunk (lane % CG) for all its rows -- its bias and projection values are
+    // loaded once -- and visits rows lane / CG, + 64 / CG, ... of the wave tile in order, across the passes
+    constexpr int RD_CG = WN / 8;
+    f32x4 rd_b0 = {0, 0, 0, 0}, rd_b1 = rd_b0, rd_w0 = rd_b0, rd_w1 = rd_b0;
+    EpilogueRows<PADDED> rd_rows(p, wrow0 + lane / RD_CG);
+    const int rd_c = wcol0 + (lane % RD_CG) * 8;
+    if (p.epi == EPI_ROWDOT && rd_c < p.N) {
+        rd_b0 = *reinterpret_cast<const f32x4*>(p.bias + rd_c);
+        rd_b1 = *reinterpret_cast<const f32x4*>(p.bias + rd_c + 4);
+        rd_w0 = *reinterpret_cast<const f32x4*>(p.gamma + rd_c);
+        rd_w1 = *reinterpret_cast<const f32x4*>(p.gamma + rd_c + 4);
+    }
     // one pass per 32-row block of the wave tile; the block index is a compile-time constant of each pass (a
     // loop that the optimizer declines to unroll would turn the accumulators into an indexed array in scratch)
     auto pass = [&](auto I) {
@@ -128,23 +169,27 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
         } else if (p.epi == EPI_ROWDOT) {
             // 8 consecutive lanes hold the 8 chunks of one 64-column projection group of a row
             if constexpr (WN % 64 == 0) {
-                constexpr int CG = WN / 8;
+                constexpr int CG = RD_CG;
+                static_assert(64 % CG == 0, "a lane keeps its column chunk");
                 float* out = reinterpret_cast<float*>(p.out);
 #pragma unroll
-                for (int it = lane; it < 32 * CG; it += 64) {
-                    const int rr = it / CG, cg = it % CG;
-                    const int r = epilogue_row<PADDED>(p, rblk + rr), c = wcol0 + cg * 8;
+                for (int n = 0; n < 32 * CG / 64; ++n) {
+                    const int rr = lane / CG + n * (64 / CG);
+                    const int r = rd_rows.row(p);
+                    rd_rows.advance(64 / CG);
+                    const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + (lane % CG) * 8);
+                    const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + (lane % CG) * 8 + 4);
                     float sum = 0.0f;
-                    if (r < p.M && c < p.N) {
-                        const f32x4 lo = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8);
-                        const f32x4 hi = *reinterpret_cast<const f32x4*>(sC + rr * WN + cg * 8 + 4);
-                        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        sum = rowdot_chunk(p, c, v);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float a = lo[e] + rd_b0[e], b = hi[e] + rd_b1[e];
+                        if (p.act == ACT_RELU) { a = fmaxf(a, 0.0f); b = fmaxf(b, 0.0f); }
+                        sum += a * rd_w0[e] + b * rd_w1[e];
                     }
                     sum += __shfl_xor(sum, 1);
                     sum += __shfl_xor(sum, 2);
                     sum += __shfl_xor(sum, 4);
-                    if ((cg & 7) == 0 && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = sum;
+                    if ((lane & 7) == 0 && r < p.M && rd_c < p.N) out[(int64_t)r * p.ldo + (rd_c >> 6)] = sum;
                 }
             }
         } else {

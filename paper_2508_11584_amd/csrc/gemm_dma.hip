@@ -24,12 +24,15 @@ bool conv_strip_applies(const GemmArgs& a) { return conv_strip_fits<384, 256>(a)
 int64_t conv_strip_tiles(const GemmArgs& a) {
     return (strip_positions(a.M / (a.cH * a.cW), a.cH, a.cW) + 383) / 384 * cdiv(a.N, 256) * (a.nz > 1 ? a.nz : 1);
 }
-hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s) { return launch_conv_strip<384, 256, 4, 2, 1>(a, s); }
+hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s) {
+    return a.epi == EPI_ROWDOT ? launch_conv_strip<384, 256, 4, 2, 1, true>(a, s) : launch_conv_strip<384, 256, 4, 2, 1, false>(a, s);
+}
 
 // LDS opt-in (more than 64 KB) where needed; called once at engine creation.
 hipError_t configure_gemm() {
     GemmArgs a{};
-    hipError_t rc = launch_conv_strip<384, 256, 4, 2, 1>(a, nullptr, true);
+    hipError_t rc = launch_conv_strip<384, 256, 4, 2, 1, true>(a, nullptr, true);
+    if (rc == hipSuccess) rc = launch_conv_strip<384, 256, 4, 2, 1, false>(a, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
