@@ -40,18 +40,10 @@ constexpr int STRIP_MAX_SLOTS = 7;        // strip load instructions per wave an
 // this range: the leading pad row and whatever follows the last pixel are nobody's output).
 static inline int64_t strip_positions(int images, int H, int W) { return ((int64_t)(images - 1) * (H + 1) + H) * (W + 1) - 1; }
 
-// Sum of a value over the two halves of a wave (lane l and lane l ^ 32), in both.
-__device__ __forceinline__ float strip_halves_sum(float v) {
-    const uint32_t u = __float_as_uint(v);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
 // ROWDOT = true: the instantiation for EPI_ROWDOT alone.  Its MFMAs take the weights as the first operand, so a
 // lane's accumulators are one pixel's channels (pixel = lane % 32, channel 8 (v / 4) + 4 (lane / 32) + v % 4 of the
 // 32-channel block) and the projection over channels is a sum inside the lane plus one exchange between the lane
-// halves: the 384 x 256 accumulators never go through LDS (staging them there and reading them back, at the LDS's
-// 128 bytes per clock with eight waves at once, took 9 of the kernel's 121 us).
+// halves (rowdot_epilogue_transposed).
 template <int BM, int BN, int WGM, int WGN, int OCC, bool ROWDOT>
 __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_strip_kernel(const GemmArgs args, int sp_rows, int tiles_m) {
     const GemmArgs p = select_problem(args);
@@ -224,42 +216,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     __syncthreads();                                     // the staging blocks of the epilogue overlay the operand buffers
 
     if constexpr (ROWDOT) {
-        // bias and projection vector of the tile's BN channels into LDS, read back by broadcast (a lane half reads
-        // four consecutive channels at a time); out[r][c / 64] = sum over the 64 channels of act(acc + bias) * w
-        static_assert(NI % 2 == 0 && 2 * BN <= 64 * WGM * WGN, "whole 64-channel groups per wave; one value per thread");
-        float* sbw = reinterpret_cast<float*>(smem);
-        if (tid < BN) sbw[tid] = p.bias[n0 + tid];
-        else if (tid < 2 * BN) sbw[tid] = p.gamma[n0 + tid - BN];
-        __syncthreads();
-        float* out = reinterpret_cast<float*>(p.out);
-        EpilogueRows<true> rows(p, m0 + wm * WM + li);
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int r = rows.row(p);
-            rows.advance(32);
-            float sum[NI / 2];
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                float sj = 0.0f;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int ch = wn * WN + j * 32 + 8 * q + 4 * g;
-                    const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbw + ch), w4 = *reinterpret_cast<const f32x4*>(sbw + BN + ch);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float a = acc[i][j][4 * q + e] + b4[e];
-                        if (p.act == ACT_RELU) a = fmaxf(a, 0.0f);
-                        sj += a * w4[e];
-                    }
-                }
-                if (j & 1) sum[j >> 1] += sj; else sum[j >> 1] = sj;
-            }
-#pragma unroll
-            for (int k = 0; k < NI / 2; ++k) {
-                const float tot = strip_halves_sum(sum[k]);
-                if (g == (k & 1) && r < p.M) out[(int64_t)r * p.ldo + ((n0 + wn * WN) >> 6) + k] = tot;
-            }
-        }
+        rowdot_epilogue_transposed<MI, NI, WM, WN, BN, 64 * NW, true>(p, acc, smem, wm, wn, tid, m0, n0);
     } else {
         wave_tile_epilogue<MI, NI, WM, WN, true>(p, acc, smem, nullptr, wave, wm, wn, lane, m0, n0);
     }

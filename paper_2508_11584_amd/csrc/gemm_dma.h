@@ -218,7 +218,64 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
 // OCC workgroups per CU (the launch bound is given in waves per SIMD: OCC * waves / 4).
 // WGM x 2 waves: WGM = 2 gives 128-row wave tiles (256 accumulator registers, one wave per SIMD),
 // WGM = 4 gives 64-row wave tiles and two waves per SIMD, i.e. twice as many waves issuing loads.
-template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE, int BM_ = 256>
+// Sum of a value over the two halves of a wave (lane l and lane l ^ 32), in both.
+__device__ __forceinline__ float wave_halves_sum(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Projection epilogue (EPI_ROWDOT) of a wave tile whose MFMAs took the W operand first: a lane's accumulators are
+// one tile row's columns (row = lane % 32 of a 32-row block, column 8 (v / 4) + 4 (lane / 32) + v % 4 of a 32-column
+// block), so out[r][c / 64] = sum over the 64 columns of act(acc + bias) * w is a sum inside the lane plus one
+// exchange between the lane halves, and the accumulators never go through LDS (staging a 384 x 256 tile there and
+// reading it back, eight waves at once at the LDS's 128 bytes per clock, took 9 of 121 us).  Bias and projection vector
+// of the tile's columns go to LDS first (the operand buffers are free; the caller's barrier is behind their last read)
+// and come back by broadcast reads of four consecutive columns.
+template <int MI, int NI, int WM, int WN, int BN, int THREADS, bool PADDED>
+__device__ __forceinline__ void rowdot_epilogue_transposed(const GemmArgs& p, f32x16 (&acc)[MI][NI], char* smem, int wm, int wn,
+                                                           int tid, int m0, int n0) {
+    static_assert(NI % 2 == 0 && 2 * BN <= THREADS, "whole 64-column groups per wave; one value per thread");
+    const int lane = tid & 63, g = lane >> 5, li = lane & 31;
+    float* sbw = reinterpret_cast<float*>(smem);
+    if (tid < BN) sbw[tid] = n0 + tid < p.N ? p.bias[n0 + tid] : 0.0f;
+    else if (tid < 2 * BN) sbw[tid] = n0 + tid - BN < p.N ? p.gamma[n0 + tid - BN] : 0.0f;
+    __syncthreads();
+    float* out = reinterpret_cast<float*>(p.out);
+    EpilogueRows<PADDED> rows(p, m0 + wm * WM + li);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int r = rows.row(p);
+        rows.advance(32);
+        float sum[NI / 2];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            float sj = 0.0f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ch = wn * WN + j * 32 + 8 * q + 4 * g;
+                const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbw + ch), w4 = *reinterpret_cast<const f32x4*>(sbw + BN + ch);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float a = acc[i][j][4 * q + e] + b4[e];
+                    if (p.act == ACT_RELU) a = fmaxf(a, 0.0f);
+                    sj += a * w4[e];
+                }
+            }
+            if (j & 1) sum[j >> 1] += sj; else sum[j >> 1] = sj;
+            __builtin_amdgcn_sched_barrier(0);       // (keeps the scheduler from lifting every block's reads to the top: no registers for that)
+        }
+#pragma unroll
+        for (int k = 0; k < NI / 2; ++k) {
+            const float tot = wave_halves_sum(sum[k]);
+            const int c = n0 + wn * WN + 64 * k;
+            if (g == (k & 1) && r < p.M && c < p.N) out[(int64_t)r * p.ldo + (c >> 6)] = tot;
+        }
+    }
+}
+
+// RD: the instantiation for EPI_ROWDOT alone (MFMAs with the W operand first, projection epilogue without LDS staging).
+template <int BN, int BK, int S, int WGM, int WGN, int OCC, int AMODE, int BM_ = 256, bool RD = false>
 __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_kernel(const GemmArgs args) {
     const GemmArgs p = select_problem(args);
     typedef bf16 T;
@@ -347,7 +404,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = RD ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0)
+                                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
                 // Issue order for the scheduler: the LDS reads of step ks + 1 are spread between the MFMAs
                 // of step ks (one read per two MFMAs), so the only wave on this SIMD never waits on LDS
                 // with an empty matrix pipe.  0x100 = DS read, 0x008 = MFMA.
@@ -379,7 +437,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = RD ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0)
+                                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
             }
@@ -419,28 +478,33 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void gemm_dma_
         return;
     }
 
-    wave_tile_epilogue<MI, NI, WM, WN>(p, acc, smem, lnrow, wave, wm, wn, lane, m0, n0);
+    if constexpr (RD) rowdot_epilogue_transposed<MI, NI, WM, WN, BN, 64 * NW, false>(p, acc, smem, wm, wn, tid, m0, n0);
+    else wave_tile_epilogue<MI, NI, WM, WN>(p, acc, smem, lnrow, wave, wm, wn, lane, m0, n0);
 }
 
-template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1, int BM = 256>
+template <int BN, int BK, int S, int WGM = 2, int WGN = 2, int OCC = 1, int BM = 256, bool RD = false>
 static inline hipError_t launch_gemm_dma(const GemmArgs& a, int amode, hipStream_t s, bool configure_only = false) {
     constexpr int stage_b = S * (BM + BN) * BK * 2, epi_b = WGM * WGN * 32 * (BN / WGN) * 4;
     constexpr int lds = (stage_b > epi_b ? stage_b : epi_b) + BM * 8;     // + (mean, rstd) of the tile's rows
     static_assert(lds * OCC <= 160 * 1024, "LDS budget of one CU");
     static bool configured = false;
     if (!configured) {
-        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t rc = hipSuccess;
+        if (!RD) rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM, false>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc == hipSuccess)
-            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM>),
+            rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM, RD>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (rc != hipSuccess) return rc;
         configured = true;
     }
     if (configure_only) return hipSuccess;
+    // the projection-only instantiation exists for convolutions (the only users of that epilogue on these tiles)
+    if (RD && (amode != A_CONV3 || a.epi != EPI_ROWDOT || a.ln_stats)) return hipErrorInvalidValue;
     const int tiles = cdiv(a.M - a.m_begin, BM) * cdiv(a.N, BN), nz = a.nz > 1 ? a.nz : 1;
-    if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
-    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
+    if (RD) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM, RD>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
+    else if (amode == A_PLAIN) hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_PLAIN, BM, false>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
+    else hipLaunchKernelGGL((gemm_dma_kernel<BN, BK, S, WGM, WGN, OCC, A_CONV3, BM, false>), dim3(tiles, nz), dim3(64 * WGM * WGN), lds, s, a);
     return hipGetLastError();
 }
 

@@ -15,8 +15,9 @@ namespace vpe {
 hipError_t launch_gemm_dma_bf16(int kind, const GemmArgs& a, int amode, hipStream_t s) {
     if (kind == 64) return launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, amode, s);
     if (kind == 65) return launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, amode, s);
-    if (kind == 384) return launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, amode, s);
-    if (kind == 256) return launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, amode, s);
+    const bool rd = amode == A_CONV3 && a.epi == EPI_ROWDOT && !a.ln_stats;   // projection epilogue from transposed accumulators
+    if (kind == 384) return rd ? launch_gemm_dma<256, 32, 2, 4, 2, 1, 384, true>(a, amode, s) : launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, amode, s);
+    if (kind == 256) return rd ? launch_gemm_dma<256, 64, 2, 4, 2, 1, 256, true>(a, amode, s) : launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, amode, s);
     return launch_gemm_dma<128, 32, 2, 4, 2, 2>(a, amode, s);
 }
 // 3x3 convolution from an input strip in LDS (conv_strip.h): 384 x 256 tiles, 96 x 128 wave tiles.
@@ -34,6 +35,8 @@ hipError_t configure_gemm() {
     hipError_t rc = launch_conv_strip<384, 256, 4, 2, 1, true>(a, nullptr, true);
     if (rc == hipSuccess) rc = launch_conv_strip<384, 256, 4, 2, 1, false>(a, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<256, 32, 2, 4, 2, 1, 384>(a, A_PLAIN, nullptr, true);
+    if (rc == hipSuccess) rc = launch_gemm_dma<256, 32, 2, 4, 2, 1, 384, true>(a, A_CONV3, nullptr, true);
+    if (rc == hipSuccess) rc = launch_gemm_dma<256, 64, 2, 4, 2, 1, 256, true>(a, A_CONV3, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<64, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<128, 64, 2, 2, 2, 2, 64>(a, A_PLAIN, nullptr, true);
     if (rc == hipSuccess) rc = launch_gemm_dma<256, 64, 2, 4, 2, 1>(a, A_PLAIN, nullptr, true);
