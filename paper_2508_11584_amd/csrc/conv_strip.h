@@ -48,7 +48,8 @@ template <int BM, int BN, int WGM, int WGN, int OCC, bool ROWDOT>
 __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_strip_kernel(const GemmArgs args, int sp_rows, int tiles_m) {
     const GemmArgs p = select_problem(args);
     constexpr int NW = WGM * WGN;
-    static_assert(NW == 8 && BN == 32 * NW, "loader mapping: eight waves, each loads 32 weight rows per tap");
+    static_assert(NW == 8 && BN % 32 == 0, "loader mapping: eight waves; a weight load instruction takes 32 rows of a tap");
+    constexpr int RB = BN / 32, WQ = 3 * RB, WPW = (WQ + NW - 1) / NW;   // row blocks per tap, weight instructions per step / per wave
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     constexpr int WTAP = BN * 32, WSTAGE = 3 * WTAP;     // bytes of one tap's weight tile / of one step's three
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -100,8 +101,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
             s_tab[slot * 64] = pixel ? (int)(row * p.lda * 2 + lhalf) : -1;
         }
     }
-    // weight rows: lane l fetches row n0 + 32 wave + l / 2, the same exchange of halves
-    const int woff = (int)(((int64_t)(n0 + 32 * wave + (lane >> 1)) * p.K) * 2 + (((lane & 1) ^ ((lane >> 4) & 1)) * 16));
+    // weight rows: instruction q of a step (tap q / RB, row block q % RB) is issued by wave q % 8; lane l fetches row
+    // n0 + 32 (q % RB) + l / 2, the same exchange of halves
+    const int woff = (int)(((int64_t)(n0 + (lane >> 1)) * p.K) * 2 + (((lane & 1) ^ ((lane >> 4) & 1)) * 16));
 
     // the table entry of this wave's i-th strip instruction (i < STRIP_MAX_SLOTS); only the wave itself reads its entries
     auto strip_off = [&](int i) -> int {
@@ -122,14 +124,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
         for (int i = 0; i < STRIP_MAX_SLOTS; ++i)
             if ((i & 1) == part) dma_strip1(c, i, strip_off(i));
     };
-    // tap i of row dy = tg - 1 for chunk c into weight stage `stage`
-    auto dma_w1 = [&](int stage, int c, int tg, int i) {
-        __builtin_amdgcn_global_load_lds(VPE_GPTR(Wt + woff + (((tg * 3 + i) * C) + c * STRIP_KC) * 2),
-                                         VPE_LPTR(s_w + stage * WSTAGE + wave * 1024 + i * WTAP), 16, 0, 0);
+    // this wave's j-th weight instruction (j < WPW) of tap row dy = tg - 1 for chunk c into weight stage `stage`
+    auto dma_w1 = [&](int stage, int c, int tg, int j) {
+        const int q = wave + NW * j;
+        if (q < WQ) {
+            const int tap = q / RB, rb = q % RB;
+            __builtin_amdgcn_global_load_lds(VPE_GPTR(Wt + woff + (int)((int64_t)rb * 32 * p.K * 2) + (((tg * 3 + tap) * C) + c * STRIP_KC) * 2),
+                                             VPE_LPTR(s_w + stage * WSTAGE + tap * WTAP + rb * 1024), 16, 0, 0);
+        }
     };
     auto dma_w = [&](int stage, int c, int tg) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) dma_w1(stage, c, tg, i);
+        for (int j = 0; j < WPW; ++j) dma_w1(stage, c, tg, j);
     };
 
     f32x16 acc[MI][NI];
@@ -148,6 +154,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     // THREE stages, so the operands of step s + 1 are complete and visible a whole step early and the last group of
     // step s reads the first fragments of step s + 1: the MFMA stream runs through the step boundary and its barrier.
     const int arow = wm * WM + li, bbase = (wn * WN + li) * 32 + ((g ^ ((li >> 3) & 1)) << 4);
+    static_assert(WPW <= 3, "weight loads go with the first groups of a step");
     auto aoff = [&](int row) { return (row << 5) + ((g ^ ((row >> 3) & 1)) << 4); };   // LDS offset of this lane's half of strip row `row`
     bf16x8 fb[NI], fa[2];
     // The step's loads (next-but-one step's weights: lw_* ; half of the next chunk's strip: ls_*) are issued one
@@ -170,8 +177,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
                 else if (i < 2) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(sa[i + 1]);
                 else if (more) fa[cur ^ 1] = *reinterpret_cast<const bf16x8*>(na);
                 const int k = i * MI + mi;                // group 0..8: weights in groups 0..2, strip instructions in 3..6
-                if (k < 3) { if (lw) dma_w1(lw_stage, lw_c, lw_tg, k); }
-                else if (k - 3 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) dma_strip1(ls_c, 2 * (k - 3) + ls_part, soff); }
+                if (k < WPW) { if (lw) dma_w1(lw_stage, lw_c, lw_tg, k); }
+                else if (k >= 3 && k - 3 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) dma_strip1(ls_c, 2 * (k - 3) + ls_part, soff); }
                 if (k >= 2 && k - 2 < (STRIP_MAX_SLOTS + 1) / 2) { if (ls) soff = strip_off(2 * (k - 2) + ls_part); }   // for the next group
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll

@@ -5,9 +5,8 @@
 #include "kernels.h"
 namespace vpe {
 hipError_t launch_gemm_dma_bf16(int bn, const GemmArgs& a, int amode, hipStream_t s);
-bool conv_strip_applies(const GemmArgs& a);
-int64_t conv_strip_tiles(const GemmArgs& a);
-hipError_t launch_conv_strip_bf16(const GemmArgs& a, hipStream_t s);
+int conv_strip_shape(const GemmArgs& a, bool any_size, int64_t* tiles);
+hipError_t launch_conv_strip_bf16(int shape, const GemmArgs& a, hipStream_t s);
 
 namespace {
 // Candidate tilings: tile, workgroups a CU holds at once, and the two coefficients of the time model
@@ -126,9 +125,9 @@ static hipError_t launch_picked(const GemmArgs& a, int amode, hipStream_t s, int
     // 256 CUs (measured on 272 x 360 x 256 -> 256, 256 tiles: 128 against 144 us for the generic 384 x 256 kernel on the
     // same box; with several rounds -- 4 x 296 x 296: 477 against 443 us -- the generic kernels stay ahead).
     // VPE_GEMM_TILE=9 forces it wherever it applies, any other forced tile switches it off.
-    if (a.m_begin == 0 && amode == A_CONV3 && (forced == 9 || (forced == 0 && !g_no_strip)) && conv_strip_applies(a) && a.epi != EPI_SWIGLU) {
-        const int64_t t = conv_strip_tiles(a);
-        if (forced == 9 || (t > 192 && t <= 256)) return launch_conv_strip_bf16(a, s);
+    if (a.m_begin == 0 && amode == A_CONV3 && (forced == 9 || (forced == 0 && !g_no_strip)) && a.epi != EPI_SWIGLU) {
+        const int shape = conv_strip_shape(a, forced == 9, nullptr);
+        if (shape) return launch_conv_strip_bf16(shape, a, s);
     }
     if ((forced == 384 || forced == 256 || forced == 128 || forced == 65) && fits) best = forced;
     if (forced == 4) best = a.epi == EPI_SWIGLU ? 2 : 4;

@@ -214,12 +214,15 @@ def test_direct_to_lds_gemm_variant(tile, monkeypatch):
     check_all(spec, 103, 203)
 
 
-def test_strip_convolution_kernel(monkeypatch):
-    # the 3x3 convolution that forms its nine taps from one input strip in LDS, forced for every convolution it can
-    # take (256 output channels per tile): detection towers reading token rows of two images with register tokens in
-    # between, the depth head's four fusion stages on 11x15 ... 88x120 grids (tiles that span several image rows,
-    # both images and the end of the tensor; taps masked at every edge), the last with the 1-channel projection
+@pytest.mark.parametrize("shape", ["1", "2"])
+def test_strip_convolution_kernel(shape, monkeypatch):
+    # the 3x3 convolution that forms its nine taps from one input strip in LDS, in both of its tile shapes (1: 384 x 256,
+    # 2: 768 x 128), forced for every convolution it can take (whole tiles of output channels): detection towers reading
+    # token rows of two images with register tokens in between, the depth head's four fusion stages on 11x15 ... 88x120
+    # grids (tiles that span several image rows, both images and the end of the tensor; taps masked at every edge), the
+    # last with the 1-channel projection
     monkeypatch.setenv("VPE_GEMM_TILE", "9")
+    monkeypatch.setenv("VPE_STRIP_SHAPE", shape)
     spec = vi.ModelSpec("strip_conv", dtype="bf16", **{**MEDIUM, "head_ch": 256, "batch": 2, "registers": 4})
     check_all(spec, 108, 208)
     # one row of patches (every pixel on the top and bottom edge) and a single patch
