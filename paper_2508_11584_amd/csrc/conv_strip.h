@@ -81,26 +81,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     // a step's 3750 clocks, and there are no seven registers to keep the offsets in.
     const int nslots = sp_rows / 32;
     int* const s_tab = reinterpret_cast<int*>(s_w + 3 * WSTAGE) + lane;        // [nslots][64]
-    {
-        const int qbase = m0 - Wp - 1 + (lane >> 1);          // lane l: row l / 2 of the instruction's 32, physical half l % 2
-        const int lhalf = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;   // ... which holds this logical half (rows 8..15, 24..31 exchanged)
-        const float inv_wp = 1.0f / (float)Wp, inv_hp = 1.0f / (float)Hp;
-        for (int slot = wave; slot < nslots; slot += NW) {
-            const int q = qbase + 32 * slot;
-            const int qq = q < 0 ? 0 : q;
-            int line = (int)((float)qq * inv_wp);            // qq / Wp, put right below (the product may be off by one)
-            line += (line + 1) * Wp <= qq;
-            line -= line * Wp > qq;
-            const int x = qq - line * Wp;
-            int img = (int)((float)line * inv_hp);
-            img += (img + 1) * Hp <= line;
-            img -= img * Hp > line;
-            const int y = line - img * Hp - 1;
-            const bool pixel = q >= 0 && x < p.cW && y >= 0 && img < images;
-            const int64_t row = (int64_t)img * p.a_istride + p.a_off + y * p.cW + x;
-            s_tab[slot * 64] = pixel ? (int)(row * p.lda * 2 + lhalf) : -1;
-        }
-    }
     // weight rows: instruction q of a step (tap q / RB, row block q % RB) is issued by wave q % 8; lane l fetches row
     // n0 + 32 (q % RB) + l / 2, the same exchange of halves
     const int woff = (int)(((int64_t)(n0 + (lane >> 1)) * p.K) * 2 + (((lane & 1) ^ ((lane >> 4) & 1)) * 16));
@@ -199,10 +179,30 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC * WGM * WGN / 4) void conv_stri
     // have, and everyone is done with step s - 1), then the loads of step s + 2's weights (into the stage step s - 1
     // used) and, in the first two steps of a chunk, half of the next chunk's strip (into the stage chunk c - 1 used).
     const int NC = C / STRIP_KC, NS = 3 * NC;
+    dma_w(0, 0, 0);                                      // (the first weights are on their way while the offsets are worked out)
+    dma_w(1, 0, 1);
+    {
+        const int qbase = m0 - Wp - 1 + (lane >> 1);          // lane l: row l / 2 of the instruction's 32, physical half l % 2
+        const int lhalf = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;   // ... which holds this logical half (rows 8..15, 24..31 exchanged)
+        const float inv_wp = 1.0f / (float)Wp, inv_hp = 1.0f / (float)Hp;
+        for (int slot = wave; slot < nslots; slot += NW) {
+            const int q = qbase + 32 * slot;
+            const int qq = q < 0 ? 0 : q;
+            int line = (int)((float)qq * inv_wp);            // qq / Wp, put right below (the product may be off by one)
+            line += (line + 1) * Wp <= qq;
+            line -= line * Wp > qq;
+            const int x = qq - line * Wp;
+            int img = (int)((float)line * inv_hp);
+            img += (img + 1) * Hp <= line;
+            img -= img * Hp > line;
+            const int y = line - img * Hp - 1;
+            const bool pixel = q >= 0 && x < p.cW && y >= 0 && img < images;
+            const int64_t row = (int64_t)img * p.a_istride + p.a_off + y * p.cW + x;
+            s_tab[slot * 64] = pixel ? (int)(row * p.lda * 2 + lhalf) : -1;
+        }
+    }
     dma_strip(0, 0);
     dma_strip(0, 1);
-    dma_w(0, 0, 0);
-    dma_w(1, 0, 1);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
 #pragma unroll
