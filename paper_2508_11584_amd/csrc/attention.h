@@ -29,6 +29,8 @@ struct AttnArgs {
     int B, N, npad, dim, heads;
     float scale_log2e;   // (1 / sqrt(64)) * log2(e)
     int pad;             // readable rows of qk / elements of vt past their ends
+    int shared_gpu;      // the launch runs beside other streams' kernels (several encoder lanes): prefer a shape that
+                         // leaves room on its CUs over the fastest one on an empty GPU
 };
 
 // Exchange between the two halves of a wave without going through LDS (v_permlane32_swap): both operands are the

@@ -54,8 +54,12 @@ hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {
     // query waves sharing each key tile and no merge.  Wider workgroups (eight query waves, or two query blocks per
     // wave) halve the L2 -> LDS traffic and are slower all the same; narrower ones (two waves) double it and are
     // slower too.
+    // Beside other streams' kernels the footprint counts for more than the time alone: (1,2,4) holds a CU's LDS
+    // (128 KB) for itself, (1,2,2) takes half and four waves.  ViT-S 476x630, three encoder lanes + heads: 1968 against
+    // 1888 frames/s with (1,2,2), although the kernel alone takes 14.3 against 13.0 us (and frame latency 1.069
+    // against 1.058 ms); even (1,4,1) -- 32 KB, 22.5 us alone -- gives 1941.
     const int64_t qblocks = (int64_t)cdiv(a.N, 32) * a.B * a.heads;
-    int variant = qblocks >= 2048 ? 141 : qblocks >= 400 ? 122 : 124;
+    int variant = qblocks >= 2048 ? 141 : (qblocks >= 400 || a.shared_gpu) ? 122 : 124;
     if (forced) variant = forced;
     return dtype ? launch_variant<bf16>(variant, a, s) : launch_variant<float>(forced == 141 || qblocks >= 2048 ? 141 : 114, a, s);
 }

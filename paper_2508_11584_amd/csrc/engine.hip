@@ -708,7 +708,7 @@ int enqueue_encoder_body(vpe_engine& e, int slot, int lane, hipStream_t s) {
             HIPCHK(&e, launch_gemm(dt, a, A_PLAIN, s));
         }
         {
-            AttnArgs a{L.qk, L.vt, L.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f, ATTN_PAD};
+            AttnArgs a{L.qk, L.vt, L.att, e.B, e.N, e.npad, D, e.nh, 0.125f * 1.4426950408889634f, ATTN_PAD, e.lanes > 1};
             HIPCHK(&e, launch_attention(dt, a, s));
         }
         {
@@ -1415,7 +1415,7 @@ int vpe_time_kernel(vpe_engine* e, int which, int reps, float* ms_per_launch, do
                 a.epi = EPI_QKV; a.out = L0.qk; a.ldo = 2 * D; a.out2 = L0.vt; a.ntok = e->N; a.npad = e->npad; a.dim = D;
                 HIPCHK(e, launch_gemm(dt, a, A_PLAIN, s));
             } else if (which == 1) {
-                AttnArgs a{L0.qk, L0.vt, L0.att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f, ATTN_PAD};
+                AttnArgs a{L0.qk, L0.vt, L0.att, e->B, e->N, e->npad, D, e->nh, 0.125f * 1.4426950408889634f, ATTN_PAD, e->lanes > 1};
                 HIPCHK(e, launch_attention(dt, a, s));
             } else if (which == 5 || which == 7) {
                 // out-projection / fc2 of block 0 with the LayerScale residual epilogue (the residual stream of lane 0
