@@ -137,6 +137,28 @@ __device__ __forceinline__ float gelu_erf(float v) {
     return 0.5f * v * (1.0f + copysignf(erf_abs, v));
 }
 
+// The same function for results that are rounded to bf16: erf(x) = x P(x^2) on |x| <= 3, P of degree 9 (least-squares fit
+// at Chebyshev nodes, |error of erf| <= 1.9e-5; beyond 3 the value at 3, 0.99998, clamped to 1), Horner in fp32: no
+// reciprocal, no exponential (two quarter-rate instructions of the form above), 14 instead of 23 issue slots.  The
+// result differs from the exact form by at most 1e-5 |v| -- 1/400 of a bf16 rounding step.
+__device__ __forceinline__ float gelu_erf_bf16(float v) {
+    const float x = fminf(fabsf(v) * 0.70710678118654752f, 3.0f);
+    const float t = x * x;
+    float p = fmaf(-4.469939086e-09f, t, 2.302152922e-07f);
+    p = fmaf(p, t, -5.322654488e-06f);
+    p = fmaf(p, t, 7.394709974e-05f);
+    p = fmaf(p, t, -7.009955007e-04f);
+    p = fmaf(p, t, 4.897189327e-03f);
+    p = fmaf(p, t, -2.645343542e-02f);
+    p = fmaf(p, t, 1.125671491e-01f);
+    p = fmaf(p, t, -3.760564327e-01f);
+    p = fmaf(p, t, 1.128376126e+00f);
+    const float erf_abs = fminf(p * x, 1.0f);
+    return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+}
+template <typename T>
+__device__ __forceinline__ float gelu_for(float v) { return sizeof(T) == 2 ? gelu_erf_bf16(v) : gelu_erf(v); }
+
 // Spread consecutive block ids (which the hardware deals round-robin to the 8 XCDs) so that
 // each XCD works on one contiguous range of tiles and its L2 sees neighbouring A/W panels.
 __device__ __forceinline__ int xcd_contiguous(int bid, int nb) {
@@ -192,7 +214,7 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& p, int r, int c, 
             for (int i = 0; i < 8; ++i) v[i] = fmaxf(v[i], 0.0f);
         } else if (p.act == ACT_GELU) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = gelu_erf(v[i]);
+            for (int i = 0; i < 8; ++i) v[i] = gelu_for<T>(v[i]);
         }
         const int64_t orow = (int64_t)(r / p.o_rpi) * p.o_istride + p.o_off + r % p.o_rpi;
         if (p.add1) {

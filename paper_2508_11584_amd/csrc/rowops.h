@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void activation_kernel(T* __restrict__ h, int6
         for (int i = 0; i < 8; ++i) v[i] = v[i] / (1.0f + __expf(-v[i])) * w[i];
     } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = gelu_erf(v[i]);
+        for (int i = 0; i < 8; ++i) v[i] = gelu_for<T>(v[i]);
     }
     store8(p, v);
 }
