@@ -158,6 +158,13 @@ __device__ __forceinline__ float gelu_erf_bf16(float v) {
 }
 template <typename T>
 __device__ __forceinline__ float gelu_for(float v) { return sizeof(T) == 2 ? gelu_erf_bf16(v) : gelu_erf(v); }
+// SiLU(a) * b.  For results rounded to bf16 the quotient is one v_rcp_f32 (1 ulp) and a product instead of the
+// correctly rounded division sequence (about ten instructions).
+template <typename T>
+__device__ __forceinline__ float swiglu_for(float a, float b) {
+    const float d = 1.0f + __expf(-a);
+    return sizeof(T) == 2 ? a * __builtin_amdgcn_rcpf(d) * b : a / d * b;
+}
 
 // Spread consecutive block ids (which the hardware deals round-robin to the 8 XCDs) so that
 // each XCD works on one contiguous range of tiles and its L2 sees neighbouring A/W panels.
@@ -467,7 +474,7 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs& p, f32x16 (&acc)[
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float a = src[i] + p.bias[ca + i], b = src[32 + i] + p.bias[ca + 32 + i];
-                    h[i] = a / (1.0f + __expf(-a)) * b;
+                    h[i] = swiglu_for<T>(a, b);
                 }
                 store8(out + (int64_t)r * p.ldo + oc, h);
             }

@@ -128,7 +128,7 @@ __device__ __forceinline__ void wave_tile_epilogue(const GemmArgs& p, f32x16 (&a
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const float a = src[e] + p.bias[ca + e], b = src[32 + e] + p.bias[ca + 32 + e];
-                        h[e] = a / (1.0f + __expf(-a)) * b;
+                        h[e] = swiglu_for<T>(a, b);
                     }
                     store8(out + (int64_t)r * p.ldo + (ca >> 6) * 32 + j0, h);
                 }

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void activation_kernel(T* __restrict__ h, int6
 #pragma unroll
         for (int i = 0; i < 8; ++i) w[i] = to_f32(p[cols / 2 + i]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = v[i] / (1.0f + __expf(-v[i])) * w[i];
+        for (int i = 0; i < 8; ++i) v[i] = swiglu_for<T>(v[i], w[i]);
     } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = gelu_for<T>(v[i]);
