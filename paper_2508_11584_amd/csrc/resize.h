@@ -128,20 +128,52 @@ __device__ __forceinline__ void add_block(const T* __restrict__ src, int b, int 
         }
 }
 
+// The r map is enlarged by exactly 2: output rows 2 i and 2 i + 1 are 1/4 in[i - 1] + 3/4 in[i] and 3/4 in[i] + 1/4 in[i + 1]
+// (indices clamped to the map, which is what clamping the sample position gives), likewise along x -- fixed weights and
+// fixed roles of the three source rows and columns: no tap arithmetic, no selects.
+template <typename T>
+__device__ __forceinline__ void add_block_x2(const T* __restrict__ src, int b, int h, int w, int C, int cg, int i, int j,
+                                             float (&acc)[2][2][Elem<T>::CE]) {
+    constexpr int CE = Elem<T>::CE;
+    const T* base = src + (int64_t)b * h * w * C + cg * CE;
+    const int rows[3] = {i > 0 ? i - 1 : 0, i, i + 1 < h ? i + 1 : h - 1};
+    const int ca = (j > 0 ? j - 1 : 0) * C, cb = j * C, cc = (j + 1 < w ? j + 1 : w - 1) * C;
+    float hz[3][2][CE];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const T* rp = base + rows[k] * w * C;
+        float va[CE], vb[CE], vc[CE];
+        Vec<T, CE>::load(rp + ca, va);
+        Vec<T, CE>::load(rp + cb, vb);
+        Vec<T, CE>::load(rp + cc, vc);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+            hz[k][0][e] = fmaf(0.75f, vb[e], 0.25f * va[e]);
+            hz[k][1][e] = fmaf(0.75f, vb[e], 0.25f * vc[e]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+            acc[0][k][e] += fmaf(0.75f, hz[1][k][e], 0.25f * hz[0][k][e]);
+            acc[1][k][e] += fmaf(0.75f, hz[1][k][e], 0.25f * hz[2][k][e]);
+        }
+}
+
 // PSHARED: the p map is enlarged by a multiple of 4 in both directions (decided by the launcher).
+// Grid: x over (block column, channel group) pairs, y = block row, z = image: the row, the image and the row's taps
+// are the same for a whole workgroup, and a thread's only division is by the number of channel groups.
 template <typename T, bool PSHARED>
 __global__ __launch_bounds__(256) void fuse_upsample_kernel(const T* __restrict__ p, int gh, int gw,
                                                             const T* __restrict__ r, int B, int Hs, int Ws,
                                                             int C, T* __restrict__ z) {
     constexpr int CE = Elem<T>::CE;
     const int groups = C / CE, bw = Ws / 2, bh = Hs / 2;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)B * bh * bw * groups) return;
-    const int cg = (int)(idx % groups);
-    int64_t blk = idx / groups;
-    const int x0 = 2 * (int)(blk % bw);
-    blk /= bw;
-    const int y0 = 2 * (int)(blk % bh), b = (int)(blk / bh);
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= bw * groups) return;
+    const int xb = t / groups, cg = t - xb * groups;
+    const int x0 = 2 * xb, yb = blockIdx.y, y0 = 2 * yb, b = blockIdx.z;
     float acc[2][2][CE];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -150,7 +182,7 @@ __global__ __launch_bounds__(256) void fuse_upsample_kernel(const T* __restrict_
 #pragma unroll
             for (int e = 0; e < CE; ++e) acc[i][k][e] = 0.0f;
     add_block<T, PSHARED>(p, b, gh, gw, C, cg, y0, x0, Hs, Ws, acc);
-    if (r) add_block<T, false>(r, b, bh, bw, C, cg, y0, x0, Hs, Ws, acc);
+    if (r) add_block_x2<T>(r, b, bh, bw, C, cg, yb, xb, acc);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll

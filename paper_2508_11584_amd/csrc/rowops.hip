@@ -64,8 +64,9 @@ hipError_t launch_fuse_upsample(int dtype, const void* p, int gh, int gw, const 
     // is a multiple of 4: a sample boundary lies between outputs y and y + 1 only if f (2 j + 1) = 2 y + 2,
     // and for even y the right side is 2 mod 4
     const bool shared = Hs % (4 * gh) == 0 && Ws % (4 * gw) == 0;
-    const int64_t n = (int64_t)B * (Hs / 2) * (Ws / 2) * (C / (dtype ? 8 : 4));
-    const dim3 grid(blocks_for(n, 256)), block(256);
+    const int64_t per_row = (int64_t)(Ws / 2) * (C / (dtype ? 8 : 4));
+    if (per_row >= (int64_t(1) << 31) || Hs / 2 > 65535 || B > 65535) return hipErrorInvalidValue;   // grid y, z limits
+    const dim3 grid(blocks_for(per_row, 256), Hs / 2, B), block(256);
     if (dtype) {
         if (shared) hipLaunchKernelGGL((fuse_upsample_kernel<bf16, true>), grid, block, 0, s, (const bf16*)p, gh, gw, (const bf16*)r, B, Hs, Ws, C, (bf16*)z);
         else hipLaunchKernelGGL((fuse_upsample_kernel<bf16, false>), grid, block, 0, s, (const bf16*)p, gh, gw, (const bf16*)r, B, Hs, Ws, C, (bf16*)z);
