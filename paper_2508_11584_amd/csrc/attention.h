@@ -134,8 +134,14 @@ template <> struct AttnMma<bf16> {
             o0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st & 1][0], b[st & 1], o0, 0, 0, 0);
             o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st & 1][1], b[st & 1], o1, 0, 0, 0);
             if (LM) l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, b[st & 1], l, 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
             if (st < 3) b[(st + 1) & 1] = probs(st + 1);
+            // one MFMA, then a third of the next step's exponentials and conversions, three times
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x402, 8, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 };
